@@ -1,0 +1,384 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix about the Flag
+Aggregator, checked without reference to the oracle's own formulas.
+
+Each test names the statement of the paper it rests on.  None of them needs a GPU.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import (as_f64_matrix, decode_bf16, fa_literal, fa_scaled,
+                    projector_difference, tsqr_r)
+
+
+def _rand(n, p, seed, col_scales=True):
+    rng = np.random.default_rng(seed)
+    G = rng.standard_normal((n, p))
+    if col_scales:
+        G = G * rng.uniform(0.3, 4.0, p)[None, :]
+    return G
+
+
+def _principal_cosines(Y1, Y2):
+    return np.linalg.svd(Y1.T @ Y2, compute_uv=False)
+
+
+# Independent statement of the FA objective (Eq. 5 + Sec. 2.3 option (2)), with explicit
+# loops over workers and over ordered pairs i != j.
+def eq5_objective(Y, G, lam, pair_factor=None):
+    n, p = G.shape
+    total = 0.0
+    for i in range(p):
+        g = G[:, i]
+        z = Y.T @ g
+        total += math.sqrt(max(1.0 - float(z @ z) / float(g @ g), 0.0))
+    if lam > 0:
+        fac = lam / (p - 1) if pair_factor is None else pair_factor
+        for i in range(p):
+            for j in range(p):
+                if i == j:
+                    continue
+                d = G[:, i] - G[:, j]
+                z = Y.T @ d
+                total += fac * math.sqrt(max(1.0 - float(z @ z) / float(d @ d), 0.0))
+    return total
+
+
+def _retract(Y, D, t):
+    Q, R = np.linalg.qr(Y + t * D)
+    return Q * np.sign(np.diag(R))[None, :]
+
+
+# --------------------------------------------------------------------------- PCA pin
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("m", [1, 3, 5])
+def test_first_solve_is_pca(seed, m):
+    """Appendix E.2: one FA iteration with uniform weights is PCA of the (normalised)
+    gradient matrix.  Reference route: eigenvectors of the n x n matrix sum_i g~_i g~_i^T."""
+    G = _rand(30, 7, seed)
+    res = fa_literal(G, m, 0.0, 1, 0.0)
+    Gn = G / np.linalg.norm(G, axis=0)[None, :]
+    evals, evecs = np.linalg.eigh(Gn @ Gn.T)
+    top = evecs[:, np.argsort(-evals)[:m]]
+    cos = _principal_cosines(top, res["Y"])
+    assert np.all(np.abs(cos - 1.0) < 1e-10)
+    # the output is the column average of the reconstruction Y Y^T G (Sec. 2.1, Alg. 1)
+    recon = top @ (top.T @ G)
+    assert np.allclose(res["out"], recon.mean(axis=1), rtol=0, atol=1e-10 * np.abs(G).max())
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.7])
+def test_feasibility_and_ratio_range(lam):
+    """Eq. 5 constraint Y^T Y = I; Sec. 2.1/2.2: explained variances lie in [0, 1]."""
+    G = _rand(25, 9, 3)
+    res = fa_literal(G, 4, lam, 7, 0.0)
+    Y = res["Y"]
+    assert np.abs(Y.T @ Y - np.eye(4)).max() < 1e-12
+    assert np.all(res["v"] >= 0) and np.all(res["v"] <= 1 + 1e-12)
+    assert np.all(res["u"] >= 0) and np.all(res["u"] <= 1 + 1e-12)
+    # the ratios really are ||Y^T g||^2 / ||g||^2
+    for i in range(9):
+        g = G[:, i]
+        assert abs(res["v"][i] - np.sum((Y.T @ g) ** 2) / (g @ g)) < 1e-12
+
+
+@pytest.mark.parametrize("lam", [0.0, 1.0, 10.0])
+@pytest.mark.parametrize("iters", [1, 6])
+def test_full_subspace_gives_the_mean(lam, iters):
+    """Sec. 2.1: g in span(Y) is fully explained and Y Y^T G reconstructs G, so with
+    m >= rank(G) the aggregate is the plain mean of the gradients and all ratios are 1."""
+    G = _rand(20, 6, 4)
+    res = fa_literal(G, 6, lam, iters, 0.0)
+    assert np.allclose(res["out"], G.mean(axis=1), atol=1e-12 * np.abs(G).max() * 10)
+    assert np.allclose(res["v"], 1.0, atol=1e-12)
+    # rank-deficient G (rank 3) with m = 3 < p
+    rng = np.random.default_rng(9)
+    B = rng.standard_normal((20, 3))
+    G3 = B @ rng.standard_normal((3, 6))
+    res = fa_literal(G3, 3, lam, iters, 0.0)
+    assert np.allclose(res["out"], G3.mean(axis=1), atol=1e-11 * np.abs(G3).max())
+    assert np.allclose(res["v"], 1.0, atol=1e-11)
+
+
+@pytest.mark.parametrize("lam", [0.0, 1.0])
+@pytest.mark.parametrize("m", [1, 3])
+def test_identical_gradients(lam, m):
+    """All workers send the same g: the aggregate must be g (rank 1; with lam > 0 every
+    pairwise distance D_ij is zero and those terms drop out)."""
+    g = np.random.default_rng(5).standard_normal(17)
+    G = np.repeat(g[:, None], 5, axis=1)
+    res = fa_literal(G, m, lam, 4, 0.0)
+    assert np.allclose(res["out"], g, atol=1e-12)
+    res_s = fa_scaled(np.ascontiguousarray(G.T), m, lam, 4, 0.0)
+    assert np.allclose(res_s["out"], g, atol=1e-12)
+
+
+@pytest.mark.parametrize("theta_deg", [20.0, 60.0, 85.0])
+def test_two_workers_bisector(theta_deg):
+    """p = 2, m = 1, lam = 0: PCA of two unit directions at an acute angle is their
+    bisector; by symmetry the two ratios (hence weights) stay equal, so every IRLS solve
+    returns the bisector again.  Ratios equal cos^2(theta/2)."""
+    th = math.radians(theta_deg)
+    n = 6
+    rng = np.random.default_rng(11)
+    Q, _ = np.linalg.qr(rng.standard_normal((n, 2)))
+    a = Q[:, 0]
+    b = math.cos(th) * Q[:, 0] + math.sin(th) * Q[:, 1]
+    G = np.stack([2.5 * a, 0.4 * b], axis=1)          # different norms
+    res = fa_literal(G, 1, 0.0, 9, 0.0)
+    y = (a + b) / np.linalg.norm(a + b)
+    assert abs(abs(float(y @ res["Y"][:, 0])) - 1.0) < 1e-12
+    assert np.allclose(res["v"], math.cos(th / 2) ** 2, atol=1e-12)
+    expect = 0.5 * y * float(y @ (G[:, 0] + G[:, 1]))
+    assert np.allclose(res["out"], expect, atol=1e-12)
+    # objective trace: 2 sin(theta/2) at every solve
+    assert np.allclose(res["objective"], 2 * math.sin(th / 2), atol=1e-10)
+
+
+def test_orthogonal_columns_total_tie():
+    """Mutually orthogonal gradients, lam = 0: the normalised Gram matrix is the identity
+    and every m-dimensional subspace of span(G) is a valid first solve.  What is unique:
+    Y^T Y = I, Y in span(G), and sum_i v_i = m."""
+    rng = np.random.default_rng(2)
+    Q, _ = np.linalg.qr(rng.standard_normal((15, 6)))
+    G = Q * rng.uniform(0.5, 2.0, 6)[None, :]
+    res = fa_literal(G, 3, 0.0, 1, 0.0)
+    Y = res["Y"]
+    assert np.abs(Y.T @ Y - np.eye(3)).max() < 1e-12
+    assert np.linalg.norm(Y - Q @ (Q.T @ Y)) < 1e-12
+    assert abs(res["v"].sum() - 3.0) < 1e-12
+
+
+# ----------------------------------------------------------------- IRLS as MM procedure
+@pytest.mark.parametrize("seed", range(5))
+@pytest.mark.parametrize("lam", [0.0, 1.0])
+def test_objective_monotone_while_unclamped(seed, lam):
+    """Appendix E.2 / Sec. 2.3: the re-weighting is a convergent procedure; as a
+    majorise-minimise scheme for Eq. 5 the objective cannot rise (weight floor inactive)."""
+    G = _rand(14, 8, 20 + seed)
+    p, delta = 8, 1e-6
+    off = ~np.eye(p, dtype=bool)
+    prev = None
+    checked = 0
+    for k in range(1, 31):
+        res = fa_literal(G, 2, lam, k, 0.0, delta=delta)
+        obj = res["objective"][-1]
+        # the recorded objective equals Eq. 5 evaluated independently at this Y
+        assert abs(obj - eq5_objective(res["Y"], G, lam)) < 1e-7
+        if prev is not None and prev[1] > delta:      # floor was inactive for this step
+            assert obj <= prev[0] + 1e-10
+            checked += 1
+        min_rho = (1 - res["v"]).min()
+        if lam > 0:
+            min_rho = min(min_rho, (1 - res["u"][off]).min())
+        prev = (obj, min_rho)
+    assert checked >= 3
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_converged_point_is_stationary_for_eq5(seed):
+    """The fixed point of the IRLS must be a stationary point of Eq. 5 itself (objective
+    written out independently above, ordered pairs, factor lam/(p-1)).  This pins the
+    weight exponent (-1/2 on the residual), the pairwise normalisation by D_ij and the
+    ordered-pair factor: with any of them changed the fixed point moves and the
+    derivative below is O(0.1)."""
+    rng = np.random.default_rng(seed)
+    n, p, m, lam = 12, 8, 2, 1.0
+    G = rng.standard_normal((n, p)) * rng.uniform(0.5, 3, p)[None, :]
+    res = fa_literal(G, m, lam, 400, 0.0)
+    Y = res["Y"]
+    off = ~np.eye(p, dtype=bool)
+    assert min((1 - res["v"]).min(), (1 - res["u"][off]).min()) > 1e-3   # interior point
+    worst = 0.0
+    worst_wrong_factor = 0.0
+    h = 1e-5
+    for _ in range(6):
+        D = rng.standard_normal((n, m))
+        D -= Y @ (Y.T @ D)
+        D /= np.linalg.norm(D)
+        dd = (eq5_objective(_retract(Y, D, h), G, lam)
+              - eq5_objective(_retract(Y, D, -h), G, lam)) / (2 * h)
+        worst = max(worst, abs(dd))
+        fac = 0.5 * lam / (p - 1)        # what an unordered pair sum would give
+        dw = (eq5_objective(_retract(Y, D, h), G, lam, fac)
+              - eq5_objective(_retract(Y, D, -h), G, lam, fac)) / (2 * h)
+        worst_wrong_factor = max(worst_wrong_factor, abs(dw))
+    assert worst < 1e-6
+    assert worst_wrong_factor > 1e-3      # the check has power
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("lam", [0.0, 1.0])
+def test_converged_point_is_a_local_minimum_by_sampling(seed, lam):
+    """Brute force: no nearby feasible Y has a lower Eq. 5 value than the converged one
+    (also at 'vertex' solutions where some gradients are explained exactly)."""
+    rng = np.random.default_rng(100 + seed)
+    n, p, m = 9, 7, 2
+    G = rng.standard_normal((n, p)) * rng.uniform(0.5, 3, p)[None, :]
+    # a small weight floor, so that the fixed point sits within ~sqrt(delta) of the vertex
+    res = fa_literal(G, m, lam, 500, 0.0, delta=1e-12)
+    Y = res["Y"]
+    a0 = eq5_objective(Y, G, lam)
+    for _ in range(300):
+        D = rng.standard_normal((n, m))
+        t = 10 ** rng.uniform(-4, -1.5)
+        assert eq5_objective(_retract(Y, D, t), G, lam) >= a0 - 2e-5
+
+
+def test_iters_and_tol_semantics():
+    """Sec. 3 'Implementation Details': stop at a small error or after a fixed number of
+    flag-mean solves.  iters counts solves; tol compares successive objective values."""
+    G = _rand(16, 7, 7)
+    full = fa_literal(G, 3, 1.0, 30, 0.0)
+    assert full["iters_done"] == 30
+    tol = 1e-3
+    early = fa_literal(G, 3, 1.0, 30, tol)
+    obj = np.array(full["objective"])
+    k_stop = next(k for k in range(1, 30) if abs(obj[k - 1] - obj[k]) < tol)
+    assert early["iters_done"] == k_stop + 1
+    ref = fa_literal(G, 3, 1.0, k_stop + 1, 0.0)
+    assert np.allclose(early["out"], ref["out"], atol=1e-14)
+    # the test needs two objective values: a huge tol stops right after the second solve
+    assert fa_literal(G, 3, 1.0, 30, 1e9)["iters_done"] == 2
+    assert fa_literal(G, 3, 1.0, 1, 1e9)["iters_done"] == 1
+
+
+def test_weight_floor_is_applied():
+    """Readings: weights are max(rho, delta)^(-1/2); an exactly explained worker gets
+    delta^(-1/2)."""
+    G = _rand(10, 4, 8)
+    res = fa_literal(G, 2, 0.0, 60, 0.0, delta=1e-6)
+    assert res["w"].max() <= 1e3 * (1 + 1e-12)
+    rho = 1 - res["v"]
+    expect = np.maximum(rho, 1e-6) ** -0.5
+    assert np.allclose(res["w"], expect, rtol=1e-6)
+
+
+# ------------------------------------------------------------------------ metamorphic
+@pytest.mark.parametrize("lam", [0.0, 1.0])
+def test_permutation_scale_rotation(lam):
+    G = _rand(18, 7, 12)
+    m, iters = 3, 6
+    base = fa_literal(G, m, lam, iters, 0.0)
+    rng = np.random.default_rng(0)
+    perm = rng.permutation(7)
+    r = fa_literal(G[:, perm], m, lam, iters, 0.0)
+    assert np.allclose(r["out"], base["out"], atol=1e-10)
+    assert np.allclose(r["v"], base["v"][perm], atol=1e-10)
+    r = fa_literal(-3.5 * G, m, lam, iters, 0.0)
+    assert np.allclose(r["out"], -3.5 * base["out"], atol=1e-10)
+    Q, _ = np.linalg.qr(rng.standard_normal((18, 18)))
+    r = fa_literal(Q @ G, m, lam, iters, 0.0)
+    assert np.allclose(r["out"], Q @ base["out"], atol=1e-10)
+    # output lies in span(G) (Appendix D: Y Y^T G = G S_FA + ...)
+    coef, *_ = np.linalg.lstsq(G, base["out"], rcond=None)
+    assert np.linalg.norm(G @ coef - base["out"]) < 1e-10
+
+
+def test_column_rescaling_leaves_subspace_unchanged_at_lambda0():
+    """At lam = 0 only the normalised gradients enter Eq. 5, so positive per-column
+    rescaling leaves Y (and the ratios) unchanged."""
+    G = _rand(18, 7, 13)
+    a = fa_literal(G, 3, 0.0, 8, 0.0)
+    alpha = np.random.default_rng(1).uniform(0.1, 9.0, 7)
+    b = fa_literal(G * alpha[None, :], 3, 0.0, 8, 0.0)
+    assert np.all(np.abs(_principal_cosines(a["Y"], b["Y"]) - 1) < 1e-10)
+    assert np.allclose(a["v"], b["v"], atol=1e-10)
+
+
+def test_zero_column_is_a_dropped_worker():
+    """A zero gradient (a worker whose message was lost and zeroed at the server, Sec. 3
+    communication-loss experiment) has no direction: at lam = 0 the subspace is that of
+    the remaining workers and the aggregate scales by (p-1)/p."""
+    G = _rand(15, 6, 14)
+    Gz = np.concatenate([G[:, :2], np.zeros((15, 1)), G[:, 2:]], axis=1)
+    a = fa_literal(G, 2, 0.0, 5, 0.0)
+    b = fa_literal(Gz, 2, 0.0, 5, 0.0)
+    assert np.allclose(b["out"], a["out"] * 6 / 7, atol=1e-12)
+    assert b["w"][2] == 0.0 and b["v"][2] == 0.0
+    # with lam > 0 the call must still be finite
+    c = fa_literal(Gz, 2, 1.0, 5, 0.0)
+    assert np.all(np.isfinite(c["out"]))
+
+
+def test_lambda_large_pairs_dominate():
+    """Sec. 2.3: with lam = Theta(p) the pairwise terms dominate.  As lam grows the first
+    solve tends to PCA of the normalised pairwise differences alone."""
+    G = _rand(16, 6, 15)
+    p = 6
+    diffs = []
+    for i in range(p):
+        for j in range(p):
+            if i != j:
+                d = G[:, i] - G[:, j]
+                diffs.append(d / np.linalg.norm(d))
+    Dn = np.stack(diffs, axis=1)
+    evals, evecs = np.linalg.eigh(Dn @ Dn.T)
+    top = evecs[:, np.argsort(-evals)[:2]]
+    r = fa_literal(G, 2, 1e9, 1, 0.0)
+    assert np.all(np.abs(_principal_cosines(top, r["Y"]) - 1) < 1e-7)
+
+
+# -------------------------------------------------------------- scaled form == literal
+@pytest.mark.parametrize("lam", [0.0, 0.1, 1.0])
+@pytest.mark.parametrize("shape", [(200, 8, 4), (97, 5, 2), (64, 3, 3)])
+def test_scaled_matches_literal(lam, shape):
+    n, p, m = shape
+    G = _rand(n, p, n + p)
+    Gw = np.ascontiguousarray(G.T)
+    a = fa_literal(G, m, lam, 9, 0.0)
+    b = fa_scaled(Gw, m, lam, 9, 0.0, chunk_rows=37)
+    assert np.linalg.norm(a["out"] - b["out"]) <= 1e-11 * np.linalg.norm(a["out"])
+    assert np.allclose(a["v"], b["v"], atol=1e-11)
+    assert np.allclose(a["objective"], b["objective"], atol=1e-6)   # sqrt of 1e-16 noise at exact fits
+    # Y = G A reproduces the literal subspace
+    Yb = G @ b["A"]
+    assert np.abs(Yb.T @ Yb - np.eye(m)).max() < 1e-10
+    assert np.all(np.abs(_principal_cosines(a["Y"], Yb) - 1) < 1e-10)
+    K = G.T @ G
+    assert np.allclose(b["K"], K, atol=1e-10 * np.abs(K).max())
+    assert projector_difference(b["A"], b["A"], K) == 0.0
+
+
+def test_tsqr_is_an_isometry_with_duplicates_and_ragged_chunks():
+    rng = np.random.default_rng(3)
+    Gw = rng.standard_normal((5, 1003)).astype(np.float32)
+    Gw[3] = Gw[1]                                 # exact duplicate column
+    R = tsqr_r(Gw, chunk_rows=100)
+    G = as_f64_matrix(Gw)
+    assert np.allclose(R.T @ R, G.T @ G, atol=1e-9)
+    assert np.allclose(np.tril(R, -1), 0.0)
+    res = fa_scaled(Gw, 2, 1.0, 5, 0.0, chunk_rows=100)
+    lit = fa_literal(G, 2, 1.0, 5, 0.0)
+    assert np.linalg.norm(res["out"] - lit["out"]) <= 1e-10 * np.linalg.norm(lit["out"])
+
+
+def test_projector_difference_matches_dense():
+    rng = np.random.default_rng(4)
+    G = rng.standard_normal((30, 5))
+    A1 = rng.standard_normal((5, 2))
+    A2 = rng.standard_normal((5, 2))
+    P1 = (G @ A1) @ (G @ A1).T
+    P2 = (G @ A2) @ (G @ A2).T
+    assert abs(projector_difference(A1, A2, G.T @ G) - np.linalg.norm(P1 - P2)) < 1e-9
+
+
+def test_bf16_decode_known_patterns():
+    bits = np.array([0x3F80, 0xC000, 0x3FC0, 0x0000, 0x8000, 0x7F80], dtype=np.uint16)
+    vals = decode_bf16(bits)
+    assert vals.dtype == np.float32
+    assert vals[0] == 1.0 and vals[1] == -2.0 and vals[2] == 1.5
+    assert vals[3] == 0.0 and np.signbit(vals[4]) and np.isinf(vals[5])
+
+
+def test_argument_errors():
+    G = _rand(10, 4, 1)
+    with pytest.raises(ValueError):
+        fa_literal(G, 0, 0.0, 1, 0.0)
+    with pytest.raises(ValueError):
+        fa_literal(G, 5, 0.0, 1, 0.0)
+    with pytest.raises(ValueError):
+        fa_literal(G, 2, -1.0, 1, 0.0)
+    with pytest.raises(ValueError):
+        fa_literal(G, 2, 0.0, 0, 0.0)
