@@ -1,0 +1,150 @@
+/*
+ * fa.h -- C ABI of the Flag Aggregator hot path for AMD MI355X (gfx950).
+ *
+ * The library computes the parameter server's aggregation step of
+ * "Flag Aggregator" (arXiv 2302.05865): given p worker gradients g_1..g_p in R^n
+ * it finds an orthonormal Y (n x m) for the FA objective (Eq. 5 with the
+ * data-dependent regulariser, Sec. 2.3 option (2)) by iteratively re-weighted
+ * least squares (Alg. 1, step "IRLS"; Sec. 3 "Implementation Details") and
+ * returns d = (1/p) Y Y^T G 1 (Alg. 1, "Obtain gradient direction").
+ *
+ * Everything n-sized runs in hand-written HIP kernels on the stream given at
+ * creation.  All "device" pointers are plain HIP device addresses owned by the
+ * caller; the library retains none of them after the call has completed on the
+ * stream.  All "host" pointers are ordinary host memory.
+ *
+ * Storage of G ("worker-major"): gradient i is contiguous, element k of
+ * gradient i is at  G + (i*ldg + k) * elem_size,  ldg >= n.  G must be 16-byte
+ * aligned and ldg*elem_size a multiple of 16.  This is the paper's n x p
+ * matrix G (columns = workers, Sec. 2.1) stored column by column, i.e. the
+ * layout in which a parameter server receives p flat gradients (Alg. 1).
+ *
+ * Threading: a context is bound to one device and one stream and is not
+ * thread-safe; distinct contexts are independent.
+ */
+#ifndef FA_H_
+#define FA_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FA_P_MAX 64        /* largest number of workers p */
+#define FA_ITERS_MAX 256   /* largest IRLS budget (length of the objective trace) */
+
+typedef struct fa_ctx fa_ctx; /* opaque, library-owned */
+
+typedef enum {
+  FA_OK = 0,
+  FA_ERR_ARG = 1,        /* bad argument; nothing was enqueued */
+  FA_ERR_ALLOC = 2,      /* device/host allocation failed */
+  FA_ERR_DEVICE = 3,     /* a HIP call failed */
+  FA_ERR_NONFINITE = 4,  /* G holds NaN/Inf (detected on device from G^T G); out is NaN */
+  FA_ERR_ZERO_INPUT = 5  /* every gradient is zero; out is zero */
+} fa_status;
+
+typedef enum { FA_F32 = 0, FA_BF16 = 1 } fa_dtype; /* storage type of G */
+
+typedef struct {
+  int64_t n_max;      /* largest n this context will see (sizes the workspace) */
+  int p_max;          /* largest p, 1..FA_P_MAX */
+  int dtype;          /* fa_dtype */
+  void* stream;       /* hipStream_t, borrowed; NULL = the default stream */
+  double clamp_delta; /* weight floor: w = max(residual, delta)^(-1/2); default 1e-6 */
+  double rank_tol;    /* eigenvalues of the normalised Gram below rank_tol*max are
+                         treated as zero; default 1e-12 */
+  double pair_tol;    /* a pair with D_ij^2 <= pair_tol*(|g_i|^2+|g_j|^2) counts as
+                         D_ij = 0 and its term is dropped; default 1e-12 */
+} fa_config;
+
+/* What the last fa_aggregate / fa_irls call on the context found (all fp64). */
+typedef struct {
+  int status;      /* fa_status of the device-side checks */
+  int p, m;        /* as passed */
+  int rank;        /* numerical rank of G */
+  int iters_done;  /* IRLS solves performed (<= iters; fewer if tol stopped it) */
+  int sweeps;      /* Jacobi sweeps spent in total (diagnostic) */
+  double eigengap; /* (mu_m - mu_{m+1}) / mu_1 of the last weighted PCA (inf if m >= rank) */
+  double objective[FA_ITERS_MAX]; /* Eq. 5 value after each solve */
+  double s[FA_P_MAX];  /* |g_i|^2 */
+  double v[FA_P_MAX];  /* explained variance |Y^T g_i|^2/|g_i|^2 of each worker (Sec. 2.1) */
+  double w[FA_P_MAX];  /* last IRLS weights of the data terms */
+  double c[FA_P_MAX];  /* out = sum_i c[i] g_i */
+  double A[FA_P_MAX * FA_P_MAX]; /* Y = G A; A[i*m + a], i < p, a < m (row-major p x m) */
+  double K[FA_P_MAX * FA_P_MAX]; /* G^T G, row-major p x p */
+} fa_info;
+
+/* Fill *cfg with the defaults (n_max = 0, p_max = FA_P_MAX, FA_F32, NULL stream,
+ * delta 1e-6, rank_tol 1e-12, pair_tol 1e-12). */
+void fa_default_config(fa_config* cfg);
+
+/* Allocate a context on the current HIP device: the per-block Gram partials
+ * (sized from n_max, p_max) and the small p x p workspace.  Returns FA_ERR_ARG for
+ * n_max < 1, p_max outside 1..FA_P_MAX or an unknown dtype. */
+fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx);
+
+/* Free everything the context owns (synchronises its stream first).  NULL is ignored. */
+void fa_destroy(fa_ctx* ctx);
+
+/* Replace the stream later calls are enqueued on (hipStream_t, borrowed). */
+fa_status fa_set_stream(fa_ctx* ctx, void* stream);
+
+/*
+ * The aggregation step (Eq. 5 solved by IRLS, then Alg. 1's direction):
+ *   G      device, worker-major (see above), p gradients of n elements, read twice
+ *   m      subspace dimension, 1 <= m <= p  (the paper uses ceil((p+1)/2))
+ *   lambda weight of the pairwise regulariser, >= 0 (ordered pairs, factor lambda/(p-1))
+ *   iters  number of weighted-PCA solves including the first, uniform one, 1..FA_ITERS_MAX
+ *   tol    stop when successive objective values differ by less than tol; 0 = never
+ *   out    device, n floats, caller-owned; receives d
+ * Asynchronous on the context's stream; allocates nothing.  Argument errors
+ * (including p > p_max, n > n_max, misaligned G/ldg, NULL pointers) return
+ * FA_ERR_ARG synchronously.  Data errors are found on the device and reported by
+ * fa_get_info: non-finite input fills out with NaN, all-zero input with zeros.
+ */
+fa_status fa_aggregate(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, int m,
+                       double lambda, int iters, double tol, float* out);
+
+/* Wait for the context's stream and copy the record of the last solve to host memory. */
+fa_status fa_get_info(fa_ctx* ctx, fa_info* host_out);
+
+/*
+ * Single steps of the path, exported so each kernel can be checked and timed alone.
+ *
+ * fa_gram: norms and pairwise inner products, K = G^T G (p x p, fp64; the quantities
+ *   |g_i|^2 of Sec. 2.1 and D_ij^2 = K_ii + K_jj - 2 K_ij of Sec. 2.3).  Streams G
+ *   once; synchronises and writes K row-major to host memory K_host (p*p doubles).
+ * fa_irls: the p x p part alone (normalisation, IRLS with the Jacobi eigensolver,
+ *   coefficients) from a Gram matrix given in host memory; results via fa_get_info.
+ * fa_combine: out = sum_i c[i] g_i with c (p doubles) given in host memory.  Streams G
+ *   once.  Asynchronous.
+ * fa_basis: Y = G A for the A of the last solve (Sec. 2.1's basis, materialised once):
+ *   Y is device memory, m columns of n floats, column a at Y + a*ldy, ldy >= n.
+ */
+fa_status fa_gram(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, double* K_host);
+fa_status fa_irls(fa_ctx* ctx, const double* K_host, int p, int m, double lambda, int iters,
+                  double tol);
+fa_status fa_combine(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n,
+                     const double* c_host, float* out);
+fa_status fa_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, float* Y,
+                   int64_t ldy);
+
+/*
+ * Per-kernel timing of fa_aggregate with HIP events on the context's stream.
+ * fa_set_profiling(ctx, 1) makes every later fa_aggregate record events around its
+ * kernels; fa_get_timings synchronises and returns the last call's durations in
+ * milliseconds: ms[0] Gram pass, ms[1] partial reduction, ms[2] p x p IRLS,
+ * ms[3] aggregate pass.
+ */
+fa_status fa_set_profiling(fa_ctx* ctx, int enabled);
+fa_status fa_get_timings(fa_ctx* ctx, float ms[4]);
+
+const char* fa_status_string(fa_status s);
+const char* fa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FA_H_ */

@@ -1,0 +1,248 @@
+// C ABI of the Flag Aggregator library (see include/fa.h): argument checking, workspace
+// ownership, and the order in which the kernels are enqueued.  No arithmetic happens here.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "fa.h"
+#include "fa_internal.h"
+
+struct fa_ctx {
+  int device;
+  hipStream_t stream;
+  fa_config cfg;
+  int num_cus;
+  int gram_max_blocks;
+  int combine_max_blocks;
+  double* partials;   // gram_max_blocks * NTP(p_max) * 256
+  double* Kd;         // FA_P_MAX^2
+  double* cd;         // FA_P_MAX
+  double* gws;        // 2 * FA_P_MAX * (FA_P_MAX + 1)
+  fa_info* info_d;
+  int has_solution;   // info_d holds an A from a completed fa_aggregate / fa_irls
+  int last_p, last_m;
+  int profiling;
+  hipEvent_t ev[5];
+  int ev_recorded;
+};
+
+static int elem_size(int dtype) { return dtype == FA_F32 ? 4 : 2; }
+
+extern "C" void fa_default_config(fa_config* cfg) {
+  if (!cfg) return;
+  cfg->n_max = 0;
+  cfg->p_max = FA_P_MAX;
+  cfg->dtype = FA_F32;
+  cfg->stream = nullptr;
+  cfg->clamp_delta = 1e-6;
+  cfg->rank_tol = 1e-12;
+  cfg->pair_tol = 1e-12;
+}
+
+extern "C" const char* fa_status_string(fa_status s) {
+  switch (s) {
+    case FA_OK: return "ok";
+    case FA_ERR_ARG: return "invalid argument";
+    case FA_ERR_ALLOC: return "allocation failed";
+    case FA_ERR_DEVICE: return "HIP call failed";
+    case FA_ERR_NONFINITE: return "input holds NaN or Inf";
+    case FA_ERR_ZERO_INPUT: return "all gradients are zero";
+  }
+  return "unknown status";
+}
+
+extern "C" const char* fa_version(void) { return "fa-mi355x 0.1 (gfx950)"; }
+
+extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
+  if (!cfg || !out_ctx) return FA_ERR_ARG;
+  *out_ctx = nullptr;
+  if (cfg->n_max < 1 || cfg->p_max < 1 || cfg->p_max > FA_P_MAX) return FA_ERR_ARG;
+  if (cfg->dtype != FA_F32 && cfg->dtype != FA_BF16) return FA_ERR_ARG;
+  if (!(cfg->clamp_delta > 0.0) || !(cfg->rank_tol >= 0.0) || !(cfg->pair_tol >= 0.0))
+    return FA_ERR_ARG;
+  fa_ctx* c = new (std::nothrow) fa_ctx;
+  if (!c) return FA_ERR_ALLOC;
+  memset(c, 0, sizeof(*c));
+  c->cfg = *cfg;
+  c->stream = (hipStream_t)cfg->stream;
+  if (hipGetDevice(&c->device) != hipSuccess) { delete c; return FA_ERR_DEVICE; }
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, c->device) != hipSuccess) { delete c; return FA_ERR_DEVICE; }
+  c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  c->gram_max_blocks = c->num_cus * FA_GRAM_WAVES_PER_CU;
+  c->combine_max_blocks = 1 << 20;
+  const int T = (cfg->p_max + 15) / 16;
+  const size_t ntp = (size_t)T * (T + 1) / 2;
+  const size_t part_bytes = (size_t)c->gram_max_blocks * ntp * 256 * sizeof(double);
+  bool ok = true;
+  ok = ok && hipMalloc((void**)&c->partials, part_bytes) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->Kd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->cd, sizeof(double) * (FA_P_MAX + 8)) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->gws, sizeof(double) * 2 * FA_P_MAX * (FA_P_MAX + 1)) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->info_d, sizeof(fa_info)) == hipSuccess;
+  if (!ok) { fa_destroy(c); return FA_ERR_ALLOC; }
+  if (hipMemset(c->info_d, 0, sizeof(fa_info)) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
+  for (int i = 0; i < 5; ++i)
+    if (hipEventCreate(&c->ev[i]) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
+  if (fa_irls_prepare() != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
+  *out_ctx = c;
+  return FA_OK;
+}
+
+extern "C" void fa_destroy(fa_ctx* c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  if (c->partials) (void)hipFree(c->partials);
+  if (c->Kd) (void)hipFree(c->Kd);
+  if (c->cd) (void)hipFree(c->cd);
+  if (c->gws) (void)hipFree(c->gws);
+  if (c->info_d) (void)hipFree(c->info_d);
+  for (int i = 0; i < 5; ++i)
+    if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+  delete c;
+}
+
+extern "C" fa_status fa_set_stream(fa_ctx* c, void* stream) {
+  if (!c) return FA_ERR_ARG;
+  c->stream = (hipStream_t)stream;
+  return FA_OK;
+}
+
+static bool check_matrix_args(const fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n) {
+  if (!c || !G) return false;
+  if (p < 1 || p > c->cfg.p_max || n < 1 || n > c->cfg.n_max || ldg < n) return false;
+  const int es = elem_size(c->cfg.dtype);
+  if (((uintptr_t)G & 15u) != 0) return false;
+  if ((ldg * es) % 16 != 0 && p > 1) return false;
+  return true;
+}
+
+static bool check_solver_args(int p, int m, double lambda, int iters, double tol) {
+  if (m < 1 || m > p) return false;
+  if (!(lambda >= 0.0) || !isfinite(lambda)) return false;
+  if (iters < 1 || iters > FA_ITERS_MAX) return false;
+  if (!(tol >= 0.0)) return false;
+  return true;
+}
+
+extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n, int m,
+                                  double lambda, int iters, double tol, float* out) {
+  if (!check_matrix_args(c, G, ldg, p, n) || !out || ((uintptr_t)out & 15u) != 0)
+    return FA_ERR_ARG;
+  if (!check_solver_args(p, m, lambda, iters, tol)) return FA_ERR_ARG;
+  hipStream_t st = c->stream;
+  const bool prof = c->profiling != 0;
+  c->ev_recorded = 0;
+  if (prof && hipEventRecord(c->ev[0], st) != hipSuccess) return FA_ERR_DEVICE;
+  // S1: norms and Gram matrix, per-wave partials;  S2: their fixed-order sum
+  int nparts = 0;
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+                              &nparts, st) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (prof && hipEventRecord(c->ev[1], st) != hipSuccess) return FA_ERR_DEVICE;
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (prof && hipEventRecord(c->ev[2], st) != hipSuccess) return FA_ERR_DEVICE;
+  // S3-S5: p x p IRLS and coefficients
+  if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, st) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (prof && hipEventRecord(c->ev[3], st) != hipSuccess) return FA_ERR_DEVICE;
+  // S6: out = G c
+  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks, st) !=
+      hipSuccess)
+    return FA_ERR_DEVICE;
+  if (prof) {
+    if (hipEventRecord(c->ev[4], st) != hipSuccess) return FA_ERR_DEVICE;
+    c->ev_recorded = 1;
+  }
+  c->has_solution = 1;
+  c->last_p = p;
+  c->last_m = m;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_get_info(fa_ctx* c, fa_info* host_out) {
+  if (!c || !host_out) return FA_ERR_ARG;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
+  if (hipMemcpy(host_out, c->info_d, sizeof(fa_info), hipMemcpyDeviceToHost) != hipSuccess)
+    return FA_ERR_DEVICE;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n,
+                             double* K_host) {
+  if (!check_matrix_args(c, G, ldg, p, n) || !K_host) return FA_ERR_ARG;
+  int nparts = 0;
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+                              &nparts, c->stream) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
+  if (hipMemcpy(K_host, c->Kd, sizeof(double) * p * p, hipMemcpyDeviceToHost) != hipSuccess)
+    return FA_ERR_DEVICE;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_irls(fa_ctx* c, const double* K_host, int p, int m, double lambda,
+                             int iters, double tol) {
+  if (!c || !K_host || p < 1 || p > c->cfg.p_max) return FA_ERR_ARG;
+  if (!check_solver_args(p, m, lambda, iters, tol)) return FA_ERR_ARG;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
+  if (hipMemcpy(c->Kd, K_host, sizeof(double) * p * p, hipMemcpyHostToDevice) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->stream) != hipSuccess)
+    return FA_ERR_DEVICE;
+  c->has_solution = 1;
+  c->last_p = p;
+  c->last_m = m;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_combine(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n,
+                                const double* c_host, float* out) {
+  if (!check_matrix_args(c, G, ldg, p, n) || !c_host || !out || ((uintptr_t)out & 15u) != 0)
+    return FA_ERR_ARG;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
+  if (hipMemcpy(c->cd, c_host, sizeof(double) * p, hipMemcpyHostToDevice) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks,
+                        c->stream) != hipSuccess)
+    return FA_ERR_DEVICE;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n, float* Y,
+                              int64_t ldy) {
+  if (!check_matrix_args(c, G, ldg, p, n) || !Y || ((uintptr_t)Y & 15u) != 0) return FA_ERR_ARG;
+  if (!c->has_solution || c->last_p != p) return FA_ERR_ARG;
+  const int m = c->last_m;
+  if (ldy < n || ((ldy * 4) % 16 != 0 && m > 1)) return FA_ERR_ARG;
+  // column a of Y = G * A[:, a]; A is row-major p x m inside the device-side record
+  const double* A = reinterpret_cast<const double*>(reinterpret_cast<const char*>(c->info_d) +
+                                                    offsetof(fa_info, A));
+  for (int a = 0; a < m; ++a)
+    if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, A + a, m, Y + (int64_t)a * ldy,
+                          c->combine_max_blocks, c->stream) != hipSuccess)
+      return FA_ERR_DEVICE;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_set_profiling(fa_ctx* c, int enabled) {
+  if (!c) return FA_ERR_ARG;
+  c->profiling = enabled ? 1 : 0;
+  c->ev_recorded = 0;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_get_timings(fa_ctx* c, float ms[4]) {
+  if (!c || !ms) return FA_ERR_ARG;
+  if (!c->ev_recorded) return FA_ERR_ARG;
+  if (hipEventSynchronize(c->ev[4]) != hipSuccess) return FA_ERR_DEVICE;
+  for (int k = 0; k < 4; ++k)
+    if (hipEventElapsedTime(&ms[k], c->ev[k], c->ev[k + 1]) != hipSuccess) return FA_ERR_DEVICE;
+  return FA_OK;
+}

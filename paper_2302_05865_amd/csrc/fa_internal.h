@@ -1,0 +1,36 @@
+// Internal interface between the C ABI (fa_api.hip) and the kernel launchers
+// (fa_kernels.hip).  Not installed; include/fa.h is the public header.
+#ifndef FA_INTERNAL_H_
+#define FA_INTERNAL_H_
+
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fa.h"
+
+#define FA_IRLS_THREADS 256   // workgroup size of the p x p solver
+#define FA_GRAM_WAVES_PER_CU 8 // single-wave workgroups of the Gram kernel per compute unit
+
+// K1: partial Grams of G, one per launched wavefront, into `partials` (up to max_blocks *
+// T(T+1)/2 * 256 doubles, T = ceil(p/16)); *nparts receives how many were written.
+hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                                   int max_blocks, double* partials, int* nparts,
+                                   hipStream_t st);
+// K2: their fixed-order sum into Kd (p*p doubles, row-major).
+hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
+                                 hipStream_t st);
+
+// K3: p x p solver.  Kd p*p doubles; cd p doubles out; info_d device fa_info; gws global
+// workspace of 2*FA_P_MAX*(FA_P_MAX+1) doubles.
+hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
+                          double delta, double rank_tol, double pair_tol, double* cd,
+                          fa_info* info_d, double* gws, hipStream_t st);
+hipError_t fa_irls_prepare(void);
+
+// K4: out = sum_i c[i*cstride] g_i.
+hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                             const double* c, int cstride, float* out, int max_blocks,
+                             hipStream_t st);
+
+#endif

@@ -1,0 +1,397 @@
+// HIP kernels of the Flag Aggregator hot path for gfx950 (MI355X), and their launchers.
+//
+//   K1 fa_gram_kernel        norms + Gram matrix K = G^T G, one streaming pass over G
+//   K2 fa_gram_reduce_kernel fixed-order reduction of the per-wave partial Grams
+//   K3 fa_irls_kernel        the p x p part: normalisation, IRLS (weighted PCA by Jacobi),
+//                            coefficients c with out = G c
+//   K4 fa_combine_kernel     out = G c, second streaming pass over G
+//
+// Paper: Sec. 2.1 (explained variance needs |g_i|^2 and Y^T g_i), Sec. 2.3 (D_ij^2),
+// Eq. 5 (objective), Alg. 1 (IRLS step and d = (1/p) Y Y^T G 1).
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "fa.h"
+#include "fa_internal.h"
+
+typedef double v4f64 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------------------------------
+// storage element types: 16 bytes per lane per load
+struct ElemF32 {
+  static constexpr int SIZE = 4;
+  static constexpr int EPL = 4;  // elements per 16-byte lane load
+};
+struct ElemBF16 {
+  static constexpr int SIZE = 2;
+  static constexpr int EPL = 8;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// 16 bytes of column `base` starting at element row0, zero-filled past row n.
+template <typename E>
+__device__ __forceinline__ uint4 load16_guarded(const unsigned char* base, int64_t row0,
+                                                int64_t n) {
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (row0 + E::EPL <= n) {
+    v = *reinterpret_cast<const uint4*>(base + row0 * E::SIZE);
+  } else if (row0 < n) {
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if constexpr (E::SIZE == 4) {
+      const uint32_t* src = reinterpret_cast<const uint32_t*>(base) + row0;
+      for (int e = 0; e < 4; ++e)
+        if (row0 + e < n) w[e] = src[e];
+    } else {
+      const uint16_t* src = reinterpret_cast<const uint16_t*>(base) + row0;
+      for (int e = 0; e < 8; ++e)
+        if (row0 + e < n) w[e >> 1] |= (uint32_t)src[e] << (16 * (e & 1));
+    }
+    v = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// K1: Gram matrix by fp64 matrix-core accumulation.
+//
+// One wavefront per workgroup; each wavefront owns a private LDS tile and walks row tiles
+// blockIdx.x, blockIdx.x + gridDim.x, ...  (a fixed assignment, so results are reproducible).
+// Per tile: 16-byte coalesced global loads (next tile's loads are in flight while this
+// tile is multiplied) -> LDS laid out [column][row] -> each lane reads the four rows of "its"
+// column -> v_mfma_f64_16x16x4_f64, whose A and B operands are the same register for a
+// diagonal 16x16 block of G^T G: lane (c, k) supplies G[row_k][c].
+// Products of fp32 (or bf16) inputs are exact in fp64 and the accumulation is fp64, which the
+// small differences 1 - v_i of the IRLS weights need.
+//
+// T   = number of 16-column blocks (p <= 16 T)
+// CPL = columns covered by one load instruction (1: a wave reads 1 KiB of one column;
+//       4: 256 B of each of four columns, which keeps the LDS tile small for large p)
+template <int T, int CPL, typename E>
+__global__ __launch_bounds__(64) void fa_gram_kernel(const unsigned char* __restrict__ G,
+                                                     int64_t ldg, int p, int64_t n,
+                                                     int64_t ntiles,
+                                                     double* __restrict__ partials) {
+  constexpr int EPL = E::EPL;
+  constexpr int LPC = 64 / CPL;            // lanes per column in one load instruction
+  constexpr int R = LPC * EPL;             // rows per tile
+  constexpr int NCG = T * 16 / CPL;        // load instructions per tile
+  constexpr int CS = R * E::SIZE + 16;     // LDS bytes per column (+16: bank spread)
+  constexpr int NTP = T * (T + 1) / 2;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[T * 16 * CS];
+
+  const int lane = threadIdx.x;
+  const int lcol = lane / LPC;
+  const int lrow = (lane % LPC) * EPL;
+  const int c16 = lane & 15, kq = lane >> 4;
+
+  v4f64 acc[NTP];
+#pragma unroll
+  for (int i = 0; i < NTP; ++i) acc[i] = v4f64{0.0, 0.0, 0.0, 0.0};
+
+  uint4 regs[NCG];
+  int64_t tile = blockIdx.x;
+#pragma unroll
+  for (int cg = 0; cg < NCG; ++cg) {
+    const int col = cg * CPL + lcol;
+    regs[cg] = make_uint4(0u, 0u, 0u, 0u);
+    if (col < p)
+      regs[cg] = load16_guarded<E>(G + (int64_t)col * ldg * E::SIZE, tile * R + lrow, n);
+  }
+
+  for (; tile < ntiles; tile += gridDim.x) {
+    __syncthreads();  // the previous tile's LDS reads are complete
+#pragma unroll
+    for (int cg = 0; cg < NCG; ++cg) {
+      const int col = cg * CPL + lcol;
+      *reinterpret_cast<uint4*>(lds + col * CS + lrow * E::SIZE) = regs[cg];
+    }
+    __syncthreads();
+    const int64_t next = tile + gridDim.x;
+    if (next < ntiles) {
+#pragma unroll
+      for (int cg = 0; cg < NCG; ++cg) {
+        const int col = cg * CPL + lcol;
+        if (col < p)
+          regs[cg] = load16_guarded<E>(G + (int64_t)col * ldg * E::SIZE, next * R + lrow, n);
+      }
+    }
+#pragma unroll 2
+    for (int t = 0; t < R / 16; ++t) {
+      double x[T][4];
+#pragma unroll
+      for (int tt = 0; tt < T; ++tt) {
+        const int col = tt * 16 + c16;
+        const unsigned char* src = lds + col * CS + (16 * t + 4 * kq) * E::SIZE;
+        float f0, f1, f2, f3;
+        if constexpr (E::SIZE == 4) {
+          const float4 f = *reinterpret_cast<const float4*>(src);
+          f0 = f.x; f1 = f.y; f2 = f.z; f3 = f.w;
+        } else {
+          const uint2 h = *reinterpret_cast<const uint2*>(src);
+          f0 = bf16_bits_to_f32(h.x & 0xffffu); f1 = bf16_bits_to_f32(h.x >> 16);
+          f2 = bf16_bits_to_f32(h.y & 0xffffu); f3 = bf16_bits_to_f32(h.y >> 16);
+        }
+        const bool on = col < p;   // columns past p hold stale LDS contents
+        x[tt][0] = on ? (double)f0 : 0.0;
+        x[tt][1] = on ? (double)f1 : 0.0;
+        x[tt][2] = on ? (double)f2 : 0.0;
+        x[tt][3] = on ? (double)f3 : 0.0;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        int tp = 0;
+#pragma unroll
+        for (int a = 0; a < T; ++a)
+#pragma unroll
+          for (int b = a; b < T; ++b) {
+            acc[tp] = __builtin_amdgcn_mfma_f64_16x16x4f64(x[a][j], x[b][j], acc[tp], 0, 0, 0);
+            ++tp;
+          }
+      }
+    }
+  }
+
+  // accumulator register r of lane l is entry (row 4*(l/16)+r, column l%16) of the block
+  double* dst = partials + (int64_t)blockIdx.x * NTP * 256;
+#pragma unroll
+  for (int tp = 0; tp < NTP; ++tp)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) dst[(tp * 4 + r) * 64 + lane] = acc[tp][r];
+}
+
+// K2: K = sum over waves of their partial Grams, in a fixed order (32 interleaved strands of
+// sequential sums, then the strands in order), so the result does not depend on timing.
+__global__ __launch_bounds__(256) void fa_gram_reduce_kernel(const double* __restrict__ partials,
+                                                             int nparts, int T, int p,
+                                                             double* __restrict__ K) {
+  const int NTP = T * (T + 1) / 2;
+  const int ei = threadIdx.x & 7, g = threadIdx.x >> 3;
+  const int E = blockIdx.x * 8 + ei;  // entry in [0, NTP*256)
+  double acc = 0.0;
+  for (int b = g; b < nparts; b += 32) acc += partials[(int64_t)b * NTP * 256 + E];
+  __shared__ double sh[256];
+  sh[threadIdx.x] = acc;
+  __syncthreads();
+  if (g == 0 && E < NTP * 256) {
+    double tot = 0.0;
+    for (int gg = 0; gg < 32; ++gg) tot += sh[gg * 8 + ei];
+    int tp = E >> 8, e = E & 255;
+    const int r = e >> 6, l = e & 63;
+    int ta = 0, tb = 0;
+    for (int a = 0, k = 0; a < T; ++a)
+      for (int b = a; b < T; ++b, ++k)
+        if (k == tp) { ta = a; tb = b; }
+    const int gi = ta * 16 + 4 * (l >> 4) + r, gj = tb * 16 + (l & 15);
+    if (gi < p && gj < p && gi <= gj) {
+      K[gi * p + gj] = tot;
+      K[gj * p + gi] = tot;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// K4: out[k] = sum_i c[i] G[k][i]  (Alg. 1: d = (1/p) Y Y^T G 1 = G c).  Each thread owns 16
+// bytes of every column (coalesced), accumulates in fp64 and writes fp32.
+template <typename E>
+__global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __restrict__ G,
+                                                         int64_t ldg, int p, int64_t n,
+                                                         const double* __restrict__ c,
+                                                         int cstride, float* __restrict__ out) {
+  constexpr int EPL = E::EPL;
+  __shared__ double cs[FA_P_MAX + 8];
+  if (threadIdx.x < FA_P_MAX + 8)
+    cs[threadIdx.x] = (int)threadIdx.x < p ? c[(int64_t)threadIdx.x * cstride] : 0.0;
+  __syncthreads();
+  const int64_t ngroups = (n + EPL - 1) / EPL;
+  for (int64_t gidx = (int64_t)blockIdx.x * 256 + threadIdx.x; gidx < ngroups;
+       gidx += (int64_t)gridDim.x * 256) {
+    const int64_t row0 = gidx * EPL;
+    double acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.0;
+    for (int c0 = 0; c0 < p; c0 += 8) {
+      uint4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        v[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (c0 + u < p) v[u] = load16_guarded<E>(G + (int64_t)(c0 + u) * ldg * E::SIZE, row0, n);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const double cc = cs[c0 + u];
+        if constexpr (E::SIZE == 4) {
+          acc[0] += cc * (double)__uint_as_float(v[u].x);
+          acc[1] += cc * (double)__uint_as_float(v[u].y);
+          acc[2] += cc * (double)__uint_as_float(v[u].z);
+          acc[3] += cc * (double)__uint_as_float(v[u].w);
+        } else {
+          acc[0] += cc * (double)bf16_bits_to_f32(v[u].x & 0xffffu);
+          acc[1] += cc * (double)bf16_bits_to_f32(v[u].x >> 16);
+          acc[2] += cc * (double)bf16_bits_to_f32(v[u].y & 0xffffu);
+          acc[3] += cc * (double)bf16_bits_to_f32(v[u].y >> 16);
+          acc[4] += cc * (double)bf16_bits_to_f32(v[u].z & 0xffffu);
+          acc[5] += cc * (double)bf16_bits_to_f32(v[u].z >> 16);
+          acc[6] += cc * (double)bf16_bits_to_f32(v[u].w & 0xffffu);
+          acc[7] += cc * (double)bf16_bits_to_f32(v[u].w >> 16);
+        }
+      }
+    }
+    float* dst = out + row0;
+    if (row0 + EPL <= n) {
+#pragma unroll
+      for (int e = 0; e < EPL; e += 4)
+        *reinterpret_cast<float4*>(dst + e) =
+            make_float4((float)acc[e], (float)acc[e + 1], (float)acc[e + 2], (float)acc[e + 3]);
+    } else {
+      for (int e = 0; e < EPL; ++e)
+        if (row0 + e < n) dst[e] = (float)acc[e];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// K3: the p x p solver, one workgroup, matrices in LDS.
+#define FA_FN __device__
+#define FA_TID ((int)threadIdx.x)
+#define FA_NT ((int)blockDim.x)
+#define FA_FOR(i, n) for (int i = FA_TID; i < (n); i += FA_NT)
+#define FA_SYNC() __syncthreads()
+#include "fa_irls_core.inc"
+
+__global__ __launch_bounds__(FA_IRLS_THREADS) void fa_irls_kernel(const double* __restrict__ Kg,
+                                                                  fa_irls_args ar, double* cg,
+                                                                  fa_info* info, double* gws,
+                                                                  int big_in_global) {
+  extern __shared__ __attribute__((aligned(16))) double dyn[];
+  const int p = ar.p;
+  const int ld = p | 1;
+  fa_irls_mem sm;
+  sm.ld = ld;
+  double* q = dyn;
+  const size_t msz = (size_t)p * ld;
+  sm.R = q; q += msz;
+  sm.Ut = q; q += msz;
+  sm.CM = q; q += msz;
+  sm.T = q; q += msz;
+  if (big_in_global) {
+    sm.D2inv = gws;
+    sm.Vt = gws + msz;
+  } else {
+    sm.D2inv = q; q += msz;
+    sm.Vt = q; q += msz;
+  }
+  sm.s = q; q += FA_P_MAX;
+  sm.dinv = q; q += FA_P_MAX;
+  sm.w = q; q += FA_P_MAX;
+  sm.rho = q; q += FA_P_MAX;
+  sm.v = q; q += FA_P_MAX;
+  sm.lam0 = q; q += FA_P_MAX;
+  sm.mu = q; q += FA_P_MAX;
+  sm.beta = q; q += FA_P_MAX;
+  sm.rot_c = q; q += FA_P_MAX / 2;
+  sm.rot_s = q; q += FA_P_MAX / 2;
+  sm.red = q; q += FA_IRLS_THREADS;
+  int* qi = reinterpret_cast<int*>(q);
+  sm.rot_p = qi; qi += FA_P_MAX / 2;
+  sm.rot_q = qi; qi += FA_P_MAX / 2;
+  sm.pos = qi; qi += FA_P_MAX;
+  sm.order = qi; qi += FA_P_MAX;
+  sm.flag = qi; qi += 8;
+  fa_irls_solve(Kg, ar, sm, cg, info);
+}
+
+size_t fa_irls_lds_bytes(int p, int* big_in_global) {
+  const size_t msz = (size_t)p * (p | 1) * sizeof(double);
+  const size_t small = (8 * FA_P_MAX + FA_P_MAX + FA_IRLS_THREADS) * sizeof(double) +
+                       (3 * FA_P_MAX + 8) * sizeof(int);
+  size_t need = 6 * msz + small;
+  *big_in_global = 0;
+  if (need > 60 * 1024) {   // keep the common sizes under the default dynamic-LDS limit
+    need = 4 * msz + small;
+    *big_in_global = 1;
+  }
+  return need;
+}
+
+// ------------------------------------------------------------------------------------------
+// launchers (host).  Shapes are validated by the callers in fa_api.cpp.
+template <int T, int CPL, typename E>
+static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
+                                double* partials, int* nparts, hipStream_t st) {
+  constexpr int R = (64 / CPL) * E::EPL;
+  const int64_t ntiles = (n + R - 1) / R;
+  const int blocks = (int)(ntiles < max_blocks ? ntiles : max_blocks);
+  *nparts = blocks;
+  hipLaunchKernelGGL((fa_gram_kernel<T, CPL, E>), dim3(blocks), dim3(64), 0, st,
+                     (const unsigned char*)G, ldg, p, n, ntiles, partials);
+  return hipGetLastError();
+}
+
+hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                                   int max_blocks, double* partials, int* nparts,
+                                   hipStream_t st) {
+  const int T = (p + 15) / 16;
+  hipError_t e = hipErrorInvalidValue;
+  if (dtype == FA_F32) {
+    switch (T) {
+      case 1: e = launch_gram_t<1, 1, ElemF32>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 2: e = launch_gram_t<2, 4, ElemF32>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 3: e = launch_gram_t<3, 4, ElemF32>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 4: e = launch_gram_t<4, 4, ElemF32>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+    }
+  } else {
+    switch (T) {
+      case 1: e = launch_gram_t<1, 1, ElemBF16>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 2: e = launch_gram_t<2, 4, ElemBF16>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 3: e = launch_gram_t<3, 4, ElemBF16>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 4: e = launch_gram_t<4, 4, ElemBF16>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+    }
+  }
+  return e;
+}
+
+hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
+                                 hipStream_t st) {
+  const int T = (p + 15) / 16;
+  const int NTP = T * (T + 1) / 2;
+  hipLaunchKernelGGL(fa_gram_reduce_kernel, dim3(NTP * 32), dim3(256), 0, st, partials, nparts, T,
+                     p, Kd);
+  return hipGetLastError();
+}
+
+hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
+                          double delta, double rank_tol, double pair_tol, double* cd,
+                          fa_info* info_d, double* gws, hipStream_t st) {
+  fa_irls_args ar;
+  ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
+  ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
+  int big = 0;
+  const size_t lds = fa_irls_lds_bytes(p, &big);
+  hipLaunchKernelGGL(fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d,
+                     gws, big);
+  return hipGetLastError();
+}
+
+hipError_t fa_irls_prepare(void) {
+  // allow the single-workgroup solver its large dynamic LDS (p = 64 needs ~140 KiB)
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls_kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                             const double* c, int cstride, float* out, int max_blocks,
+                             hipStream_t st) {
+  const int epl = dtype == FA_F32 ? 4 : 8;
+  const int64_t ngroups = (n + epl - 1) / epl;
+  int64_t blocks = (ngroups + 255) / 256;
+  if (blocks > max_blocks) blocks = max_blocks;
+  if (dtype == FA_F32)
+    hipLaunchKernelGGL((fa_combine_kernel<ElemF32>), dim3((unsigned)blocks), dim3(256), 0, st,
+                       (const unsigned char*)G, ldg, p, n, c, cstride, out);
+  else
+    hipLaunchKernelGGL((fa_combine_kernel<ElemBF16>), dim3((unsigned)blocks), dim3(256), 0, st,
+                       (const unsigned char*)G, ldg, p, n, c, cstride, out);
+  return hipGetLastError();
+}

@@ -1,0 +1,270 @@
+"""Parity of the HIP path against the fp64 CPU oracle, through the C ABI.
+
+Gate (fp32 storage): relative L2 error of the aggregate <= 1e-4 and projector difference
+||P_gpu - P_oracle||_F <= 1e-4 on Y, on the same seeded inputs.  The single kernels are held
+to what their arithmetic allows: the Gram matrix is accumulated in fp64 from exact products
+(<= 1e-12 relative to sqrt(K_ii K_jj)); the aggregate pass rounds an fp64 sum to fp32 once
+(<= 2^-23 relative per element).
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import as_f64_matrix, fa_literal, fa_scaled, projector_difference
+from paper_2302_05865_amd import FaError, FlagAggregator
+
+from gpu_util import announce, rel_l2, to_device
+
+pytestmark = pytest.mark.gpu
+
+GATE = 1e-4
+
+
+@pytest.fixture(scope="module")
+def agg_f32():
+    a = FlagAggregator(n_max=1 << 22, p_max=64, dtype="f32")
+    yield a
+    a.close()
+
+
+@pytest.fixture(scope="module")
+def agg_bf16():
+    a = FlagAggregator(n_max=1 << 22, p_max=64, dtype="bf16")
+    yield a
+    a.close()
+
+
+# ----------------------------------------------------------------------------- K1 + K2
+@pytest.mark.parametrize("p", [1, 2, 7, 15, 16, 17, 31, 32, 33, 48, 64])
+@pytest.mark.parametrize("n", [1, 3, 255, 257, 4099, 300_001])
+def test_gram_matches_fp64_definition(agg_f32, p, n):
+    announce("gram f32", p, n)
+    Gw = si.random_dense(p, n, seed=p * 1000 + n % 997, scale=3.0)
+    K = agg_f32.fa_gram(to_device(Gw))
+    G = as_f64_matrix(Gw)
+    ref = G.T @ G
+    scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref))) + 1e-300
+    assert np.max(np.abs(K - ref) / scale) <= 1e-12
+    assert np.array_equal(K, K.T)
+
+
+@pytest.mark.parametrize("p", [3, 16, 32, 40, 64])
+@pytest.mark.parametrize("n", [5, 1023, 100_003])
+def test_gram_bf16_storage(agg_bf16, p, n):
+    announce("gram bf16", p, n)
+    Gw = si.f32_to_bf16_bits(si.random_dense(p, n, seed=p + n, scale=2.0).reshape(-1)).reshape(p, n)
+    K = agg_bf16.fa_gram(to_device(Gw))
+    G = as_f64_matrix(Gw)
+    ref = G.T @ G
+    scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref))) + 1e-300
+    assert np.max(np.abs(K - ref) / scale) <= 1e-12
+
+
+def test_gram_with_row_stride_and_determinism(agg_f32):
+    announce("gram strided")
+    p, n, ld = 15, 70_001, 70_016
+    Gw = si.random_dense(p, ld, seed=5)
+    dev = to_device(Gw)[:, :n]
+    assert dev.stride(0) == ld
+    K1 = agg_f32.fa_gram(dev)
+    K2 = agg_f32.fa_gram(dev)
+    G = as_f64_matrix(Gw[:, :n])
+    ref = G.T @ G
+    assert np.max(np.abs(K1 - ref)) <= 1e-12 * np.abs(ref).max()
+    assert np.array_equal(K1, K2)          # fixed-order reduction: bitwise reproducible
+
+
+# ---------------------------------------------------------------------------------- K4
+@pytest.mark.parametrize("p", [1, 7, 15, 16, 33, 64])
+@pytest.mark.parametrize("n", [1, 6, 1025, 250_003])
+def test_combine_matches_definition(agg_f32, p, n):
+    announce("combine f32", p, n)
+    Gw = si.random_dense(p, n, seed=p + 17 * (n % 101))
+    c = np.random.default_rng(p).standard_normal(p)
+    out = agg_f32.fa_combine(to_device(Gw), c).cpu().numpy()
+    ref = as_f64_matrix(Gw) @ c
+    tol = 2.0 ** -23 * np.abs(as_f64_matrix(Gw)) @ np.abs(c) + 1e-30
+    assert np.all(np.abs(out - ref) <= tol)
+
+
+@pytest.mark.parametrize("p,n", [(5, 9), (32, 100_001)])
+def test_combine_bf16_storage(agg_bf16, p, n):
+    announce("combine bf16", p, n)
+    Gw = si.f32_to_bf16_bits(si.random_dense(p, n, seed=3).reshape(-1)).reshape(p, n)
+    c = np.random.default_rng(p).standard_normal(p)
+    out = agg_bf16.fa_combine(to_device(Gw), c).cpu().numpy()
+    ref = as_f64_matrix(Gw) @ c
+    tol = 2.0 ** -23 * np.abs(as_f64_matrix(Gw)) @ np.abs(c) + 1e-30
+    assert np.all(np.abs(out - ref) <= tol)
+
+
+# ---------------------------------------------------------------------------------- K3
+@pytest.mark.parametrize("name,n", [("cfg1", 20000), ("cfg2", 50000), ("cfg3", 50000),
+                                    ("cfg4", 30000), ("cfg5", 20000)])
+def test_irls_kernel_from_oracle_gram(agg_f32, name, n):
+    """The p x p kernel alone, fed the oracle's Gram matrix: isolates K3 from K1's rounding."""
+    announce("irls", name, n)
+    w = si.WORKLOADS[name].with_n(n)
+    Gw, _ = si.make_inputs(w, 0)
+    ref = fa_scaled(Gw, w.m, w.lam, w.iters, 0.0)
+    agg_f32.fa_irls(ref["K"], w.m, w.lam, w.iters, 0.0)
+    info = agg_f32.fa_get_info()
+    assert info.status == 0 and info.iters_done == w.iters
+    G = as_f64_matrix(Gw)
+    assert rel_l2(G @ info.c, ref["out"]) <= 1e-9
+    assert projector_difference(info.A, ref["A"], ref["K"]) <= 1e-9
+    assert np.allclose(info.objective, ref["objective"], atol=1e-6)
+    assert np.allclose(info.v, ref["v"], atol=1e-9)
+
+
+# ------------------------------------------------------------------------- end to end
+def _check_aggregate(agg, w, seed, lam=None, n_gate=GATE):
+    lam = w.lam if lam is None else lam
+    Gw, meta = si.make_inputs(w, seed)
+    ref = fa_scaled(Gw, w.m, lam, w.iters, 0.0)
+    dev = to_device(Gw)
+    out = agg.fa_aggregate(dev, w.m, lam, w.iters, 0.0)
+    info = agg.fa_get_info()
+    got = out.cpu().numpy().astype(np.float64)
+    e_out = rel_l2(got, ref["out"])
+    e_proj = projector_difference(info.A, ref["A"], ref["K"])
+    announce(w.name, "seed", seed, "lam", lam, "rel_l2", e_out, "proj", e_proj, "gap",
+             info.eigengap, "rank", info.rank, "sweeps", info.sweeps)
+    assert info.status == 0 and info.iters_done == w.iters
+    assert e_out <= n_gate
+    assert e_proj <= n_gate
+    assert np.allclose(info.v, ref["v"], atol=1e-6)
+    return info
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("lam", [0.0, 1.0])
+def test_aggregate_cfg1_full_size(agg_f32, seed, lam):
+    _check_aggregate(agg_f32, si.WORKLOADS["cfg1"], seed, lam)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+@pytest.mark.parametrize("name,n", [("cfg2", 700_003), ("cfg3", 500_001)])
+def test_aggregate_p15_reduced_n(agg_f32, name, n, seed):
+    _check_aggregate(agg_f32, si.WORKLOADS[name].with_n(n), seed)
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.1, 1.0])
+def test_aggregate_cfg5_reduced_n(agg_f32, lam):
+    _check_aggregate(agg_f32, si.WORKLOADS["cfg5"].with_n(300_007), 0, lam)
+
+
+def test_aggregate_cfg4_bf16_reduced_n(agg_bf16):
+    _check_aggregate(agg_bf16, si.WORKLOADS["cfg4"].with_n(400_003), 0)
+
+
+# ---------------------------------------------------------------------- special cases
+def test_full_subspace_returns_the_mean(agg_f32):
+    announce("m = p -> mean")
+    Gw = si.random_dense(9, 50_001, seed=11)
+    out = agg_f32.fa_aggregate(to_device(Gw), 9, 1.0, 5, 0.0).cpu().numpy()
+    assert rel_l2(out, as_f64_matrix(Gw).mean(axis=1)) <= 1e-6
+
+
+def test_identical_gradients_return_the_gradient(agg_f32):
+    announce("identical gradients")
+    g = si.random_dense(1, 40_003, seed=12)
+    Gw = np.repeat(g, 6, axis=0)
+    out = agg_f32.fa_aggregate(to_device(Gw), 3, 1.0, 4, 0.0).cpu().numpy()
+    info = agg_f32.fa_get_info()
+    assert info.rank == 1
+    assert rel_l2(out, g[0].astype(np.float64)) <= 1e-6
+
+
+def test_single_worker_and_tiny_n(agg_f32):
+    announce("p = 1, tiny n")
+    for n in (1, 2, 5):
+        Gw = si.random_dense(1, n, seed=n)
+        out = agg_f32.fa_aggregate(to_device(Gw), 1, 1.0, 3, 0.0).cpu().numpy()
+        assert rel_l2(out, Gw[0].astype(np.float64)) <= 1e-6
+    Gw = si.random_dense(4, 3, seed=9)          # n < p: rank 3
+    ref = fa_literal(as_f64_matrix(Gw), 2, 1.0, 4, 0.0)
+    out = agg_f32.fa_aggregate(to_device(Gw), 2, 1.0, 4, 0.0).cpu().numpy()
+    assert rel_l2(out, ref["out"]) <= GATE
+
+
+def test_zero_column_and_duplicate_columns(agg_f32):
+    announce("zero column + duplicates")
+    Gw = si.random_dense(7, 30_001, seed=13)
+    Gw[2] = 0.0
+    Gw[5] = Gw[1]
+    ref = fa_scaled(Gw, 3, 1.0, 6, 0.0)
+    out = agg_f32.fa_aggregate(to_device(Gw), 3, 1.0, 6, 0.0).cpu().numpy()
+    info = agg_f32.fa_get_info()
+    assert info.rank == 5 and info.w[2] == 0.0
+    assert rel_l2(out, ref["out"]) <= GATE
+
+
+def test_nonfinite_and_all_zero_inputs(agg_f32):
+    announce("nan / zero input")
+    Gw = si.random_dense(5, 10_000, seed=14)
+    Gw[3, 777] = np.nan
+    out = agg_f32.fa_aggregate(to_device(Gw), 2, 1.0, 3, 0.0).cpu().numpy()
+    assert agg_f32.fa_get_info().status == 4 and np.all(np.isnan(out))
+    Gw = np.zeros((5, 10_000), dtype=np.float32)
+    out = agg_f32.fa_aggregate(to_device(Gw), 2, 1.0, 3, 0.0).cpu().numpy()
+    assert agg_f32.fa_get_info().status == 5 and np.all(out == 0)
+
+
+def test_tol_stops_like_the_oracle(agg_f32):
+    announce("tol stop")
+    w = si.WORKLOADS["cfg1"].with_n(50_000)
+    Gw, _ = si.make_inputs(w, 3)
+    ref = fa_scaled(Gw, w.m, 1.0, 50, 1e-4)
+    out = agg_f32.fa_aggregate(to_device(Gw), w.m, 1.0, 50, 1e-4).cpu().numpy()
+    info = agg_f32.fa_get_info()
+    assert info.iters_done == ref["iters_done"] < 50
+    assert rel_l2(out, ref["out"]) <= GATE
+
+
+def test_bitwise_reproducible(agg_f32):
+    announce("determinism")
+    w = si.WORKLOADS["cfg2"].with_n(400_001)
+    Gw, _ = si.make_inputs(w, 4)
+    dev = to_device(Gw)
+    a = agg_f32.fa_aggregate(dev, w.m, w.lam, w.iters, 0.0).clone()
+    b = agg_f32.fa_aggregate(dev, w.m, w.lam, w.iters, 0.0)
+    assert torch.equal(a, b)
+
+
+def test_basis_is_orthonormal_and_matches_oracle_subspace(agg_f32):
+    announce("fa_basis")
+    w = si.WORKLOADS["cfg2"].with_n(200_001)
+    Gw, _ = si.make_inputs(w, 0)
+    dev = to_device(Gw)
+    agg_f32.fa_aggregate(dev, w.m, w.lam, w.iters, 0.0)
+    Y = agg_f32.fa_basis(dev, w.m).cpu().numpy().astype(np.float64).T      # n x m
+    assert np.abs(Y.T @ Y - np.eye(w.m)).max() <= 1e-5
+    ref = fa_scaled(Gw, w.m, w.lam, w.iters, 0.0)
+    Yo = as_f64_matrix(Gw) @ ref["A"]
+    cos = np.linalg.svd(Yo.T @ Y, compute_uv=False)
+    assert np.all(np.abs(cos - 1) <= 1e-5)
+
+
+def test_argument_errors(agg_f32):
+    announce("argument errors")
+    dev = to_device(si.random_dense(4, 100, seed=1))
+    with pytest.raises(FaError):
+        agg_f32.fa_aggregate(dev, 0, 1.0, 3, 0.0)
+    with pytest.raises(FaError):
+        agg_f32.fa_aggregate(dev, 5, 1.0, 3, 0.0)
+    with pytest.raises(FaError):
+        agg_f32.fa_aggregate(dev, 2, -1.0, 3, 0.0)
+    with pytest.raises(FaError):
+        agg_f32.fa_aggregate(dev, 2, 1.0, 0, 0.0)
+    with pytest.raises(FaError):
+        agg_f32.fa_aggregate(dev, 2, 1.0, 3, -1.0)
+    with pytest.raises(FaError):
+        agg_f32.fa_aggregate(dev[:, 1:], 2, 1.0, 3, 0.0)       # misaligned base pointer
+    small = FlagAggregator(n_max=50, p_max=4)
+    with pytest.raises(FaError):
+        small.fa_aggregate(dev, 2, 1.0, 3, 0.0)                 # n > n_max
+    small.close()
+    with pytest.raises(TypeError):
+        agg_f32.fa_aggregate(dev.double(), 2, 1.0, 3, 0.0)

@@ -1,0 +1,107 @@
+"""Host logic of the library's p x p solver (csrc/fa_irls_core.inc) against the oracle.
+
+The solver text is written as barrier-separated parallel-for phases; tests/emul builds it as
+a sequential host program (test-only, never part of libfa.so).  Comparing that build with the
+oracle checks the solver's indexing, Jacobi ordering, rank handling and coefficient formulas
+here, without a GPU.  The GPU tests run the same text as a kernel.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import as_f64_matrix, fa_literal, fa_scaled, projector_difference
+from paper_2302_05865_amd._ctypes_defs import FaInfo
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def emul(tmp_path_factory):
+    out = tmp_path_factory.mktemp("emul") / "libirls_emul.so"
+    subprocess.check_call(["g++", "-O2", "-shared", "-fPIC", "-I", os.path.join(ROOT, "include"),
+                           "-I", os.path.join(ROOT, "paper_2302_05865_amd", "csrc"),
+                           os.path.join(ROOT, "tests", "emul", "irls_emul.cpp"), "-o", str(out)])
+    lib = ctypes.CDLL(str(out))
+
+    def run(K, m, lam, iters, tol, delta=1e-6, rank_tol=1e-12, pair_tol=1e-12):
+        K = np.ascontiguousarray(K, dtype=np.float64)
+        p = K.shape[0]
+        info = FaInfo()
+        c = np.zeros(p)
+        d = ctypes.c_double
+        rc = lib.fa_irls_emulate(K.ctypes.data_as(ctypes.c_void_p), p, m, d(lam), iters, d(tol),
+                                 d(delta), d(rank_tol), d(pair_tol),
+                                 c.ctypes.data_as(ctypes.c_void_p), ctypes.byref(info))
+        assert rc == 0
+        return c, info
+    return run
+
+
+@pytest.mark.parametrize("name,n", [("cfg1", 20000), ("cfg2", 50000), ("cfg3", 50000),
+                                    ("cfg4", 30000), ("cfg5", 20000)])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_solver_text_matches_oracle_on_workload_shapes(emul, name, n, seed):
+    w = si.WORKLOADS[name].with_n(n)
+    Gw, _ = si.make_inputs(w, seed)
+    ref = fa_scaled(Gw, w.m, w.lam, w.iters, 0.0)
+    G = as_f64_matrix(Gw)
+    K = G.T @ G
+    c, info = emul(K, w.m, w.lam, w.iters, 0.0)
+    out = G @ c
+    assert info.status == 0 and info.iters_done == w.iters
+    assert np.linalg.norm(out - ref["out"]) <= 1e-9 * np.linalg.norm(ref["out"])
+    A = np.array(info.A[:w.p * w.m]).reshape(w.p, w.m)
+    assert projector_difference(A, ref["A"], K) <= 1e-9
+    assert np.allclose(np.array(info.objective[:w.iters]), ref["objective"], atol=1e-6)
+    assert np.allclose(np.array(info.v[:w.p]), ref["v"], atol=1e-9)
+
+
+@pytest.mark.parametrize("lam", [0.0, 1.0])
+def test_solver_text_small_cases(emul, lam):
+    rng = np.random.default_rng(0)
+    for (n, p, m) in [(40, 1, 1), (40, 2, 1), (40, 3, 3), (60, 9, 4), (50, 16, 8), (80, 17, 5)]:
+        G = rng.standard_normal((n, p)) * rng.uniform(0.3, 3, p)[None, :]
+        ref = fa_literal(G, m, lam, 6, 0.0)
+        c, info = emul(G.T @ G, m, lam, 6, 0.0)
+        assert np.linalg.norm(G @ c - ref["out"]) <= 1e-8 * np.linalg.norm(ref["out"])
+        assert info.rank == p
+
+
+def test_solver_text_degenerate_inputs(emul):
+    rng = np.random.default_rng(1)
+    g = rng.standard_normal(30)
+    # identical gradients, rank 1
+    G = np.repeat(g[:, None], 5, axis=1)
+    c, info = emul(G.T @ G, 3, 1.0, 4, 0.0)
+    assert info.rank == 1 and np.allclose(G @ c, g, atol=1e-12)
+    # a zero column and a duplicate pair
+    G = rng.standard_normal((30, 6))
+    G[:, 2] = 0.0
+    G[:, 4] = G[:, 1]
+    ref = fa_literal(G, 2, 1.0, 5, 0.0)
+    c, info = emul(G.T @ G, 2, 1.0, 5, 0.0)
+    assert info.rank == 4
+    assert np.linalg.norm(G @ c - ref["out"]) <= 1e-10 * np.linalg.norm(ref["out"])
+    # all zero / non-finite
+    c, info = emul(np.zeros((4, 4)), 2, 1.0, 3, 0.0)
+    assert info.status == 5 and np.all(c == 0)
+    K = np.eye(4); K[1, 2] = K[2, 1] = np.nan
+    c, info = emul(K, 2, 1.0, 3, 0.0)
+    assert info.status == 4 and np.all(np.isnan(c))
+
+
+def test_solver_text_stop_rule(emul):
+    rng = np.random.default_rng(3)
+    G = rng.standard_normal((40, 7)) * rng.uniform(0.3, 3, 7)[None, :]
+    full = fa_literal(G, 3, 1.0, 30, 0.0)
+    early = fa_literal(G, 3, 1.0, 30, 1e-3)
+    c, info = emul(G.T @ G, 3, 1.0, 30, 1e-3)
+    assert info.iters_done == early["iters_done"] < 30
+    assert np.linalg.norm(G @ c - early["out"]) <= 1e-10 * np.linalg.norm(early["out"])
+    assert np.allclose(np.array(info.w[:7]), early["w"], rtol=1e-8)
+    c, info = emul(G.T @ G, 3, 1.0, 30, 0.0)
+    assert np.allclose(np.array(info.w[:7]), full["w"], rtol=1e-6)
