@@ -153,7 +153,7 @@ __global__ __launch_bounds__(64) void fa_gram_kernel(const unsigned char* __rest
     }
   }
 
-  // accumulator register r of lane l is entry (row 4*(l/16)+r, column l%16) of the block
+  // accumulator register r of lane l is entry (row 4*r + l/16, column l%16) of the block
   double* dst = partials + (int64_t)blockIdx.x * NTP * 256;
 #pragma unroll
   for (int tp = 0; tp < NTP; ++tp)
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(256) void fa_gram_reduce_kernel(const double* __res
     for (int a = 0, k = 0; a < T; ++a)
       for (int b = a; b < T; ++b, ++k)
         if (k == tp) { ta = a; tb = b; }
-    const int gi = ta * 16 + 4 * (l >> 4) + r, gj = tb * 16 + (l & 15);
+    const int gi = ta * 16 + 4 * r + (l >> 4), gj = tb * 16 + (l & 15);
     if (gi < p && gj < p && gi <= gj) {
       K[gi * p + gj] = tot;
       K[gj * p + gi] = tot;

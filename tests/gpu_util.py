@@ -4,10 +4,20 @@ import torch
 
 
 def to_device(Gw: np.ndarray) -> torch.Tensor:
-    """Worker-major host array (fp32, or uint16 bf16 bits) -> device tensor [p, n]."""
+    """Worker-major host array (fp32, or uint16 bf16 bits) -> device tensor [p, n].
+
+    The library wants every gradient 16-byte aligned, so the rows live in a buffer whose row
+    pitch is rounded up to 16 bytes; the returned tensor is the [p, n] view of it."""
+    p, n = Gw.shape
+    per16 = 8 if Gw.dtype == np.uint16 else 4
+    ld = (n + per16 - 1) // per16 * per16
     if Gw.dtype == np.uint16:
-        return torch.from_numpy(Gw.view(np.int16)).cuda().view(torch.bfloat16)
-    return torch.from_numpy(Gw).cuda()
+        buf = torch.zeros((p, ld), dtype=torch.bfloat16, device="cuda")
+        buf[:, :n] = torch.from_numpy(Gw.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        buf = torch.zeros((p, ld), dtype=torch.float32, device="cuda")
+        buf[:, :n] = torch.from_numpy(Gw).cuda()
+    return buf[:, :n]
 
 
 def rel_l2(a: np.ndarray, b: np.ndarray) -> float:

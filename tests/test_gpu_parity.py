@@ -65,7 +65,7 @@ def test_gram_with_row_stride_and_determinism(agg_f32):
     announce("gram strided")
     p, n, ld = 15, 70_001, 70_016
     Gw = si.random_dense(p, ld, seed=5)
-    dev = to_device(Gw)[:, :n]
+    dev = torch.from_numpy(Gw).cuda()[:, :n]
     assert dev.stride(0) == ld
     K1 = agg_f32.fa_gram(dev)
     K2 = agg_f32.fa_gram(dev)
@@ -262,6 +262,8 @@ def test_argument_errors(agg_f32):
         agg_f32.fa_aggregate(dev, 2, 1.0, 3, -1.0)
     with pytest.raises(FaError):
         agg_f32.fa_aggregate(dev[:, 1:], 2, 1.0, 3, 0.0)       # misaligned base pointer
+    with pytest.raises(FaError):
+        agg_f32.fa_aggregate(torch.zeros((4, 99), device="cuda"), 2, 1.0, 3, 0.0)  # row pitch
     small = FlagAggregator(n_max=50, p_max=4)
     with pytest.raises(FaError):
         small.fa_aggregate(dev, 2, 1.0, 3, 0.0)                 # n > n_max
