@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libfa.so")
-SOURCES = ["fa_kernels.hip", "fa_api.hip"]
+SOURCES = ["fa_kernels.hip", "fa_irls16.hip", "fa_api.hip"]
 
 
 def hipcc_path() -> str:

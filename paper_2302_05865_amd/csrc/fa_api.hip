@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <new>
+#include <stdlib.h>
 #include <string.h>
 
 #include "fa.h"
@@ -23,6 +24,7 @@ struct fa_ctx {
   int has_solution;   // info_d holds an A from a completed fa_aggregate / fa_irls
   int last_p, last_m;
   int profiling;
+  int force_generic;  // FA_IRLS_GENERIC=1 in the environment: use the any-p solver for p <= 16 too
   hipEvent_t ev[5];
   int ev_recorded;
 };
@@ -66,6 +68,10 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   memset(c, 0, sizeof(*c));
   c->cfg = *cfg;
   c->stream = (hipStream_t)cfg->stream;
+  {
+    const char* e = getenv("FA_IRLS_GENERIC");
+    c->force_generic = (e && e[0] == '1') ? 1 : 0;
+  }
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return FA_ERR_DEVICE; }
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, c->device) != hipSuccess) { delete c; return FA_ERR_DEVICE; }
@@ -146,7 +152,7 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   if (prof && hipEventRecord(c->ev[2], st) != hipSuccess) return FA_ERR_DEVICE;
   // S3-S5: p x p IRLS and coefficients
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, st) != hipSuccess)
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->force_generic, st) != hipSuccess)
     return FA_ERR_DEVICE;
   if (prof && hipEventRecord(c->ev[3], st) != hipSuccess) return FA_ERR_DEVICE;
   // S6: out = G c
@@ -194,7 +200,7 @@ extern "C" fa_status fa_irls(fa_ctx* c, const double* K_host, int p, int m, doub
   if (hipMemcpy(c->Kd, K_host, sizeof(double) * p * p, hipMemcpyHostToDevice) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->stream) != hipSuccess)
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->force_generic, c->stream) != hipSuccess)
     return FA_ERR_DEVICE;
   c->has_solution = 1;
   c->last_p = p;

@@ -25,8 +25,12 @@ hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, doub
 // workspace of 2*FA_P_MAX*(FA_P_MAX+1) doubles.
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double* cd,
-                          fa_info* info_d, double* gws, hipStream_t st);
+                          fa_info* info_d, double* gws, int force_generic, hipStream_t st);
 hipError_t fa_irls_prepare(void);
+// K3 for p <= 16 (latency-tuned single-workgroup solver, static LDS).
+hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int iters, double tol,
+                            double delta, double rank_tol, double pair_tol, double* cd,
+                            fa_info* info_d, hipStream_t st);
 
 // K4: out = sum_i c[i*cstride] g_i.
 hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,

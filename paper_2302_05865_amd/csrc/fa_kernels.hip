@@ -363,7 +363,10 @@ hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, doub
 
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double* cd,
-                          fa_info* info_d, double* gws, hipStream_t st) {
+                          fa_info* info_d, double* gws, int force_generic, hipStream_t st) {
+  if (p <= 16 && !force_generic)
+    return fa_launch_irls16(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d,
+                            st);
   fa_irls_args ar;
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
   ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
