@@ -220,9 +220,14 @@ def fa_scaled(Gw: np.ndarray, m: int, lam: float, iters: int, tol: float,
 def projector_difference(A1: np.ndarray, A2: np.ndarray, K: np.ndarray) -> float:
     """Frobenius norm of ``P1 - P2`` for ``P_k = (G A_k)(G A_k)^T``, from ``K = G^T G``.
 
-    ``P1 - P2 = G M G^T`` with ``M = A1 A1^T - A2 A2^T``, so
-    ``||P1 - P2||_F^2 = tr(M K M K)``.
+    ``P1 - P2 = G M G^T`` with ``M = A1 A1^T - A2 A2^T``, and with the symmetric square root
+    ``F = K^{1/2}`` (``G = Q F`` for some ``Q`` with orthonormal columns)
+    ``||G M G^T||_F = ||F M F||_F = ||(F A1)(F A1)^T - (F A2)(F A2)^T||_F``.
+    Evaluated in this form: components of ``A_k`` in the null space of ``G`` (free when the
+    gradients are linearly dependent) are annihilated by ``F`` before any subtraction, whereas
+    ``sqrt(tr((M K)^2))`` cancels O(1) terms and has a noise floor near 1e-8.
     """
-    M = A1 @ A1.T - A2 @ A2.T
-    MK = M @ K
-    return float(np.sqrt(max(np.trace(MK @ MK), 0.0)))
+    lam, V = np.linalg.eigh((K + K.T) / 2)
+    F = (V * np.sqrt(np.maximum(lam, 0.0))[None, :]) @ V.T
+    W1, W2 = F @ A1, F @ A2
+    return float(np.linalg.norm(W1 @ W1.T - W2 @ W2.T))

@@ -24,7 +24,8 @@ struct fa_ctx {
   int has_solution;   // info_d holds an A from a completed fa_aggregate / fa_irls
   int last_p, last_m;
   int profiling;
-  int force_generic;  // FA_IRLS_GENERIC=1 in the environment: use the any-p solver for p <= 16 too
+  int solver;         // FA_IRLS_SOLVER in the environment: 0 default, 1 = p<=16 Jacobi path,
+                      // 2 = any-p Jacobi kernel (testing)
   hipEvent_t ev[5];
   int ev_recorded;
 };
@@ -69,8 +70,8 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   c->cfg = *cfg;
   c->stream = (hipStream_t)cfg->stream;
   {
-    const char* e = getenv("FA_IRLS_GENERIC");
-    c->force_generic = (e && e[0] == '1') ? 1 : 0;
+    const char* e = getenv("FA_IRLS_SOLVER");
+    c->solver = (e && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 0;
   }
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return FA_ERR_DEVICE; }
   hipDeviceProp_t prop;
@@ -85,7 +86,8 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   ok = ok && hipMalloc((void**)&c->partials, part_bytes) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->Kd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->cd, sizeof(double) * (FA_P_MAX + 8)) == hipSuccess;
-  ok = ok && hipMalloc((void**)&c->gws, sizeof(double) * 2 * FA_P_MAX * (FA_P_MAX + 1)) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->gws, sizeof(double) * (2 * FA_P_MAX * (FA_P_MAX + 1) + 258)) ==
+                 hipSuccess;
   ok = ok && hipMalloc((void**)&c->info_d, sizeof(fa_info)) == hipSuccess;
   if (!ok) { fa_destroy(c); return FA_ERR_ALLOC; }
   if (hipMemset(c->info_d, 0, sizeof(fa_info)) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
@@ -152,7 +154,7 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   if (prof && hipEventRecord(c->ev[2], st) != hipSuccess) return FA_ERR_DEVICE;
   // S3-S5: p x p IRLS and coefficients
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->force_generic, st) != hipSuccess)
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, st) != hipSuccess)
     return FA_ERR_DEVICE;
   if (prof && hipEventRecord(c->ev[3], st) != hipSuccess) return FA_ERR_DEVICE;
   // S6: out = G c
@@ -174,6 +176,16 @@ extern "C" fa_status fa_get_info(fa_ctx* c, fa_info* host_out) {
   if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
   if (hipMemcpy(host_out, c->info_d, sizeof(fa_info), hipMemcpyDeviceToHost) != hipSuccess)
     return FA_ERR_DEVICE;
+  if (host_out->status == FA_OK && host_out->eigengap != host_out->eigengap) {
+    // the purification path needs no eigenvalues; get the diagnostic gap now, off the hot path
+    if (fa_launch_gap(c->gws + 2 * FA_P_MAX * (FA_P_MAX + 1), c->info_d, c->stream) != hipSuccess)
+      return FA_ERR_DEVICE;
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
+    if (hipMemcpy(&host_out->eigengap,
+                  reinterpret_cast<const char*>(c->info_d) + offsetof(fa_info, eigengap),
+                  sizeof(double), hipMemcpyDeviceToHost) != hipSuccess)
+      return FA_ERR_DEVICE;
+  }
   return FA_OK;
 }
 
@@ -200,7 +212,7 @@ extern "C" fa_status fa_irls(fa_ctx* c, const double* K_host, int p, int m, doub
   if (hipMemcpy(c->Kd, K_host, sizeof(double) * p * p, hipMemcpyHostToDevice) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->force_generic, c->stream) != hipSuccess)
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, c->stream) != hipSuccess)
     return FA_ERR_DEVICE;
   c->has_solution = 1;
   c->last_p = p;

@@ -22,15 +22,21 @@ hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, doub
                                  hipStream_t st);
 
 // K3: p x p solver.  Kd p*p doubles; cd p doubles out; info_d device fa_info; gws global
-// workspace of 2*FA_P_MAX*(FA_P_MAX+1) doubles.
+// workspace of 2*FA_P_MAX*(FA_P_MAX+1) + 258 doubles.  solver: 0 = default (p <= 16:
+// purification with Jacobi fallback), 1 = p <= 16 Jacobi path, 2 = any-p Jacobi kernel.
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double* cd,
-                          fa_info* info_d, double* gws, int force_generic, hipStream_t st);
+                          fa_info* info_d, double* gws, int solver, hipStream_t st);
 hipError_t fa_irls_prepare(void);
 // K3 for p <= 16 (latency-tuned single-workgroup solver, static LDS).
+// mlast: 258 doubles; the fast path leaves the last weighted-PCA matrix there (16 x 16, then
+// rank and m) for fa_launch_gap.  use_purification = 0 forces the Jacobi path.
 hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int iters, double tol,
                             double delta, double rank_tol, double pair_tol, double* cd,
-                            fa_info* info_d, hipStream_t st);
+                            fa_info* info_d, double* mlast, int use_purification,
+                            hipStream_t st);
+// eigengap (mu_m - mu_{m+1}) / mu_1 of the matrix left in mlast, into info_d->eigengap.
+hipError_t fa_launch_gap(const double* mlast, fa_info* info_d, hipStream_t st);
 
 // K4: out = sum_i c[i*cstride] g_i.
 hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,

@@ -1,5 +1,10 @@
 // K3 for p <= 16: the p x p part of the Flag Aggregator (normalisation, IRLS by repeated
-// weighted PCA, coefficients) as one 256-thread workgroup with a latency-tuned Jacobi.
+// weighted PCA, coefficients) in one workgroup.  Two paths:
+//   * fast path (namespace fastp, wave 0): projector by matrix-core purification, no eigensolver;
+//   * Jacobi path (rest of this file, 256 threads): full eigen-decomposition per solve, used
+//     when the purification cannot converge (tied eigenvalues) or when asked for.
+//
+// The Jacobi path:
 //
 // Same mathematics as fa_irls_core.inc (Eq. 5 / Sec. 2.3 option (2) objective, Alg. 1 IRLS
 // step and direction; see the header of that file for the R-factor formulation).  What
@@ -47,48 +52,49 @@ struct Smem {
   double red[4];
   int pos[NP], order[NP];
   int done[2], sweeps, status, rank;
+#ifdef FA_K3_TIMING
+  long long t_master, t_tail, t_jacobi;   // shader-clock cycles (diagnostic build)
+#endif
 };
 
+// 1/sqrt(x) from the hardware estimate plus NR Newton steps.
+template <int NR>
 __device__ __forceinline__ double rsq_nr(double x) {
   double y = __builtin_amdgcn_rsq(x);
   const double hx = 0.5 * x;
-  double e = fma(-hx * y, y, 0.5);
-  y = fma(y, e, y);
-  e = fma(-hx * y, y, 0.5);
-  y = fma(y, e, y);
+#pragma unroll
+  for (int k = 0; k < NR; ++k) {
+    const double e = fma(-hx * y, y, 0.5);
+    y = fma(y, e, y);
+  }
   return y;
 }
 
-// Plane rotation zeroing A_pq:  x_p' = c x_p - s x_q,  x_q' = s x_p + c x_q.
-// *big: the off-diagonal entry exceeded 1e-9 relative to sqrt(|A_pp A_qq|).
-__device__ __forceinline__ void rotation(double app, double aqq, double apq, double* c, double* s,
+// Plane rotation for the index pair (a,b) of a symmetric matrix, zeroing A_ab:
+//   x_a' = c x_a - s x_b,  x_b' = s x_a + c x_b.
+// With zeta = A_bb - A_aa, N = 2 A_ab sign(zeta), D = |zeta| + sqrt(zeta^2 + 4 A_ab^2):
+//   tan = N / D,  c = D / sqrt(D^2 + N^2),  s = N / sqrt(D^2 + N^2)
+// (the small-angle root of the Jacobi equation; two reciprocal square roots, no division).
+// *big: the off-diagonal entry exceeded 1e-9 relative to sqrt(|A_aa A_bb|).
+__device__ __forceinline__ void rotation(double aaa, double abb, double aab, double* c, double* s,
                                          bool* active, bool* big) {
-  const double dd = fabs(app * aqq);
-  const double o2 = apq * apq;
-  const bool act = (o2 > 1e-30 * dd) && (fabs(apq) > 1e-300);
-  const double zeta = aqq - app;
-  const double nn = zeta < 0.0 ? -2.0 * apq : 2.0 * apq;
+  const double dd = fabs(aaa * abb);
+  const double o2 = aab * aab;
+  const bool act = (o2 > 1e-30 * dd) && (fabs(aab) > 1e-300);
+  const double zeta = abb - aaa;
+  const double nn = zeta < 0.0 ? -2.0 * aab : 2.0 * aab;
   const double h2 = fma(zeta, zeta, 4.0 * o2);
-  const double h = h2 * rsq_nr(act ? h2 : 1.0);
-  const double dn = fabs(zeta) + h;
-  const double wn = rsq_nr(act ? fma(dn, dn, nn * nn) : 1.0);
+  const double dn = fma(h2, rsq_nr<1>(act ? h2 : 1.0), fabs(zeta));
+  const double wn = rsq_nr<2>(act ? fma(dn, dn, nn * nn) : 1.0);
   *c = act ? dn * wn : 1.0;
   *s = act ? nn * wn : 0.0;
   *active = act;
   *big = act && (o2 > 1e-18 * dd);
 }
 
-__device__ __forceinline__ void pair_of(int round, int t, int* p, int* q) {
-  int a, b;
-  if (t == 0) {
-    a = NP - 1; b = round;
-  } else {
-    a = round + t; if (a >= NP - 1) a -= NP - 1;
-    b = round - t; if (b < 0) b += NP - 1;
-  }
-  *p = a < b ? a : b;
-  *q = a < b ? b : a;
-}
+// Round-robin pairing of 16 indices: index 15 stays, the others advance cyclically.
+// Slot t of round 0 holds (15, 0) for t = 0 and (t, 15 - t) otherwise.
+__device__ __forceinline__ int rr_next(int x) { return x >= 14 ? (x == 15 ? 15 : 0) : x + 1; }
 
 __device__ __forceinline__ void wave_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -97,55 +103,62 @@ __device__ __forceinline__ void wave_fence() {
 
 // One sweep by the master wavefront (all 64 lanes of wave 0).  Returns true when the sweep
 // made M diagonal to working precision (nothing above 1e-9 relative was met).
-__device__ bool master_sweep(double* M, Rot (*lg)[NPAIR], int lane) {
+__device__ __forceinline__ bool master_sweep(double* __restrict__ M, Rot (*lg)[NPAIR], int lane) {
   const int t = lane >> 3, u = lane & 7;
+  int a0 = t == 0 ? 15 : t, b0 = t == 0 ? 0 : 15 - t;
+  int a1 = u == 0 ? 15 : u, b1 = u == 0 ? 0 : 15 - u;
   bool big = false, any = false;
+#pragma unroll 1
   for (int round = 0; round < NROUND; ++round) {
-    int p0, q0, p1, q1;
-    pair_of(round, t, &p0, &q0);
-    pair_of(round, u, &p1, &q1);
-    const double app0 = M[p0 * LD + p0], aqq0 = M[q0 * LD + q0], apq0 = M[p0 * LD + q0];
-    const double app1 = M[p1 * LD + p1], aqq1 = M[q1 * LD + q1], apq1 = M[p1 * LD + q1];
-    const double b00 = M[p0 * LD + p1], b01 = M[p0 * LD + q1];
-    const double b10 = M[q0 * LD + p1], b11 = M[q0 * LD + q1];
+    const int ra0 = a0 * LD, rb0 = b0 * LD, ra1 = a1 * LD, rb1 = b1 * LD;
+    const double daa0 = M[ra0 + a0], dbb0 = M[rb0 + b0], dab0 = M[ra0 + b0];
+    const double daa1 = M[ra1 + a1], dbb1 = M[rb1 + b1], dab1 = M[ra1 + b1];
+    const double b00 = M[ra0 + a1], b01 = M[ra0 + b1];
+    const double b10 = M[rb0 + a1], b11 = M[rb0 + b1];
     double c0, s0, c1, s1;
-    bool a0, a1, g0, g1;
-    rotation(app0, aqq0, apq0, &c0, &s0, &a0, &g0);
-    rotation(app1, aqq1, apq1, &c1, &s1, &a1, &g1);
-    const bool round_active = __ballot(a0 || a1) != 0ull;
+    bool act0, act1, g0, g1;
+    rotation(daa0, dbb0, dab0, &c0, &s0, &act0, &g0);
+    rotation(daa1, dbb1, dab1, &c1, &s1, &act1, &g1);
+    const bool round_active = __ballot(act0 || act1) != 0ull;
     big = big || (__ballot(g0 || g1) != 0ull);
     any = any || round_active;
     if (u == 0) {
       Rot e;
-      e.c = c0; e.s = s0; e.p = p0; e.q = q0; e.active = a0 ? 1 : 0; e.pad = 0;
+      e.c = c0; e.s = s0; e.p = a0; e.q = b0; e.active = act0 ? 1 : 0; e.pad = 0;
       lg[round][t] = e;
     }
     if (round_active) {
       const double x00 = c0 * b00 - s0 * b10, x01 = c0 * b01 - s0 * b11;
       const double x10 = s0 * b00 + c0 * b10, x11 = s0 * b01 + c0 * b11;
-      double d00 = c1 * x00 - s1 * x01, d01 = s1 * x00 + c1 * x01;
-      double d10 = c1 * x10 - s1 * x11, d11 = s1 * x10 + c1 * x11;
-      if (t == u && a0) { d01 = 0.0; d10 = 0.0; }
-      M[p0 * LD + p1] = d00; M[p0 * LD + q1] = d01;
-      M[q0 * LD + p1] = d10; M[q0 * LD + q1] = d11;
+      const double d00 = c1 * x00 - s1 * x01, d01 = s1 * x00 + c1 * x01;
+      double d10 = c1 * x10 - s1 * x11;
+      const double d11 = s1 * x10 + c1 * x11;
+      if (t == u) d10 = d01;     // keep the diagonal block exactly symmetric
+      M[ra0 + a1] = d00; M[ra0 + b1] = d01;
+      M[rb0 + a1] = d10; M[rb0 + b1] = d11;
     }
+    a0 = rr_next(a0); b0 = rr_next(b0); a1 = rr_next(a1); b1 = rr_next(b1);
     wave_fence();
   }
   return !any || !big;
 }
 
 // Replay one sweep's log on the rows of X (16 columns) by one wavefront.
-__device__ void replay_sweep(double* X, const Rot (*lg)[NPAIR], int lane) {
+__device__ __forceinline__ void replay_sweep(double* __restrict__ X, const Rot (*lg)[NPAIR],
+                                             int lane) {
+#pragma unroll 1
   for (int round = 0; round < NROUND; ++round) {
-#pragma unroll
-    for (int k = lane; k < NPAIR * NP; k += 64) {
-      const int t = k >> 4, j = k & 15;
-      const Rot e = lg[round][t];
-      if (e.active) {
-        const double x = X[e.p * LD + j], y = X[e.q * LD + j];
-        X[e.p * LD + j] = e.c * x - e.s * y;
-        X[e.q * LD + j] = e.s * x + e.c * y;
-      }
+    const int j = lane & 15;
+    const Rot e0 = lg[round][lane >> 4], e1 = lg[round][4 + (lane >> 4)];
+    const double x0 = X[e0.p * LD + j], y0 = X[e0.q * LD + j];
+    const double x1 = X[e1.p * LD + j], y1 = X[e1.q * LD + j];
+    if (e0.active) {
+      X[e0.p * LD + j] = e0.c * x0 - e0.s * y0;
+      X[e0.q * LD + j] = e0.s * x0 + e0.c * y0;
+    }
+    if (e1.active) {
+      X[e1.p * LD + j] = e1.c * x1 - e1.s * y1;
+      X[e1.q * LD + j] = e1.s * x1 + e1.c * y1;
     }
     wave_fence();
   }
@@ -154,13 +167,19 @@ __device__ void replay_sweep(double* X, const Rot (*lg)[NPAIR], int lane) {
 // Diagonalise sm.M (16 x 16, live part in the leading block) and apply the same rotations
 // to the rows of XA (by wave 1) and XB (by wave 2); either may be null.  Leaves pos/order
 // (descending eigenvalues of the first `nlive` diagonal entries) in sm.pos / sm.order.
-__device__ void jacobi16(Smem& sm, double* XA, double* XB, int nlive) {
+__device__ __forceinline__ void jacobi16(Smem& sm, double* XA, double* XB, int nlive) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int sweep = 0;
   for (; sweep < MAX_SWEEPS; ++sweep) {
     const int buf = sweep & 1;
     if (wave == 0) {
+#ifdef FA_K3_TIMING
+      const long long t0 = clock64();
+#endif
       const bool fin = master_sweep(sm.M, sm.log[buf], lane);
+#ifdef FA_K3_TIMING
+      if (lane == 0) sm.t_master += clock64() - t0;
+#endif
       if (lane == 0) {
         sm.done[buf] = (fin || sweep + 1 == MAX_SWEEPS) ? 1 : 0;
         sm.sweeps += 1;
@@ -173,6 +192,9 @@ __device__ void jacobi16(Smem& sm, double* XA, double* XB, int nlive) {
     if (sm.done[buf]) break;
   }
   // the last sweep's log; meanwhile the master ranks the eigenvalues
+#ifdef FA_K3_TIMING
+  const long long t1 = clock64();
+#endif
   const int buf = sweep & 1;
   if (wave == 1 && XA) replay_sweep(XA, sm.log[buf], lane);
   if (wave == 2 && XB) replay_sweep(XB, sm.log[buf], lane);
@@ -194,10 +216,13 @@ __device__ void jacobi16(Smem& sm, double* XA, double* XB, int nlive) {
     }
   }
   __syncthreads();
+#ifdef FA_K3_TIMING
+  if (threadIdx.x == 0) sm.t_tail += clock64() - t1;
+#endif
 }
 
 // Deterministic sum over the workgroup (fixed butterfly inside each wave, waves in order).
-__device__ double block_sum(double x, Smem& sm) {
+__device__ __forceinline__ double block_sum(double x, Smem& sm) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
   __syncthreads();
@@ -208,18 +233,396 @@ __device__ double block_sum(double x, Smem& sm) {
 
 }  // namespace
 
+
+// ==========================================================================================
+// Fast path (wave 0 only): the weighted PCA needs only the *projector* P onto the m leading
+// eigenvectors of M = R C R^T -- the residuals 1 - v_i = |(I-P) r_i|^2 / s_i, the pair
+// residuals and the final direction are all functions of P.  P is computed without an
+// eigensolver, by trace-correcting purification: scale M into [0,1], then repeat
+//     X <- X^2          if that brings trace(X) closer to m,
+//     X <- 2X - X^2     otherwise,
+// which drives every eigenvalue to 0 or 1 while steering exactly m of them to 1.  Each step is
+// one 16 x 16 fp64 product = four v_mfma_f64_16x16x4_f64 on registers: for a symmetric X the
+// accumulator layout (register r of lane l = entry (4r + l/16, l%16)) is at once the A- and
+// the B-operand layout, so the iteration never leaves the register file.  trace(X^2) =
+// |X|_F^2 is reduced on the vector ALU while the matrix core multiplies.
+// R comes from a pivoted Cholesky factorisation of the normalised Gram matrix (R^T R = K~,
+// rank-revealing), so no eigen-decomposition is needed at set-up either.
+// If the purification does not converge (eigenvalues m and m+1 tie), the Jacobi path below
+// redoes the whole solve.
+namespace fastp {
+
+constexpr int LDF = 17;
+constexpr int LDZ = 18;          // column pitch of Zs (16-byte aligned rows of 16 doubles)
+constexpr int MAX_PURIFY = 128;
+
+struct Fmem {
+  double Kt[16 * LDF];   // Gram, then normalised Gram
+  double Rt[16 * LDF];   // rows of R~ (pivoted Cholesky): R~^T R~ = K~
+  double Rr[16 * LDF];   // R = R~ D^1/2
+  double Xi[16 * LDF];   // inverse of the pivot block of R~
+  double Bm[16 * LDF];   // right inverse of R: R Bm = I_r   (p x r)
+  double Ps[16 * LDF];   // projector
+  double Um[16 * LDF];   // orthonormal basis of range(P) (r x mm), as rows: Um[k][a]
+  double Am[16 * LDF];   // A (p x m)
+  __attribute__((aligned(16))) double Zs[16 * LDZ];   // (I-P) R by columns
+  double s[16], dinv[16], r1[16], beta[16];
+  int piv[16];
+};
+
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x) {
+  int lo = __double2loint(x), hi = __double2hiint(x);
+  lo = __builtin_amdgcn_mov_dpp(lo, CTRL, 0xf, 0xf, false);
+  hi = __builtin_amdgcn_mov_dpp(hi, CTRL, 0xf, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+// sum / max over each 16-lane row (lanes l with equal l/16); every lane of the row gets it
+__device__ __forceinline__ double row_sum(double x) {
+  x += dpp_f64<0x128>(x);   // row_ror:8
+  x += dpp_f64<0x124>(x);   // row_ror:4
+  x += dpp_f64<0x122>(x);   // row_ror:2
+  x += dpp_f64<0x121>(x);   // row_ror:1
+  return x;
+}
+__device__ __forceinline__ double row_max(double x) {
+  x = fmax(x, dpp_f64<0x128>(x));
+  x = fmax(x, dpp_f64<0x124>(x));
+  x = fmax(x, dpp_f64<0x122>(x));
+  x = fmax(x, dpp_f64<0x121>(x));
+  return x;
+}
+__device__ __forceinline__ double lane_bcast(double x, int srclane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(x), srclane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(x), srclane);
+  return __hiloint2double(hi, lo);
+}
+// deterministic sum over the wavefront, same value in every lane
+__device__ __forceinline__ double wave_sum(double x) {
+  x = row_sum(x);
+  return ((lane_bcast(x, 0) + lane_bcast(x, 16)) + lane_bcast(x, 32)) + lane_bcast(x, 48);
+}
+
+__device__ __forceinline__ v4d mm16(const v4d& a, const v4d& b) {
+  v4d acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s], b[s], acc, 0, 0, 0);
+  return acc;
+}
+
+// Greedy diagonal-pivoted Cholesky of the PSD matrix S (16 x 16 in LDS): rows[k][j] with
+// rows^T rows = S.  Stops at max_rank rows or when the largest remaining diagonal entry is
+// <= tol.  Executed by all 64 lanes (the four 16-lane rows do the same work).  Returns the
+// number of rows; piv[k] is the column chosen at step k.
+__device__ int pivoted_cholesky(const double* S, double* rows, int* piv, double tol, int max_rank,
+                                int lane) {
+  const int j = lane & 15;
+  double d = S[j * LDF + j];
+  bool used = false;
+  int rank = 0;
+  for (int k = 0; k < max_rank; ++k) {
+    const double mx = lane_bcast(row_max(used ? -1.0 : d), 0);
+    if (!(mx > tol)) break;
+    const unsigned long long bal = __ballot(!used && d == mx) & 0xffffull;
+    const int pv = __ffsll((long long)bal) - 1;
+    double acc = S[pv * LDF + j];
+    for (int a = 0; a < k; ++a) acc -= rows[a * LDF + pv] * rows[a * LDF + j];
+    const double dp = lane_bcast(acc, pv);           // recomputed pivot value S_k[pv][pv]
+    if (!(dp > 0.0)) break;
+    const double rk = used ? 0.0 : acc / sqrt(dp);
+    if (lane < 16) rows[k * LDF + j] = rk;
+    if (lane == 0) piv[k] = pv;
+    d -= rk * rk;
+    if (j == pv) used = true;
+    rank = k + 1;
+    wave_fence();
+  }
+  for (int k = rank; k < 16; ++k) {
+    if (lane < 16) rows[k * LDF + j] = 0.0;
+    if (lane == 0) piv[k] = 0;
+  }
+  wave_fence();
+  return rank;
+}
+
+// Returns 1 when the solve was completed here (including the error statuses), 0 when the
+// caller must fall back to the Jacobi path.
+__device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, double lambda,
+                     double tol, double delta, double rank_tol, double pair_tol,
+                     double* __restrict__ cg, fa_info* __restrict__ info,
+                     double* __restrict__ mlast, Fmem& fm) {
+  const int lane = threadIdx.x & 63;
+  const int c16 = lane & 15, q4 = lane >> 4;
+  const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
+
+  // ---- Gram, norms, status ---------------------------------------------------------------
+  bool bad = false;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int i = 4 * r + q4;
+    const bool in = i < p && c16 < p;
+    const double kv = in ? Kg[i * p + c16] : 0.0;
+    fm.Kt[i * LDF + c16] = kv;
+    if (in) info->K[i * p + c16] = kv;
+    bad = bad || !(fabs(kv) <= 1.79e308);
+  }
+  wave_fence();
+  const double sj = fm.Kt[c16 * LDF + c16];            // |g_j|^2 of this lane's column
+  const double dj = sj > 0.0 ? 1.0 / sqrt(sj) : 0.0;
+  const bool any_bad = __ballot(bad) != 0ull;
+  const bool any_live = __ballot(sj > 0.0) != 0ull;
+  if (lane < 16) { fm.s[lane] = sj; fm.dinv[lane] = dj; }
+  wave_fence();
+  if (any_bad || !any_live) {
+    const int st = any_bad ? 4 : 5;
+    if (lane < p) {
+      const double cv = any_bad ? nan("") : 0.0;
+      cg[lane] = cv;
+      info->c[lane] = cv; info->s[lane] = sj; info->v[lane] = 0.0; info->w[lane] = 0.0;
+    }
+    for (int idx = lane; idx < p * m; idx += 64) info->A[idx] = 0.0;
+    if (lane == 0) {
+      info->status = st; info->p = p; info->m = m; info->rank = 0; info->iters_done = 0;
+      info->sweeps = 0; info->eigengap = 0.0;
+    }
+    return 1;
+  }
+
+  // ---- pairwise distances (registers, entry (4r+q4, c16)), normalised Gram (LDS) ---------
+  double d2inv[4], kt[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int i = 4 * r + q4;
+    const double si = fm.s[i], di = fm.dinv[i];
+    const double kv = fm.Kt[i * LDF + c16];
+    const double d2 = si + sj - 2.0 * kv;
+    const bool livep = i < p && c16 < p && i != c16 && d2 > pair_tol * (si + sj);
+    d2inv[r] = livep ? 1.0 / d2 : 0.0;
+    kt[r] = i == c16 ? (si > 0.0 ? 1.0 : 0.0) : kv * di * dj;
+  }
+  wave_fence();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) fm.Kt[(4 * r + q4) * LDF + c16] = kt[r];
+  wave_fence();
+
+  // ---- R from the pivoted Cholesky factorisation of K~; rank; right inverse --------------
+  const int rank = pivoted_cholesky(fm.Kt, fm.Rt, fm.piv, rank_tol, 16, lane);
+  // Xi = inverse of the (upper triangular, in pivot order) block R~[:, piv]; lane c16 solves
+  // for column c16 by back substitution
+  for (int k = rank - 1; k >= 0; --k) {
+    double acc = (k == c16) ? 1.0 : 0.0;
+    for (int l = k + 1; l < rank; ++l) acc -= fm.Rt[k * LDF + fm.piv[l]] * fm.Xi[l * LDF + c16];
+    const double xv = acc / fm.Rt[k * LDF + fm.piv[k]];
+    if (lane < 16) fm.Xi[k * LDF + c16] = (c16 < rank) ? xv : 0.0;
+    wave_fence();
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int i = 4 * r + q4;
+    fm.Bm[i * LDF + c16] = 0.0;
+    fm.Rr[i * LDF + c16] = (i < rank) ? fm.Rt[i * LDF + c16] * sqrt(sj) : 0.0;
+    fm.Um[i * LDF + c16] = 0.0;
+  }
+  wave_fence();
+  for (int k = lane >> 4; k < rank; k += 4) {
+    const int i = fm.piv[k];
+    fm.Bm[i * LDF + c16] = (c16 < rank) ? fm.Xi[k * LDF + c16] * fm.dinv[i] : 0.0;
+  }
+  wave_fence();
+  v4d ra, rb;   // R as A operand (entry (c16, 4s+q4)) and as B operand (entry (4s+q4, c16))
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    ra[s] = fm.Rr[c16 * LDF + 4 * s + q4];
+    rb[s] = fm.Rr[(4 * s + q4) * LDF + c16];
+  }
+  if (lane < 16) {
+    double acc = 0.0;
+    for (int jj = 0; jj < 16; ++jj) acc += fm.Rr[lane * LDF + jj];
+    fm.r1[lane] = acc;                                 // R 1
+  }
+  wave_fence();
+
+  // ---- IRLS ------------------------------------------------------------------------------
+  const int mm = m < rank ? m : rank;
+  bool isdiag[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) isdiag[r] = (4 * r + q4) == c16;
+  const bool livej = sj > 0.0;
+  double wj = livej ? 1.0 : 0.0;                      // IRLS weight of this lane's column
+  double rhoj = 0.0;
+  v4d cp;                                              // pair part of C, entry (4r+q4, c16)
+#pragma unroll
+  for (int r = 0; r < 4; ++r) cp[r] = -2.0 * coef * d2inv[r];
+  v4d x = {0.0, 0.0, 0.0, 0.0}, mk = {0.0, 0.0, 0.0, 0.0};
+  double prev_obj = 0.0;
+  int iters_done = 0, steps = 0;
+  for (int it = 0; it < iters; ++it) {
+    // C = diag(w/s) + Laplacian of the pair part;  M = R C R^T via W = C R^T, M = R W
+    v4d c;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const double rs = row_sum(cp[r]);
+      c[r] = isdiag[r] ? wj * dj * dj - rs : cp[r];
+    }
+    const v4d wmat = mm16(c, ra);
+    mk = mm16(ra, wmat);
+    if (mm < rank) {
+      // scale into [0, 1]: M is PSD, so 0 <= eigenvalues <= trace(M)
+      double tr = 0.0;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) tr += isdiag[r] ? mk[r] : 0.0;
+      const double hi = wave_sum(tr);
+      const double sc = 1.0 / hi;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) x[r] = mk[r] * sc;
+      bool conv = false;
+      for (int k = 0; k < MAX_PURIFY; ++k) {
+        const v4d y = mm16(x, x);
+        double td = 0.0, tf = 0.0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          td += isdiag[r] ? x[r] : 0.0;
+          tf = fma(x[r], x[r], tf);
+        }
+        const double tX = wave_sum(td), tY = wave_sum(tf);   // trace(X), trace(X^2)
+        if (tX - tY < 1e-13) { conv = true; break; }
+        ++steps;
+        const bool sq = fabs(tY - (double)mm) < fabs(2.0 * tX - tY - (double)mm);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[r] = sq ? y[r] : 2.0 * x[r] - y[r];
+      }
+      if (!conv) return 0;
+    } else {
+      // m >= rank: Y spans all of span(G)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) x[r] = (isdiag[r] && c16 < rank) ? 1.0 : 0.0;
+    }
+    // Z = (I - P) R, by columns into LDS
+    v4d qm;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) qm[r] = isdiag[r] ? 1.0 - x[r] : -x[r];
+    const v4d z = mm16(qm, rb);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) fm.Zs[c16 * LDZ + 4 * r + q4] = z[r];
+    wave_fence();
+    double zj[16];
+    double nrm = 0.0;
+#pragma unroll
+    for (int a = 0; a < 16; ++a) {
+      zj[a] = fm.Zs[c16 * LDZ + a];
+      nrm = fma(zj[a], zj[a], nrm);
+    }
+    rhoj = nrm * dj * dj;                               // 1 - v_j
+    double part = (q4 == 0 && livej) ? sqrt(rhoj) : 0.0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = 4 * r + q4;
+      double acc = 0.0;
+#pragma unroll
+      for (int a = 0; a < 16; ++a) {
+        const double df = fm.Zs[i * LDZ + a] - zj[a];
+        acc = fma(df, df, acc);
+      }
+      const double rho = acc * d2inv[r];
+      const bool lp = d2inv[r] > 0.0;
+      part += lp ? coef * sqrt(rho) : 0.0;            // ordered pair (i, j)
+      cp[r] = lp ? -2.0 * coef * d2inv[r] / sqrt(rho > delta ? rho : delta) : 0.0;
+    }
+    wave_fence();
+    const double obj = wave_sum(part);
+    if (lane == 0) info->objective[it] = obj;
+    iters_done = it + 1;
+    const bool stop = it > 0 && fabs(prev_obj - obj) < tol;
+    prev_obj = obj;
+    if (stop) break;
+    wj = livej ? 1.0 / sqrt(rhoj > delta ? rhoj : delta) : 0.0;
+  }
+
+  // ---- epilogue: basis of range(P), A = B U_m, c = A (U_m^T R 1) / p ---------------------
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int i = 4 * r + q4;
+    fm.Ps[i * LDF + c16] = x[r];
+    mlast[i * 16 + c16] = mk[r];
+  }
+  wave_fence();
+  // P = U U^T with orthonormal U: the rows produced by the pivoted Cholesky of a projector
+  const int nb = pivoted_cholesky(fm.Ps, fm.Um, fm.piv, 1e-6, mm, lane);
+  if (nb != mm) return 0;
+  v4d ba, ub;   // B as A operand: B[c16][4s+q4];  U_m as B operand: U[a = 4s+q4][k = c16]
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    ba[s] = fm.Bm[c16 * LDF + 4 * s + q4];
+    ub[s] = fm.Um[c16 * LDF + 4 * s + q4];              // Um is stored as rows k: Um[k][a]
+  }
+  const v4d am = mm16(ba, ub);                           // A[4r+q4][c16]
+  if (lane < 16) {
+    double acc = 0.0;
+    for (int a = 0; a < 16; ++a) acc += fm.Um[lane * LDF + a] * fm.r1[a];
+    fm.beta[lane] = acc;                                 // (U_m^T R 1)[k]
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int i = 4 * r + q4;
+    fm.Am[i * LDF + c16] = am[r];
+    if (i < p && c16 < m) info->A[i * m + c16] = am[r];
+  }
+  wave_fence();
+  if (lane < 16 && lane < p) {
+    double acc = 0.0;
+    for (int k = 0; k < 16; ++k) acc += fm.Am[lane * LDF + k] * fm.beta[k];
+    acc /= (double)p;
+    cg[lane] = acc;
+    info->c[lane] = acc;
+    info->s[lane] = sj;
+    info->v[lane] = livej ? 1.0 - rhoj : 0.0;
+    info->w[lane] = wj;
+  }
+  if (lane == 0) {
+    info->status = 0;
+    info->p = p; info->m = m; info->rank = rank;
+    info->iters_done = iters_done;
+    info->sweeps = steps;
+    info->eigengap = nan("");        // filled in on demand by fa_get_info (needs eigenvalues)
+    mlast[256] = (double)rank;
+    mlast[257] = (double)m;
+  }
+  return 1;
+}
+
+}  // namespace fastp
+
 __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict__ Kg,
                                                         int p, int m, int iters, double lambda,
                                                         double tol, double delta, double rank_tol,
                                                         double pair_tol, double* __restrict__ cg,
-                                                        fa_info* __restrict__ info) {
+                                                        fa_info* __restrict__ info,
+                                                        double* __restrict__ mlast,
+                                                        int use_purification) {
   __shared__ Smem sm;
+  __shared__ fastp::Fmem fm;
+  __shared__ int fast_done;
   const int tid = threadIdx.x;
+  if (use_purification) {
+    if (tid < 64) {
+      const int ok = fastp::solve(Kg, p, m, iters, lambda, tol, delta, rank_tol, pair_tol, cg,
+                                  info, mlast, fm);
+      if (tid == 0) fast_done = ok;
+    }
+    __syncthreads();
+    if (fast_done) return;
+  }
   const int ri = tid >> 4, ci = tid & 15;       // this thread's entry of a 16 x 16 matrix
   const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
 
   // ---- setup: norms, status, normalised Gram, pairwise distances ------------------------
   if (tid == 0) { sm.sweeps = 0; sm.status = 0; sm.rank = 0; }
+#ifdef FA_K3_TIMING
+  const long long t_start = clock64();
+  if (tid == 0) { sm.t_master = 0; sm.t_tail = 0; sm.t_jacobi = 0; }
+#endif
   if (tid < NP) {
     const double si = tid < p ? Kg[tid * p + tid] : 0.0;
     sm.s[tid] = si;
@@ -308,7 +711,8 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
       double acc = 0.0;
       if (ri < r && ci < p) {
         const double rj = sm.R[ri * LD + ci];
-        for (int i = 0; i < p; ++i) acc += (sm.R[ri * LD + i] - rj) * sm.M[i * LD + ci];
+#pragma unroll
+        for (int i = 0; i < NP; ++i) acc += (sm.R[ri * LD + i] - rj) * sm.M[i * LD + ci];
         acc += rj * sm.w[ci] * sm.dinv[ci] * sm.dinv[ci];
       }
       sm.T[ri * LD + ci] = acc;
@@ -318,7 +722,8 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
       double acc = 0.0;
       if (ri < r && ci < r) {
         const int a = ri < ci ? ri : ci, b = ri < ci ? ci : ri;   // same sum on both sides
-        for (int j = 0; j < p; ++j) acc += sm.T[a * LD + j] * sm.R[b * LD + j];
+#pragma unroll
+        for (int j = 0; j < NP; ++j) acc += sm.T[a * LD + j] * sm.R[b * LD + j];
       }
       sm.M[ri * LD + ci] = acc;
     }
@@ -329,7 +734,8 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
     double part = 0.0;
     if (tid < p) {
       double top = 0.0, bot = 0.0;
-      for (int a = 0; a < r; ++a) {
+#pragma unroll
+      for (int a = 0; a < NP; ++a) {
         const double x = sm.R[a * LD + tid];
         if (sm.pos[a] < m) top += x * x; else bot += x * x;
       }
@@ -344,11 +750,11 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
       if (dinv2 > 0.0) {
         const int i = ri < ci ? ri : ci, j = ri < ci ? ci : ri;   // same sum for (i,j),(j,i)
         double bot = 0.0;
-        for (int a = 0; a < r; ++a)
-          if (sm.pos[a] >= m) {
-            const double x = sm.R[a * LD + i] - sm.R[a * LD + j];
-            bot += x * x;
-          }
+#pragma unroll
+        for (int a = 0; a < NP; ++a) {
+          const double x = sm.R[a * LD + i] - sm.R[a * LD + j];
+          bot += sm.pos[a] >= m ? x * x : 0.0;
+        }
         const double rho = bot * dinv2;
         part += coef * sqrt(rho);                  // ordered pair (ri, ci)
         cpair = -2.0 * coef * dinv2 / sqrt(rho > delta ? rho : delta);
@@ -412,13 +818,19 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
     double gap = __builtin_inf();
     if (m < r) gap = (sm.mu[sm.order[m - 1]] - sm.mu[sm.order[m]]) / sm.mu[sm.order[0]];
     info->eigengap = gap;
+#ifdef FA_K3_TIMING
+    info->objective[FA_ITERS_MAX - 1] = (double)(clock64() - t_start);
+    info->objective[FA_ITERS_MAX - 2] = (double)sm.t_master;
+    info->objective[FA_ITERS_MAX - 3] = (double)sm.t_tail;
+#endif
   }
 }
 
 hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int iters, double tol,
                             double delta, double rank_tol, double pair_tol, double* cd,
-                            fa_info* info_d, hipStream_t st) {
+                            fa_info* info_d, double* mlast, int use_purification,
+                            hipStream_t st) {
   hipLaunchKernelGGL(fa_irls16_kernel, dim3(1), dim3(256), 0, st, Kd, p, m, iters, lambda, tol,
-                     delta, rank_tol, pair_tol, cd, info_d);
+                     delta, rank_tol, pair_tol, cd, info_d, mlast, use_purification);
   return hipGetLastError();
 }

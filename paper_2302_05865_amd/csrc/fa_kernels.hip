@@ -363,10 +363,10 @@ hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, doub
 
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double* cd,
-                          fa_info* info_d, double* gws, int force_generic, hipStream_t st) {
-  if (p <= 16 && !force_generic)
+                          fa_info* info_d, double* gws, int solver, hipStream_t st) {
+  if (p <= 16 && solver != 2)
     return fa_launch_irls16(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d,
-                            st);
+                            gws + 2 * FA_P_MAX * (FA_P_MAX + 1), solver == 0 ? 1 : 0, st);
   fa_irls_args ar;
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
   ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
@@ -374,6 +374,38 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
   const size_t lds = fa_irls_lds_bytes(p, &big);
   hipLaunchKernelGGL(fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d,
                      gws, big);
+  return hipGetLastError();
+}
+
+// Eigenvalues of the last weighted-PCA matrix (16 x 16, left by the purification path) by the
+// Jacobi routine above; writes the relative gap between eigenvalues m and m+1.
+__global__ __launch_bounds__(64) void fa_gap_kernel(const double* __restrict__ mlast,
+                                                    fa_info* __restrict__ info) {
+  __shared__ double A[16 * 17];
+  __shared__ double vals[16], rc[8], rs[8], red[64];
+  __shared__ int rp[8], rq[8], pos[16], order[16], flag[8];
+  fa_irls_mem sm;
+  sm.ld = 17;
+  sm.rot_c = rc; sm.rot_s = rs; sm.rot_p = rp; sm.rot_q = rq; sm.red = red; sm.flag = flag;
+  sm.pos = pos; sm.order = order;
+  const int r = (int)mlast[256], m = (int)mlast[257];
+  for (int idx = threadIdx.x; idx < 256; idx += 64) A[(idx >> 4) * 17 + (idx & 15)] = mlast[idx];
+  if (threadIdx.x == 0) flag[4] = 0;
+  __syncthreads();
+  if (r < 1 || r > 16) return;
+  fa_jacobi(A, r, (double*)0, 0, (double*)0, 0, sm, 60);
+  FA_FOR(a, r) vals[a] = A[a * 17 + a];
+  FA_SYNC();
+  fa_rank_desc(vals, r, pos, order);
+  if (threadIdx.x == 0) {
+    double gap = __builtin_inf();
+    if (m < r) gap = (vals[order[m - 1]] - vals[order[m]]) / vals[order[0]];
+    info->eigengap = gap;
+  }
+}
+
+hipError_t fa_launch_gap(const double* mlast, fa_info* info_d, hipStream_t st) {
+  hipLaunchKernelGGL(fa_gap_kernel, dim3(1), dim3(64), 0, st, mlast, info_d);
   return hipGetLastError();
 }
 
