@@ -121,7 +121,7 @@ def main() -> int:
         cpu_s = time.perf_counter() - t0
         got = out.cpu().numpy().astype(np.float64)
         rel = float(np.linalg.norm(got - ref["out"]) / np.linalg.norm(ref["out"]))
-        proj = projector_difference(info.A, ref["A"], ref["K"])
+        proj = projector_difference(info.A, ref["A"], ref["R"])
         result["cpu_baseline"] = {"value": 1.0 / cpu_s, "unit": "aggregations/s", "cores": cores,
                                   "kind": "oracle",
                                   "sample": f"1 whole aggregation of {w.name} (fp64 R-factor "

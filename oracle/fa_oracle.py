@@ -217,17 +217,16 @@ def fa_scaled(Gw: np.ndarray, m: int, lam: float, iters: int, tol: float,
     return res
 
 
-def projector_difference(A1: np.ndarray, A2: np.ndarray, K: np.ndarray) -> float:
-    """Frobenius norm of ``P1 - P2`` for ``P_k = (G A_k)(G A_k)^T``, from ``K = G^T G``.
+def projector_difference(A1: np.ndarray, A2: np.ndarray, R: np.ndarray) -> float:
+    """Frobenius norm of ``P1 - P2`` for ``P_k = (G A_k)(G A_k)^T``, given any factor ``R``
+    with ``G = Q R`` (``Q`` with orthonormal columns; e.g. the ``R`` of ``fa_scaled``).
 
-    ``P1 - P2 = G M G^T`` with ``M = A1 A1^T - A2 A2^T``, and with the symmetric square root
-    ``F = K^{1/2}`` (``G = Q F`` for some ``Q`` with orthonormal columns)
-    ``||G M G^T||_F = ||F M F||_F = ||(F A1)(F A1)^T - (F A2)(F A2)^T||_F``.
-    Evaluated in this form: components of ``A_k`` in the null space of ``G`` (free when the
-    gradients are linearly dependent) are annihilated by ``F`` before any subtraction, whereas
-    ``sqrt(tr((M K)^2))`` cancels O(1) terms and has a noise floor near 1e-8.
+    ``P_k = Q (R A_k)(R A_k)^T Q^T``, hence
+    ``||P1 - P2||_F = ||(R A1)(R A1)^T - (R A2)(R A2)^T||_F``.
+    Components of ``A_k`` in the null space of ``G`` (free when the gradients are linearly
+    dependent) are annihilated by ``R`` itself, to rounding, before anything is subtracted.
+    (Forms that go through ``K = G^T G`` -- ``sqrt(tr((M K)^2))`` or ``K^{1/2}`` -- see
+    the null space only to ``sqrt(eps)`` and have a noise floor near 1e-8 there.)
     """
-    lam, V = np.linalg.eigh((K + K.T) / 2)
-    F = (V * np.sqrt(np.maximum(lam, 0.0))[None, :]) @ V.T
-    W1, W2 = F @ A1, F @ A2
+    W1, W2 = R @ A1, R @ A2
     return float(np.linalg.norm(W1 @ W1.T - W2 @ W2.T))

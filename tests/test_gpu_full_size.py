@@ -30,7 +30,7 @@ def test_full_size(name):
     info = agg.fa_get_info()
     got = out.cpu().numpy().astype(np.float64)
     e_out = rel_l2(got, ref["out"])
-    e_proj = projector_difference(info.A, ref["A"], ref["K"])
+    e_proj = projector_difference(info.A, ref["A"], ref["R"])
     announce(name, "rel_l2", e_out, "proj", e_proj, "gap", info.eigengap, "sweeps", info.sweeps)
     assert info.status == 0 and info.iters_done == w.iters
     assert e_out <= 1e-4 and e_proj <= 1e-4

@@ -113,7 +113,7 @@ def test_irls_kernel_from_oracle_gram(agg_f32, name, n):
     assert info.status == 0 and info.iters_done == w.iters
     G = as_f64_matrix(Gw)
     assert rel_l2(G @ info.c, ref["out"]) <= 1e-9
-    assert projector_difference(info.A, ref["A"], ref["K"]) <= 1e-9
+    assert projector_difference(info.A, ref["A"], ref["R"]) <= 1e-9
     assert np.allclose(info.objective, ref["objective"], atol=1e-6)
     assert np.allclose(info.v, ref["v"], atol=1e-9)
 
@@ -128,7 +128,7 @@ def _check_aggregate(agg, w, seed, lam=None, n_gate=GATE):
     info = agg.fa_get_info()
     got = out.cpu().numpy().astype(np.float64)
     e_out = rel_l2(got, ref["out"])
-    e_proj = projector_difference(info.A, ref["A"], ref["K"])
+    e_proj = projector_difference(info.A, ref["A"], ref["R"])
     announce(w.name, "seed", seed, "lam", lam, "rel_l2", e_out, "proj", e_proj, "gap",
              info.eigengap, "rank", info.rank, "sweeps", info.sweeps)
     assert info.status == 0 and info.iters_done == w.iters

@@ -55,7 +55,7 @@ def test_solver_text_matches_oracle_on_workload_shapes(emul, name, n, seed):
     assert info.status == 0 and info.iters_done == w.iters
     assert np.linalg.norm(out - ref["out"]) <= 1e-9 * np.linalg.norm(ref["out"])
     A = np.array(info.A[:w.p * w.m]).reshape(w.p, w.m)
-    assert projector_difference(A, ref["A"], K) <= 1e-9
+    assert projector_difference(A, ref["A"], ref["R"]) <= 1e-9
     assert np.allclose(np.array(info.objective[:w.iters]), ref["objective"], atol=1e-6)
     assert np.allclose(np.array(info.v[:w.p]), ref["v"], atol=1e-9)
 

@@ -338,7 +338,7 @@ def test_scaled_matches_literal(lam, shape):
     assert np.all(np.abs(_principal_cosines(a["Y"], Yb) - 1) < 1e-10)
     K = G.T @ G
     assert np.allclose(b["K"], K, atol=1e-10 * np.abs(K).max())
-    assert projector_difference(b["A"], b["A"], K) == 0.0
+    assert projector_difference(b["A"], b["A"], b["R"]) == 0.0
 
 
 def test_tsqr_is_an_isometry_with_duplicates_and_ragged_chunks():
@@ -361,7 +361,16 @@ def test_projector_difference_matches_dense():
     A2 = rng.standard_normal((5, 2))
     P1 = (G @ A1) @ (G @ A1).T
     P2 = (G @ A2) @ (G @ A2).T
-    assert abs(projector_difference(A1, A2, G.T @ G) - np.linalg.norm(P1 - P2)) < 1e-9
+    R = np.linalg.qr(G, mode="r")
+    assert abs(projector_difference(A1, A2, R) - np.linalg.norm(P1 - P2)) < 1e-9
+    # linearly dependent gradients: null-space components of A must not register
+    G2 = np.concatenate([G, G[:, :1]], axis=1)
+    R2 = np.linalg.qr(G2, mode="r")
+    B1 = np.concatenate([A1, np.zeros((1, 2))], axis=0)
+    B2 = B1.copy()
+    B2[0] += 0.5
+    B2[5] -= 0.5                      # same G2 @ B, different representation
+    assert projector_difference(B1, B2, R2) < 1e-12
 
 
 def test_bf16_decode_known_patterns():
