@@ -16,7 +16,7 @@ struct fa_ctx {
   int num_cus;
   int gram_max_blocks;
   int combine_max_blocks;
-  double* partials;   // gram_max_blocks * NTP(p_max) * 256
+  double* partials;   // gram_max_blocks * FA_GRAM_WAVES_PER_CU * NTP(p_max) * 256
   double* Kd;         // FA_P_MAX^2
   double* cd;         // FA_P_MAX
   double* gws;        // 2 * FA_P_MAX * (FA_P_MAX + 1)
@@ -77,11 +77,12 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, c->device) != hipSuccess) { delete c; return FA_ERR_DEVICE; }
   c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  c->gram_max_blocks = c->num_cus * FA_GRAM_WAVES_PER_CU;
+  c->gram_max_blocks = c->num_cus;                 // one Gram workgroup per compute unit
   c->combine_max_blocks = 1 << 20;
   const int T = (cfg->p_max + 15) / 16;
   const size_t ntp = (size_t)T * (T + 1) / 2;
-  const size_t part_bytes = (size_t)c->gram_max_blocks * ntp * 256 * sizeof(double);
+  const size_t part_bytes =
+      (size_t)c->gram_max_blocks * FA_GRAM_WAVES_PER_CU * ntp * 256 * sizeof(double);
   bool ok = true;
   ok = ok && hipMalloc((void**)&c->partials, part_bytes) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->Kd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;

@@ -10,10 +10,11 @@
 #include "fa.h"
 
 #define FA_IRLS_THREADS 256   // workgroup size of the p x p solver
-#define FA_GRAM_WAVES_PER_CU 8 // single-wave workgroups of the Gram kernel per compute unit
+#define FA_GRAM_WAVES_PER_CU 16 // most wavefronts a Gram workgroup (one per compute unit) has
 
 // K1: partial Grams of G, one per launched wavefront, into `partials` (up to max_blocks *
-// T(T+1)/2 * 256 doubles, T = ceil(p/16)); *nparts receives how many were written.
+// FA_GRAM_WAVES_PER_CU * T(T+1)/2 * 256 doubles, T = ceil(p/16)); max_blocks = workgroups
+// (one per compute unit); *nparts receives how many partials were written.
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int max_blocks, double* partials, int* nparts,
                                    hipStream_t st);

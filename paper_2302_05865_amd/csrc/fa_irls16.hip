@@ -305,6 +305,21 @@ __device__ __forceinline__ double wave_sum(double x) {
   return ((lane_bcast(x, 0) + lane_bcast(x, 16)) + lane_bcast(x, 32)) + lane_bcast(x, 48);
 }
 
+// |X|_F^2 over the wavefront in two stages, so that the second stage of one purification
+// step can be issued next to the first stage of the following one (fp64 vector operations
+// have a long dependent latency; two interleaved chains fit under one 16 x 16 product).
+__device__ __forceinline__ double fro2_stage1(const v4d& x) {
+  double t = fma(x[0], x[0], x[1] * x[1]) + fma(x[2], x[2], x[3] * x[3]);
+  t += dpp_f64<0x128>(t);
+  t += dpp_f64<0x124>(t);
+  return t;
+}
+__device__ __forceinline__ double fro2_stage2(double t) {
+  t += dpp_f64<0x122>(t);
+  t += dpp_f64<0x121>(t);
+  return (lane_bcast(t, 0) + lane_bcast(t, 16)) + (lane_bcast(t, 32) + lane_bcast(t, 48));
+}
+
 __device__ __forceinline__ v4d mm16(const v4d& a, const v4d& b) {
   v4d acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
@@ -356,6 +371,10 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   const int lane = threadIdx.x & 63;
   const int c16 = lane & 15, q4 = lane >> 4;
   const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
+#ifdef FA_K3_TIMING
+  const long long tk0 = clock64();
+  long long tk_pur = 0, tk_res = 0, tk_mm = 0, tk_setup = 0;
+#endif
 
   // ---- Gram, norms, status ---------------------------------------------------------------
   bool bad = false;
@@ -444,6 +463,9 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   }
   wave_fence();
 
+#ifdef FA_K3_TIMING
+  tk_setup = clock64() - tk0;
+#endif
   // ---- IRLS ------------------------------------------------------------------------------
   const int mm = m < rank ? m : rank;
   bool isdiag[4];
@@ -459,6 +481,9 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   double prev_obj = 0.0;
   int iters_done = 0, steps = 0;
   for (int it = 0; it < iters; ++it) {
+#ifdef FA_K3_TIMING
+    const long long ta = clock64();
+#endif
     // C = diag(w/s) + Laplacian of the pair part;  M = R C R^T via W = C R^T, M = R W
     v4d c;
 #pragma unroll
@@ -468,6 +493,10 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     }
     const v4d wmat = mm16(c, ra);
     mk = mm16(ra, wmat);
+#ifdef FA_K3_TIMING
+    const long long tb = clock64();
+    tk_mm += tb - ta;
+#endif
     if (mm < rank) {
       // scale into [0, 1]: M is PSD, so 0 <= eigenvalues <= trace(M)
       double tr = 0.0;
@@ -477,21 +506,64 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
       const double sc = 1.0 / hi;
 #pragma unroll
       for (int r = 0; r < 4; ++r) x[r] = mk[r] * sc;
+      // Steering: square when trace(X) > m, else X <- 2X - X^2.  trace(X) is carried along
+      // (after a square it is the previous |X|_F^2, otherwise 2 trace(X) - |X|_F^2), so the
+      // only reduction per step is |X|_F^2, and its result is not needed before the end of
+      // the *next* step.  A wavefront issues in order and fp64 vector operations have a
+      // dependent latency of ~32 cycles, while each of the four dependent matrix-core
+      // instructions of X^2 holds the issue port for 64: the two reduction chains (second
+      // half for X_{k-1}, first half for X_k) are therefore placed, two levels at a time, in
+      // the gaps between the four v_mfma, and scheduling barriers keep them there.
+      double tXp = 2.0, tX = 1.0;          // trace(X_{k-1}) (dummy for k = 0), trace(X_k)
+      double pend = 1.0 / 64.0;            // stage-1 partial of |X_{k-1}|_F^2 (sums to 1)
+      bool sqp = true;                     // with the above: trace(X_0) = 1 = trace(M/trace M)
       bool conv = false;
       for (int k = 0; k < MAX_PURIFY; ++k) {
-        const v4d y = mm16(x, x);
-        double td = 0.0, tf = 0.0;
+        v4d y = {0.0, 0.0, 0.0, 0.0};
+        y = __builtin_amdgcn_mfma_f64_16x16x4f64(x[0], x[0], y, 0, 0, 0);
+        double ra_ = pend + dpp_f64<0x122>(pend);
+        double b0 = x[0] * x[0], b1 = x[2] * x[2];
+        __builtin_amdgcn_sched_barrier(0);
+        ra_ = ra_ + dpp_f64<0x121>(ra_);
+        b0 = fma(x[1], x[1], b0);
+        b1 = fma(x[3], x[3], b1);
+        __builtin_amdgcn_sched_barrier(0);
+        y = __builtin_amdgcn_mfma_f64_16x16x4f64(x[1], x[1], y, 0, 0, 0);
+        const double a01 = lane_bcast(ra_, 0) + lane_bcast(ra_, 16);
+        const double a23 = lane_bcast(ra_, 32) + lane_bcast(ra_, 48);
+        double bsum = b0 + b1;
+        __builtin_amdgcn_sched_barrier(0);
+        const double tYp = a01 + a23;                      // |X_{k-1}|_F^2
+        bsum = bsum + dpp_f64<0x128>(bsum);
+        __builtin_amdgcn_sched_barrier(0);
+        y = __builtin_amdgcn_mfma_f64_16x16x4f64(x[2], x[2], y, 0, 0, 0);
+        tX = sqp ? tYp : fma(2.0, tXp, -tYp);
+        const double idem = tXp - tYp;
+        bsum = bsum + dpp_f64<0x124>(bsum);
+        __builtin_amdgcn_sched_barrier(0);
+        y = __builtin_amdgcn_mfma_f64_16x16x4f64(x[3], x[3], y, 0, 0, 0);
+        if (idem < 1e-8) {
+          // X_{k-1} is nearly idempotent: measure the current X exactly (the carried trace
+          // drifts by rounding) and stop if it is a projector to working precision
+          double td = 0.0;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          td += isdiag[r] ? x[r] : 0.0;
-          tf = fma(x[r], x[r], tf);
+          for (int r = 0; r < 4; ++r) td += isdiag[r] ? x[r] : 0.0;
+          tX = wave_sum(td);
+          const double tYe = fro2_stage2(fro2_stage1(x));
+          if (tX - tYe < 1e-13) { conv = true; break; }
         }
-        const double tX = wave_sum(td), tY = wave_sum(tf);   // trace(X), trace(X^2)
-        if (tX - tY < 1e-13) { conv = true; break; }
+        pend = bsum;
         ++steps;
-        const bool sq = fabs(tY - (double)mm) < fabs(2.0 * tX - tY - (double)mm);
+        const bool sq = tX > (double)mm;
+        if (sq) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) x[r] = sq ? y[r] : 2.0 * x[r] - y[r];
+          for (int r = 0; r < 4; ++r) x[r] = y[r];
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) x[r] = fma(2.0, x[r], -y[r]);
+        }
+        tXp = tX;
+        sqp = sq;
       }
       if (!conv) return 0;
     } else {
@@ -499,6 +571,10 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
 #pragma unroll
       for (int r = 0; r < 4; ++r) x[r] = (isdiag[r] && c16 < rank) ? 1.0 : 0.0;
     }
+#ifdef FA_K3_TIMING
+    const long long tc = clock64();
+    tk_pur += tc - tb;
+#endif
     // Z = (I - P) R, by columns into LDS
     v4d qm;
 #pragma unroll
@@ -532,6 +608,9 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     }
     wave_fence();
     const double obj = wave_sum(part);
+#ifdef FA_K3_TIMING
+    tk_res += clock64() - tc;
+#endif
     if (lane == 0) info->objective[it] = obj;
     iters_done = it + 1;
     const bool stop = it > 0 && fabs(prev_obj - obj) < tol;
@@ -588,6 +667,13 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     info->eigengap = nan("");        // filled in on demand by fa_get_info (needs eigenvalues)
     mlast[256] = (double)rank;
     mlast[257] = (double)m;
+#ifdef FA_K3_TIMING
+    info->objective[FA_ITERS_MAX - 1] = (double)(clock64() - tk0);
+    info->objective[FA_ITERS_MAX - 2] = (double)tk_pur;
+    info->objective[FA_ITERS_MAX - 3] = (double)tk_res;
+    info->objective[FA_ITERS_MAX - 4] = (double)tk_mm;
+    info->objective[FA_ITERS_MAX - 5] = (double)tk_setup;
+#endif
   }
   return 1;
 }

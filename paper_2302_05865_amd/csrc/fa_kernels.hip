@@ -17,6 +17,14 @@
 
 typedef double v4f64 __attribute__((ext_vector_type(4)));
 
+// tuning of the p <= 16 fp32 Gram kernel: columns per load instruction and waves per CU
+#ifndef FA_GRAM_CPL1
+#define FA_GRAM_CPL1 1
+#endif
+#ifndef FA_GRAM_W1
+#define FA_GRAM_W1 8
+#endif
+
 // ------------------------------------------------------------------------------------------
 // storage element types: 16 bytes per lane per load
 struct ElemF32 {
@@ -65,11 +73,40 @@ __device__ __forceinline__ uint4 load16_guarded(const unsigned char* base, int64
 // Products of fp32 (or bf16) inputs are exact in fp64 and the accumulation is fp64, which the
 // small differences 1 - v_i of the IRLS weights need.
 //
+// The operands of step t+1 are read from LDS and converted while the matrix core works on
+// step t (a wavefront issues in order; the dependent v_mfma leave room for exactly that).
+// LDS columns p..16T-1 are zeroed once and never written, so no masking is needed.
+//
+// Launch shape: one workgroup of FA_GRAM_WAVES_PER_CU wavefronts per compute unit, each
+// wavefront with its private LDS tile; the workgroup's LDS request is sized so that exactly
+// one fits per CU.  The tile assignment is static (reproducible sums), so an uneven placement
+// of workgroups would last for the whole kernel; this shape leaves the dispatcher no choice.
+//
 // T   = number of 16-column blocks (p <= 16 T)
 // CPL = columns covered by one load instruction (1: a wave reads 1 KiB of one column;
 //       4: 256 B of each of four columns, which keeps the LDS tile small for large p)
-template <int T, int CPL, typename E>
-__global__ __launch_bounds__(64) void fa_gram_kernel(const unsigned char* __restrict__ G,
+__device__ __forceinline__ void wave_lds_fence() {
+  // orders this wavefront's LDS accesses for the compiler; the hardware executes one
+  // wavefront's LDS instructions in order
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+template <typename E>
+__device__ __forceinline__ void unpack4(const unsigned char* src, double* x) {
+  if constexpr (E::SIZE == 4) {
+    const float4 f = *reinterpret_cast<const float4*>(src);
+    x[0] = (double)f.x; x[1] = (double)f.y; x[2] = (double)f.z; x[3] = (double)f.w;
+  } else {
+    const uint2 h = *reinterpret_cast<const uint2*>(src);
+    x[0] = (double)bf16_bits_to_f32(h.x & 0xffffu); x[1] = (double)bf16_bits_to_f32(h.x >> 16);
+    x[2] = (double)bf16_bits_to_f32(h.y & 0xffffu); x[3] = (double)bf16_bits_to_f32(h.y >> 16);
+  }
+}
+
+template <int T, int CPL, typename E, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
+                                                     const unsigned char* __restrict__ G,
                                                      int64_t ldg, int p, int64_t n,
                                                      int64_t ntiles,
                                                      double* __restrict__ partials) {
@@ -79,9 +116,14 @@ __global__ __launch_bounds__(64) void fa_gram_kernel(const unsigned char* __rest
   constexpr int NCG = T * 16 / CPL;        // load instructions per tile
   constexpr int CS = R * E::SIZE + 16;     // LDS bytes per column (+16: bank spread)
   constexpr int NTP = T * (T + 1) / 2;
-  __shared__ __attribute__((aligned(16))) unsigned char lds[T * 16 * CS];
+  constexpr int NSTEP = R / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
+  const int wave = threadIdx.x >> 6;
+  unsigned char* lds = lds_all + wave * (T * 16 * CS);
+  const int64_t wid = (int64_t)blockIdx.x * WAVES + wave;   // global wave index
+  const int64_t nwaves = (int64_t)gridDim.x * WAVES;
 
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63;
   const int lcol = lane / LPC;
   const int lrow = (lane % LPC) * EPL;
   const int c16 = lane & 15, kq = lane >> 4;
@@ -90,55 +132,57 @@ __global__ __launch_bounds__(64) void fa_gram_kernel(const unsigned char* __rest
 #pragma unroll
   for (int i = 0; i < NTP; ++i) acc[i] = v4f64{0.0, 0.0, 0.0, 0.0};
 
-  uint4 regs[NCG];
-  int64_t tile = blockIdx.x;
+  // zero the whole tile once: columns >= p stay zero for the life of the kernel
+  for (int off = lane * 16; off < T * 16 * CS; off += 64 * 16)
+    *reinterpret_cast<uint4*>(lds + off) = make_uint4(0u, 0u, 0u, 0u);
+
+  // this lane's source column for each load instruction (clamped: lanes of columns >= p
+  // re-read column p-1 and their data is dropped before the LDS write)
+  const unsigned char* colbase[NCG];
+  bool colon[NCG];
 #pragma unroll
   for (int cg = 0; cg < NCG; ++cg) {
     const int col = cg * CPL + lcol;
-    regs[cg] = make_uint4(0u, 0u, 0u, 0u);
-    if (col < p)
-      regs[cg] = load16_guarded<E>(G + (int64_t)col * ldg * E::SIZE, tile * R + lrow, n);
+    colon[cg] = col < p;
+    colbase[cg] = G + (int64_t)(colon[cg] ? col : p - 1) * ldg * E::SIZE;
   }
 
-  for (; tile < ntiles; tile += gridDim.x) {
-    __syncthreads();  // the previous tile's LDS reads are complete
+  uint4 regs[NCG];
+  auto load_tile = [&](int64_t tl) {
+    const int64_t row0 = tl * R + lrow;
+    if ((tl + 1) * R <= n) {               // uniform: a full tile needs no row guards
 #pragma unroll
-    for (int cg = 0; cg < NCG; ++cg) {
-      const int col = cg * CPL + lcol;
-      *reinterpret_cast<uint4*>(lds + col * CS + lrow * E::SIZE) = regs[cg];
+      for (int cg = 0; cg < NCG; ++cg)
+        regs[cg] = *reinterpret_cast<const uint4*>(colbase[cg] + row0 * E::SIZE);
+    } else {
+#pragma unroll
+      for (int cg = 0; cg < NCG; ++cg) regs[cg] = load16_guarded<E>(colbase[cg], row0, n);
     }
-    __syncthreads();
-    const int64_t next = tile + gridDim.x;
-    if (next < ntiles) {
+  };
+
+  wave_lds_fence();
+  int64_t tile = wid;
+  if (tile < ntiles) load_tile(tile);
+  for (; tile < ntiles; tile += nwaves) {
+    wave_lds_fence();  // the previous tile's LDS reads precede these writes
 #pragma unroll
-      for (int cg = 0; cg < NCG; ++cg) {
-        const int col = cg * CPL + lcol;
-        if (col < p)
-          regs[cg] = load16_guarded<E>(G + (int64_t)col * ldg * E::SIZE, next * R + lrow, n);
-      }
-    }
-#pragma unroll 2
-    for (int t = 0; t < R / 16; ++t) {
-      double x[T][4];
+    for (int cg = 0; cg < NCG; ++cg)
+      if (colon[cg])
+        *reinterpret_cast<uint4*>(lds + (cg * CPL + lcol) * CS + lrow * E::SIZE) = regs[cg];
+    wave_lds_fence();
+    const int64_t next = tile + nwaves;
+    if (next < ntiles) load_tile(next);
+
+    const unsigned char* src = lds + c16 * CS + 4 * kq * E::SIZE;
+    double xc[T][4], xn[T][4];
 #pragma unroll
-      for (int tt = 0; tt < T; ++tt) {
-        const int col = tt * 16 + c16;
-        const unsigned char* src = lds + col * CS + (16 * t + 4 * kq) * E::SIZE;
-        float f0, f1, f2, f3;
-        if constexpr (E::SIZE == 4) {
-          const float4 f = *reinterpret_cast<const float4*>(src);
-          f0 = f.x; f1 = f.y; f2 = f.z; f3 = f.w;
-        } else {
-          const uint2 h = *reinterpret_cast<const uint2*>(src);
-          f0 = bf16_bits_to_f32(h.x & 0xffffu); f1 = bf16_bits_to_f32(h.x >> 16);
-          f2 = bf16_bits_to_f32(h.y & 0xffffu); f3 = bf16_bits_to_f32(h.y >> 16);
-        }
-        const bool on = col < p;   // columns past p hold stale LDS contents
-        x[tt][0] = on ? (double)f0 : 0.0;
-        x[tt][1] = on ? (double)f1 : 0.0;
-        x[tt][2] = on ? (double)f2 : 0.0;
-        x[tt][3] = on ? (double)f3 : 0.0;
-      }
+    for (int tt = 0; tt < T; ++tt) unpack4<E>(src + tt * 16 * CS, xc[tt]);
+#pragma unroll 4
+    for (int t = 0; t < NSTEP; ++t) {
+      // operands of the next step (the last step re-reads step 0; harmless)
+      const int tn = (t + 1 < NSTEP) ? t + 1 : 0;
+#pragma unroll
+      for (int tt = 0; tt < T; ++tt) unpack4<E>(src + tt * 16 * CS + 16 * tn * E::SIZE, xn[tt]);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         int tp = 0;
@@ -146,15 +190,19 @@ __global__ __launch_bounds__(64) void fa_gram_kernel(const unsigned char* __rest
         for (int a = 0; a < T; ++a)
 #pragma unroll
           for (int b = a; b < T; ++b) {
-            acc[tp] = __builtin_amdgcn_mfma_f64_16x16x4f64(x[a][j], x[b][j], acc[tp], 0, 0, 0);
+            acc[tp] = __builtin_amdgcn_mfma_f64_16x16x4f64(xc[a][j], xc[b][j], acc[tp], 0, 0, 0);
             ++tp;
           }
       }
+#pragma unroll
+      for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xc[tt][j] = xn[tt][j];
     }
   }
 
   // accumulator register r of lane l is entry (row 4*r + l/16, column l%16) of the block
-  double* dst = partials + (int64_t)blockIdx.x * NTP * 256;
+  double* dst = partials + wid * NTP * 256;
 #pragma unroll
   for (int tp = 0; tp < NTP; ++tp)
 #pragma unroll
@@ -317,15 +365,30 @@ size_t fa_irls_lds_bytes(int p, int* big_in_global) {
 
 // ------------------------------------------------------------------------------------------
 // launchers (host).  Shapes are validated by the callers in fa_api.cpp.
-template <int T, int CPL, typename E>
+template <int T, int CPL, typename E, int WAVES>
 static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
                                 double* partials, int* nparts, hipStream_t st) {
+  static_assert(WAVES <= FA_GRAM_WAVES_PER_CU, "partials buffer is sized for this many");
   constexpr int R = (64 / CPL) * E::EPL;
+  constexpr int CS = R * E::SIZE + 16;
+  constexpr size_t tile_bytes = (size_t)T * 16 * CS;
+  static_assert(WAVES * tile_bytes <= 160 * 1024, "LDS tiles of one workgroup must fit a CU");
+  // more than half of the CU's 160 KiB, so that no second workgroup fits beside this one
+  const size_t lds_bytes = WAVES * tile_bytes > 84 * 1024 ? WAVES * tile_bytes : 84 * 1024;
+  static bool prepared = false;
+  if (!prepared) {
+    hipError_t e =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(fa_gram_kernel<T, CPL, E, WAVES>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    prepared = true;
+  }
   const int64_t ntiles = (n + R - 1) / R;
-  const int blocks = (int)(ntiles < max_blocks ? ntiles : max_blocks);
-  *nparts = blocks;
-  hipLaunchKernelGGL((fa_gram_kernel<T, CPL, E>), dim3(blocks), dim3(64), 0, st,
-                     (const unsigned char*)G, ldg, p, n, ntiles, partials);
+  int64_t wgs = (ntiles + WAVES - 1) / WAVES;
+  if (wgs > max_blocks) wgs = max_blocks;
+  *nparts = (int)wgs * WAVES;
+  hipLaunchKernelGGL((fa_gram_kernel<T, CPL, E, WAVES>), dim3((unsigned)wgs), dim3(64 * WAVES),
+                     lds_bytes, st, (const unsigned char*)G, ldg, p, n, ntiles, partials);
   return hipGetLastError();
 }
 
@@ -336,17 +399,17 @@ hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n,
   hipError_t e = hipErrorInvalidValue;
   if (dtype == FA_F32) {
     switch (T) {
-      case 1: e = launch_gram_t<1, 1, ElemF32>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 2: e = launch_gram_t<2, 4, ElemF32>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 3: e = launch_gram_t<3, 4, ElemF32>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 4: e = launch_gram_t<4, 4, ElemF32>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 1: e = launch_gram_t<1, FA_GRAM_CPL1, ElemF32, FA_GRAM_W1>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 2: e = launch_gram_t<2, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 3: e = launch_gram_t<3, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 4: e = launch_gram_t<4, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
     }
   } else {
     switch (T) {
-      case 1: e = launch_gram_t<1, 1, ElemBF16>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 2: e = launch_gram_t<2, 4, ElemBF16>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 3: e = launch_gram_t<3, 4, ElemBF16>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 4: e = launch_gram_t<4, 4, ElemBF16>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 1: e = launch_gram_t<1, 1, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 2: e = launch_gram_t<2, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 3: e = launch_gram_t<3, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 4: e = launch_gram_t<4, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
     }
   }
   return e;
