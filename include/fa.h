@@ -133,10 +133,11 @@ fa_status fa_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, fl
 
 /*
  * Per-kernel timing of fa_aggregate with HIP events on the context's stream.
- * fa_set_profiling(ctx, 1) makes every later fa_aggregate record events around its
- * kernels; fa_get_timings synchronises and returns the last call's durations in
- * milliseconds: ms[0] Gram pass, ms[1] partial reduction, ms[2] p x p IRLS,
- * ms[3] aggregate pass.
+ * fa_set_profiling(ctx, 1) makes every later fa_aggregate attach a begin and an end event
+ * to each of its kernel dispatches (the events carry the kernel's own timestamps; nothing
+ * extra is enqueued between the kernels); fa_get_timings synchronises and returns the last
+ * call's kernel durations in milliseconds: ms[0] Gram pass, ms[1] partial reduction,
+ * ms[2] p x p IRLS, ms[3] aggregate pass.
  */
 fa_status fa_set_profiling(fa_ctx* ctx, int enabled);
 fa_status fa_get_timings(fa_ctx* ctx, float ms[4]);

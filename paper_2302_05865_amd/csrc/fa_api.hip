@@ -16,7 +16,7 @@ struct fa_ctx {
   int num_cus;
   int gram_max_blocks;
   int combine_max_blocks;
-  double* partials;   // gram_max_blocks * FA_GRAM_WAVES_PER_CU * NTP(p_max) * 256
+  double* partials;   // gram_max_blocks * NTP(p_max) * 256
   double* Kd;         // FA_P_MAX^2
   double* cd;         // FA_P_MAX
   double* gws;        // 2 * FA_P_MAX * (FA_P_MAX + 1)
@@ -26,7 +26,7 @@ struct fa_ctx {
   int profiling;
   int solver;         // FA_IRLS_SOLVER in the environment: 0 default, 1 = p<=16 Jacobi path,
                       // 2 = any-p Jacobi kernel (testing)
-  hipEvent_t ev[5];
+  fa_ktime tm[4];     // per-kernel begin/end events (profiling)
   int ev_recorded;
 };
 
@@ -81,8 +81,7 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   c->combine_max_blocks = 1 << 20;
   const int T = (cfg->p_max + 15) / 16;
   const size_t ntp = (size_t)T * (T + 1) / 2;
-  const size_t part_bytes =
-      (size_t)c->gram_max_blocks * FA_GRAM_WAVES_PER_CU * ntp * 256 * sizeof(double);
+  const size_t part_bytes = (size_t)c->gram_max_blocks * ntp * 256 * sizeof(double);
   bool ok = true;
   ok = ok && hipMalloc((void**)&c->partials, part_bytes) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->Kd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;
@@ -92,8 +91,9 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   ok = ok && hipMalloc((void**)&c->info_d, sizeof(fa_info)) == hipSuccess;
   if (!ok) { fa_destroy(c); return FA_ERR_ALLOC; }
   if (hipMemset(c->info_d, 0, sizeof(fa_info)) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
-  for (int i = 0; i < 5; ++i)
-    if (hipEventCreate(&c->ev[i]) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
+  for (int i = 0; i < 4; ++i)
+    if (hipEventCreate(&c->tm[i].start) != hipSuccess ||
+        hipEventCreate(&c->tm[i].stop) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
   if (fa_irls_prepare() != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
   *out_ctx = c;
   return FA_OK;
@@ -107,8 +107,10 @@ extern "C" void fa_destroy(fa_ctx* c) {
   if (c->cd) (void)hipFree(c->cd);
   if (c->gws) (void)hipFree(c->gws);
   if (c->info_d) (void)hipFree(c->info_d);
-  for (int i = 0; i < 5; ++i)
-    if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+  for (int i = 0; i < 4; ++i) {
+    if (c->tm[i].start) (void)hipEventDestroy(c->tm[i].start);
+    if (c->tm[i].stop) (void)hipEventDestroy(c->tm[i].stop);
+  }
   delete c;
 }
 
@@ -143,29 +145,24 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   hipStream_t st = c->stream;
   const bool prof = c->profiling != 0;
   c->ev_recorded = 0;
-  if (prof && hipEventRecord(c->ev[0], st) != hipSuccess) return FA_ERR_DEVICE;
-  // S1: norms and Gram matrix, per-wave partials;  S2: their fixed-order sum
+  // S1: norms and Gram matrix, per-workgroup partials;  S2: their fixed-order sum
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
-                              &nparts, st) != hipSuccess)
+                              &nparts, st, prof ? &c->tm[0] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
-  if (prof && hipEventRecord(c->ev[1], st) != hipSuccess) return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st) != hipSuccess)
-    return FA_ERR_DEVICE;
-  if (prof && hipEventRecord(c->ev[2], st) != hipSuccess) return FA_ERR_DEVICE;
-  // S3-S5: p x p IRLS and coefficients
-  if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, st) != hipSuccess)
-    return FA_ERR_DEVICE;
-  if (prof && hipEventRecord(c->ev[3], st) != hipSuccess) return FA_ERR_DEVICE;
-  // S6: out = G c
-  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks, st) !=
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, prof ? &c->tm[1] : nullptr) !=
       hipSuccess)
     return FA_ERR_DEVICE;
-  if (prof) {
-    if (hipEventRecord(c->ev[4], st) != hipSuccess) return FA_ERR_DEVICE;
-    c->ev_recorded = 1;
-  }
+  // S3-S5: p x p IRLS and coefficients
+  if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, st,
+                     prof ? &c->tm[2] : nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  // S6: out = G c
+  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks, st,
+                        prof ? &c->tm[3] : nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (prof) c->ev_recorded = 1;
   c->has_solution = 1;
   c->last_p = p;
   c->last_m = m;
@@ -195,9 +192,9 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
   if (!check_matrix_args(c, G, ldg, p, n) || !K_host) return FA_ERR_ARG;
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
-                              &nparts, c->stream) != hipSuccess)
+                              &nparts, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream) != hipSuccess)
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
   if (hipMemcpy(K_host, c->Kd, sizeof(double) * p * p, hipMemcpyDeviceToHost) != hipSuccess)
@@ -213,7 +210,8 @@ extern "C" fa_status fa_irls(fa_ctx* c, const double* K_host, int p, int m, doub
   if (hipMemcpy(c->Kd, K_host, sizeof(double) * p * p, hipMemcpyHostToDevice) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, c->stream) != hipSuccess)
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, c->stream, nullptr) !=
+      hipSuccess)
     return FA_ERR_DEVICE;
   c->has_solution = 1;
   c->last_p = p;
@@ -229,7 +227,7 @@ extern "C" fa_status fa_combine(fa_ctx* c, const void* G, int64_t ldg, int p, in
   if (hipMemcpy(c->cd, c_host, sizeof(double) * p, hipMemcpyHostToDevice) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks,
-                        c->stream) != hipSuccess)
+                        c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   return FA_OK;
 }
@@ -245,7 +243,7 @@ extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int6
                                                     offsetof(fa_info, A));
   for (int a = 0; a < m; ++a)
     if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, A + a, m, Y + (int64_t)a * ldy,
-                          c->combine_max_blocks, c->stream) != hipSuccess)
+                          c->combine_max_blocks, c->stream, nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
   return FA_OK;
 }
@@ -260,8 +258,9 @@ extern "C" fa_status fa_set_profiling(fa_ctx* c, int enabled) {
 extern "C" fa_status fa_get_timings(fa_ctx* c, float ms[4]) {
   if (!c || !ms) return FA_ERR_ARG;
   if (!c->ev_recorded) return FA_ERR_ARG;
-  if (hipEventSynchronize(c->ev[4]) != hipSuccess) return FA_ERR_DEVICE;
+  if (hipEventSynchronize(c->tm[3].stop) != hipSuccess) return FA_ERR_DEVICE;
   for (int k = 0; k < 4; ++k)
-    if (hipEventElapsedTime(&ms[k], c->ev[k], c->ev[k + 1]) != hipSuccess) return FA_ERR_DEVICE;
+    if (hipEventElapsedTime(&ms[k], c->tm[k].start, c->tm[k].stop) != hipSuccess)
+      return FA_ERR_DEVICE;
   return FA_OK;
 }

@@ -4,30 +4,37 @@
 #define FA_INTERNAL_H_
 
 #include <hip/hip_runtime_api.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
 #include "fa.h"
 
 #define FA_IRLS_THREADS 256   // workgroup size of the p x p solver
+
+// Optional per-kernel timing: when a launcher gets a non-null fa_ktime, the kernel is
+// launched with these events attached to the dispatch itself (they carry the kernel's own
+// begin/end timestamps; no marker packets are put between the kernels).
+typedef struct { hipEvent_t start, stop; } fa_ktime;
 #define FA_GRAM_WAVES_PER_CU 16 // most wavefronts a Gram workgroup (one per compute unit) has
 
-// K1: partial Grams of G, one per launched wavefront, into `partials` (up to max_blocks *
-// FA_GRAM_WAVES_PER_CU * T(T+1)/2 * 256 doubles, T = ceil(p/16)); max_blocks = workgroups
-// (one per compute unit); *nparts receives how many partials were written.
+// K1: partial Grams of G, one per launched workgroup, into `partials` (up to max_blocks *
+// T(T+1)/2 * 256 doubles, T = ceil(p/16)); max_blocks = workgroups (one per compute unit);
+// *nparts receives how many partials were written.
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int max_blocks, double* partials, int* nparts,
-                                   hipStream_t st);
+                                   hipStream_t st, const fa_ktime* tm);
 // K2: their fixed-order sum into Kd (p*p doubles, row-major).
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
-                                 hipStream_t st);
+                                 hipStream_t st, const fa_ktime* tm);
 
 // K3: p x p solver.  Kd p*p doubles; cd p doubles out; info_d device fa_info; gws global
 // workspace of 2*FA_P_MAX*(FA_P_MAX+1) + 258 doubles.  solver: 0 = default (p <= 16:
 // purification with Jacobi fallback), 1 = p <= 16 Jacobi path, 2 = any-p Jacobi kernel.
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double* cd,
-                          fa_info* info_d, double* gws, int solver, hipStream_t st);
+                          fa_info* info_d, double* gws, int solver, hipStream_t st,
+                          const fa_ktime* tm);
 hipError_t fa_irls_prepare(void);
 // K3 for p <= 16 (latency-tuned single-workgroup solver, static LDS).
 // mlast: 258 doubles; the fast path leaves the last weighted-PCA matrix there (16 x 16, then
@@ -35,13 +42,22 @@ hipError_t fa_irls_prepare(void);
 hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int iters, double tol,
                             double delta, double rank_tol, double pair_tol, double* cd,
                             fa_info* info_d, double* mlast, int use_purification,
-                            hipStream_t st);
+                            hipStream_t st, const fa_ktime* tm);
 // eigengap (mu_m - mu_{m+1}) / mu_1 of the matrix left in mlast, into info_d->eigengap.
 hipError_t fa_launch_gap(const double* mlast, fa_info* info_d, hipStream_t st);
 
 // K4: out = sum_i c[i*cstride] g_i.
 hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                              const double* c, int cstride, float* out, int max_blocks,
-                             hipStream_t st);
+                             hipStream_t st, const fa_ktime* tm);
+
+
+#define FA_LAUNCH(tm, kern, grid, block, lds, st, ...)                                          \
+  do {                                                                                           \
+    if (tm)                                                                                      \
+      hipExtLaunchKernelGGL(kern, grid, block, lds, st, (tm)->start, (tm)->stop, 0, __VA_ARGS__); \
+    else                                                                                         \
+      hipLaunchKernelGGL(kern, grid, block, lds, st, __VA_ARGS__);                               \
+  } while (0)
 
 #endif

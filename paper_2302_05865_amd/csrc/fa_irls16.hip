@@ -509,51 +509,37 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
       // Steering: square when trace(X) > m, else X <- 2X - X^2.  trace(X) is carried along
       // (after a square it is the previous |X|_F^2, otherwise 2 trace(X) - |X|_F^2), so the
       // only reduction per step is |X|_F^2, and its result is not needed before the end of
-      // the *next* step.  A wavefront issues in order and fp64 vector operations have a
-      // dependent latency of ~32 cycles, while each of the four dependent matrix-core
-      // instructions of X^2 holds the issue port for 64: the two reduction chains (second
-      // half for X_{k-1}, first half for X_k) are therefore placed, two levels at a time, in
-      // the gaps between the four v_mfma, and scheduling barriers keep them there.
+      // the *next* step: a wavefront issues in order and fp64 vector operations have a long
+      // dependent latency, so the reduction is split in two halves (second half for X_{k-1},
+      // first half for X_k) that sit beside the four matrix-core instructions of X_k^2.
       double tXp = 2.0, tX = 1.0;          // trace(X_{k-1}) (dummy for k = 0), trace(X_k)
-      double pend = 1.0 / 64.0;            // stage-1 partial of |X_{k-1}|_F^2 (sums to 1)
+      double pend = 1.0 / 16.0;            // stage-1 partial of |X_{k-1}|_F^2 (stage 2 sums to 1)
       bool sqp = true;                     // with the above: trace(X_0) = 1 = trace(M/trace M)
       bool conv = false;
+      bool near = false;                   // X_{k-2} was nearly idempotent
       for (int k = 0; k < MAX_PURIFY; ++k) {
-        v4d y = {0.0, 0.0, 0.0, 0.0};
-        y = __builtin_amdgcn_mfma_f64_16x16x4f64(x[0], x[0], y, 0, 0, 0);
-        double ra_ = pend + dpp_f64<0x122>(pend);
-        double b0 = x[0] * x[0], b1 = x[2] * x[2];
-        __builtin_amdgcn_sched_barrier(0);
-        ra_ = ra_ + dpp_f64<0x121>(ra_);
-        b0 = fma(x[1], x[1], b0);
-        b1 = fma(x[3], x[3], b1);
-        __builtin_amdgcn_sched_barrier(0);
-        y = __builtin_amdgcn_mfma_f64_16x16x4f64(x[1], x[1], y, 0, 0, 0);
-        const double a01 = lane_bcast(ra_, 0) + lane_bcast(ra_, 16);
-        const double a23 = lane_bcast(ra_, 32) + lane_bcast(ra_, 48);
-        double bsum = b0 + b1;
-        __builtin_amdgcn_sched_barrier(0);
-        const double tYp = a01 + a23;                      // |X_{k-1}|_F^2
-        bsum = bsum + dpp_f64<0x128>(bsum);
-        __builtin_amdgcn_sched_barrier(0);
-        y = __builtin_amdgcn_mfma_f64_16x16x4f64(x[2], x[2], y, 0, 0, 0);
-        tX = sqp ? tYp : fma(2.0, tXp, -tYp);
-        const double idem = tXp - tYp;
-        bsum = bsum + dpp_f64<0x124>(bsum);
-        __builtin_amdgcn_sched_barrier(0);
-        y = __builtin_amdgcn_mfma_f64_16x16x4f64(x[3], x[3], y, 0, 0, 0);
-        if (idem < 1e-8) {
-          // X_{k-1} is nearly idempotent: measure the current X exactly (the carried trace
-          // drifts by rounding) and stop if it is a projector to working precision
+        if (near) {
+          // measure the current X exactly (the carried trace drifts by rounding) and stop
+          // if it is a projector to working precision
           double td = 0.0;
 #pragma unroll
           for (int r = 0; r < 4; ++r) td += isdiag[r] ? x[r] : 0.0;
           tX = wave_sum(td);
-          const double tYe = fro2_stage2(fro2_stage1(x));
-          if (tX - tYe < 1e-13) { conv = true; break; }
+          pend = fro2_stage1(x);
+          if (tX - fro2_stage2(pend) < 1e-13) {
+            // idempotent; it is the wanted projector only if its trace is m (the maps are
+            // monotone, so the eigenvalue order is kept whatever the steering did)
+            conv = fabs(tX - (double)mm) < 0.25;
+            break;
+          }
+          // resynchronise the carried quantities on the exact values
+          tXp = 2.0; sqp = true; pend = tX * (1.0 / 16.0);
         }
-        pend = bsum;
-        ++steps;
+        const v4d y = mm16(x, x);
+        const double tYp = fro2_stage2(pend);              // |X_{k-1}|_F^2
+        pend = fro2_stage1(x);
+        tX = sqp ? tYp : fma(2.0, tXp, -tYp);
+        near = (tXp - tYp < 1e-8);
         const bool sq = tX > (double)mm;
         if (sq) {
 #pragma unroll
@@ -564,6 +550,7 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
         }
         tXp = tX;
         sqp = sq;
+        steps = steps + 1;
       }
       if (!conv) return 0;
     } else {
@@ -915,8 +902,8 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
 hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int iters, double tol,
                             double delta, double rank_tol, double pair_tol, double* cd,
                             fa_info* info_d, double* mlast, int use_purification,
-                            hipStream_t st) {
-  hipLaunchKernelGGL(fa_irls16_kernel, dim3(1), dim3(256), 0, st, Kd, p, m, iters, lambda, tol,
-                     delta, rank_tol, pair_tol, cd, info_d, mlast, use_purification);
+                            hipStream_t st, const fa_ktime* tm) {
+  FA_LAUNCH(tm, fa_irls16_kernel, dim3(1), dim3(256), 0, st, Kd, p, m, iters, lambda, tol, delta,
+            rank_tol, pair_tol, cd, info_d, mlast, use_purification);
   return hipGetLastError();
 }

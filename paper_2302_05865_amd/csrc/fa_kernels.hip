@@ -201,36 +201,66 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
     }
   }
 
-  // accumulator register r of lane l is entry (row 4*r + l/16, column l%16) of the block
-  double* dst = partials + wid * NTP * 256;
+  // accumulator register r of lane l is entry (row 4*r + l/16, column l%16) of the block.
+  // The workgroup's wavefronts add up in wave order through LDS (the tiles are dead now),
+  // one partial Gram per workgroup leaves the kernel.
+  __syncthreads();
+  double* red = reinterpret_cast<double*>(lds_all);   // WAVES * 256 doubles <= 32 KiB
+  double* dst = partials + (int64_t)blockIdx.x * NTP * 256;
 #pragma unroll
-  for (int tp = 0; tp < NTP; ++tp)
+  for (int tp = 0; tp < NTP; ++tp) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) dst[(tp * 4 + r) * 64 + lane] = acc[tp][r];
+    for (int r = 0; r < 4; ++r) red[wave * 256 + r * 64 + lane] = acc[tp][r];
+    __syncthreads();
+    for (int e = threadIdx.x; e < 256; e += 64 * WAVES) {
+      double tot = 0.0;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) tot += red[w * 256 + e];
+      dst[tp * 256 + e] = tot;
+    }
+    __syncthreads();
+  }
 }
 
-// K2: K = sum over waves of their partial Grams, in a fixed order (32 interleaved strands of
-// sequential sums, then the strands in order), so the result does not depend on timing.
-__global__ __launch_bounds__(256) void fa_gram_reduce_kernel(const double* __restrict__ partials,
-                                                             int nparts, int T, int p,
-                                                             double* __restrict__ K) {
+// K2: K = sum over workgroups of their partial Grams, in a fixed order (sixteen interleaved
+// strands, each summed in four interleaved sub-strands, then combined in a fixed tree), so the
+// result does not depend on timing.  One 1024-thread block per 64 entries.
+__global__ __launch_bounds__(1024) void fa_gram_reduce_kernel(const double* __restrict__ partials,
+                                                              int nparts, int T, int p,
+                                                              double* __restrict__ K) {
   const int NTP = T * (T + 1) / 2;
-  const int ei = threadIdx.x & 7, g = threadIdx.x >> 3;
-  const int E = blockIdx.x * 8 + ei;  // entry in [0, NTP*256)
-  double acc = 0.0;
-  for (int b = g; b < nparts; b += 32) acc += partials[(int64_t)b * NTP * 256 + E];
-  __shared__ double sh[256];
-  sh[threadIdx.x] = acc;
+  const int ei = threadIdx.x & 63, g = threadIdx.x >> 6;   // entry, strand 0..15
+  const int E = blockIdx.x * 64 + ei;                      // entry in [0, NTP*256)
+  const int64_t stride = (int64_t)NTP * 256;
+  double a[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int b0 = g; b0 < nparts; b0 += 64) {
+    double v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int b = b0 + 16 * u;
+      v[u] = b < nparts ? partials[(int64_t)b * stride + E] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) a[u] += v[u];
+  }
+  __shared__ double sh[1024];
+  sh[threadIdx.x] = (a[0] + a[1]) + (a[2] + a[3]);
   __syncthreads();
-  if (g == 0 && E < NTP * 256) {
-    double tot = 0.0;
-    for (int gg = 0; gg < 32; ++gg) tot += sh[gg * 8 + ei];
-    int tp = E >> 8, e = E & 255;
+  if (g == 0) {
+    double t[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) t[k] = sh[k * 64 + ei];
+#pragma unroll
+    for (int w = 8; w >= 1; w >>= 1)
+#pragma unroll
+      for (int k = 0; k < w; ++k) t[k] += t[k + w];
+    const double tot = t[0];
+    const int tp = E >> 8, e = E & 255;
     const int r = e >> 6, l = e & 63;
     int ta = 0, tb = 0;
-    for (int a = 0, k = 0; a < T; ++a)
-      for (int b = a; b < T; ++b, ++k)
-        if (k == tp) { ta = a; tb = b; }
+    for (int aa = 0, k = 0; aa < T; ++aa)
+      for (int bb = aa; bb < T; ++bb, ++k)
+        if (k == tp) { ta = aa; tb = bb; }
     const int gi = ta * 16 + 4 * r + (l >> 4), gj = tb * 16 + (l & 15);
     if (gi < p && gj < p && gi <= gj) {
       K[gi * p + gj] = tot;
@@ -242,6 +272,9 @@ __global__ __launch_bounds__(256) void fa_gram_reduce_kernel(const double* __res
 // ------------------------------------------------------------------------------------------
 // K4: out[k] = sum_i c[i] G[k][i]  (Alg. 1: d = (1/p) Y Y^T G 1 = G c).  Each thread owns 16
 // bytes of every column (coalesced), accumulates in fp64 and writes fp32.
+// Rows are walked from the end of G towards the beginning: the Gram pass walks them the
+// other way, so the rows it touched last are still in the memory-side cache when this pass
+// starts with them.
 template <typename E>
 __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __restrict__ G,
                                                          int64_t ldg, int p, int64_t n,
@@ -255,7 +288,7 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
   const int64_t ngroups = (n + EPL - 1) / EPL;
   for (int64_t gidx = (int64_t)blockIdx.x * 256 + threadIdx.x; gidx < ngroups;
        gidx += (int64_t)gridDim.x * 256) {
-    const int64_t row0 = gidx * EPL;
+    const int64_t row0 = (ngroups - 1 - gidx) * EPL;
     double acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.0;
@@ -367,7 +400,8 @@ size_t fa_irls_lds_bytes(int p, int* big_in_global) {
 // launchers (host).  Shapes are validated by the callers in fa_api.cpp.
 template <int T, int CPL, typename E, int WAVES>
 static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
-                                double* partials, int* nparts, hipStream_t st) {
+                                double* partials, int* nparts, hipStream_t st,
+                                const fa_ktime* tm) {
   static_assert(WAVES <= FA_GRAM_WAVES_PER_CU, "partials buffer is sized for this many");
   constexpr int R = (64 / CPL) * E::EPL;
   constexpr int CS = R * E::SIZE + 16;
@@ -386,57 +420,58 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
   const int64_t ntiles = (n + R - 1) / R;
   int64_t wgs = (ntiles + WAVES - 1) / WAVES;
   if (wgs > max_blocks) wgs = max_blocks;
-  *nparts = (int)wgs * WAVES;
-  hipLaunchKernelGGL((fa_gram_kernel<T, CPL, E, WAVES>), dim3((unsigned)wgs), dim3(64 * WAVES),
-                     lds_bytes, st, (const unsigned char*)G, ldg, p, n, ntiles, partials);
+  *nparts = (int)wgs;
+  FA_LAUNCH(tm, (fa_gram_kernel<T, CPL, E, WAVES>), dim3((unsigned)wgs), dim3(64 * WAVES),
+            lds_bytes, st, (const unsigned char*)G, ldg, p, n, ntiles, partials);
   return hipGetLastError();
 }
 
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int max_blocks, double* partials, int* nparts,
-                                   hipStream_t st) {
+                                   hipStream_t st, const fa_ktime* tm) {
   const int T = (p + 15) / 16;
   hipError_t e = hipErrorInvalidValue;
   if (dtype == FA_F32) {
     switch (T) {
-      case 1: e = launch_gram_t<1, FA_GRAM_CPL1, ElemF32, FA_GRAM_W1>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 2: e = launch_gram_t<2, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 3: e = launch_gram_t<3, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 4: e = launch_gram_t<4, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 1: e = launch_gram_t<1, FA_GRAM_CPL1, ElemF32, FA_GRAM_W1>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
+      case 2: e = launch_gram_t<2, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
+      case 3: e = launch_gram_t<3, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
+      case 4: e = launch_gram_t<4, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
     }
   } else {
     switch (T) {
-      case 1: e = launch_gram_t<1, 1, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 2: e = launch_gram_t<2, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 3: e = launch_gram_t<3, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
-      case 4: e = launch_gram_t<4, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st); break;
+      case 1: e = launch_gram_t<1, 1, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
+      case 2: e = launch_gram_t<2, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
+      case 3: e = launch_gram_t<3, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
+      case 4: e = launch_gram_t<4, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
     }
   }
   return e;
 }
 
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
-                                 hipStream_t st) {
+                                 hipStream_t st, const fa_ktime* tm) {
   const int T = (p + 15) / 16;
   const int NTP = T * (T + 1) / 2;
-  hipLaunchKernelGGL(fa_gram_reduce_kernel, dim3(NTP * 32), dim3(256), 0, st, partials, nparts, T,
-                     p, Kd);
+  FA_LAUNCH(tm, fa_gram_reduce_kernel, dim3(NTP * 4), dim3(1024), 0, st, partials, nparts, T, p,
+            Kd);
   return hipGetLastError();
 }
 
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double* cd,
-                          fa_info* info_d, double* gws, int solver, hipStream_t st) {
+                          fa_info* info_d, double* gws, int solver, hipStream_t st,
+                          const fa_ktime* tm) {
   if (p <= 16 && solver != 2)
     return fa_launch_irls16(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d,
-                            gws + 2 * FA_P_MAX * (FA_P_MAX + 1), solver == 0 ? 1 : 0, st);
+                            gws + 2 * FA_P_MAX * (FA_P_MAX + 1), solver == 0 ? 1 : 0, st, tm);
   fa_irls_args ar;
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
   ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
   int big = 0;
   const size_t lds = fa_irls_lds_bytes(p, &big);
-  hipLaunchKernelGGL(fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d,
-                     gws, big);
+  FA_LAUNCH(tm, fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d, gws,
+            big);
   return hipGetLastError();
 }
 
@@ -480,16 +515,16 @@ hipError_t fa_irls_prepare(void) {
 
 hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                              const double* c, int cstride, float* out, int max_blocks,
-                             hipStream_t st) {
+                             hipStream_t st, const fa_ktime* tm) {
   const int epl = dtype == FA_F32 ? 4 : 8;
   const int64_t ngroups = (n + epl - 1) / epl;
   int64_t blocks = (ngroups + 255) / 256;
   if (blocks > max_blocks) blocks = max_blocks;
   if (dtype == FA_F32)
-    hipLaunchKernelGGL((fa_combine_kernel<ElemF32>), dim3((unsigned)blocks), dim3(256), 0, st,
-                       (const unsigned char*)G, ldg, p, n, c, cstride, out);
+    FA_LAUNCH(tm, (fa_combine_kernel<ElemF32>), dim3((unsigned)blocks), dim3(256), 0, st,
+              (const unsigned char*)G, ldg, p, n, c, cstride, out);
   else
-    hipLaunchKernelGGL((fa_combine_kernel<ElemBF16>), dim3((unsigned)blocks), dim3(256), 0, st,
-                       (const unsigned char*)G, ldg, p, n, c, cstride, out);
+    FA_LAUNCH(tm, (fa_combine_kernel<ElemBF16>), dim3((unsigned)blocks), dim3(256), 0, st,
+              (const unsigned char*)G, ldg, p, n, c, cstride, out);
   return hipGetLastError();
 }
