@@ -5,6 +5,14 @@ One "step" = one whole aggregation (Gram pass, partial reduction, p x p IRLS, ag
 pass) of the cfg2 workload: p = 15 worker gradients of n = 11.2M fp32 elements, m = 8,
 lambda = 1, 20 IRLS solves, synthetic seeded input already resident in HBM.
 Prints ONE JSON line.
+
+Timed regions (all with HIP events / a synchronised wall clock on the stream the library
+launches on):
+  1. `--steps` whole aggregations                  -> value (aggregations/s), ms_per_step
+  2. the same steps again with begin/end events attached to every kernel dispatch
+                                                  -> kernels{...}.ms_in_step
+  3. each kernel alone, `--steps` launches between two events
+                                                  -> kernels{...}.ms, roofline.achieved
 """
 import argparse
 import json
@@ -18,6 +26,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 
+# HBM traffic of the two streaming kernels per launch, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script (profiles/pmc_cfg2.md: counter values, calibration
+# against a plain copy of known size, and the commands).
+MEASURED_TRAFFIC_BYTES = {"fa_gram_kernel": 6.726e8, "fa_combine_kernel": 7.168e8}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -27,6 +40,9 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--n", type=int, default=0, help="override n (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times (gives the PMC byte "
+                         "counters a kernel of known traffic to be scaled against)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (the parameter server's aggregation step on "
@@ -43,6 +59,7 @@ def main() -> int:
     if args.n:
         w = w.with_n(args.n)
     torch.cuda.set_device(0)
+
     def upload(host):
         if host.dtype == np.uint16:
             return torch.from_numpy(host.view(np.int16)).cuda().view(torch.bfloat16)
@@ -57,7 +74,6 @@ def main() -> int:
     gen_s = time.time() - t0
     devs = [upload(Gw), upload(Gw1)]
     del Gw1
-    dev = devs[0]
     out = torch.empty(w.n, dtype=torch.float32, device="cuda")
     agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype)
     counter = [0]
@@ -67,6 +83,7 @@ def main() -> int:
         counter[0] += 1
         agg.fa_aggregate(g, w.m, w.lam, w.iters, 0.0, out=out)
 
+    # ---- region 1: whole aggregations -------------------------------------------------------
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -78,49 +95,78 @@ def main() -> int:
     ms_per_step = 1e3 * elapsed / args.steps
     value = args.steps / elapsed
 
-    # per-kernel durations: HIP events recorded by the library on the stream it launches on
+    # ---- region 2: per-dispatch events inside the step --------------------------------------
     agg.fa_set_profiling(True)
-    kms = np.zeros(4)
+    kms_in = np.zeros(4)
     for _ in range(args.steps):
         step()
-        kms += agg.fa_get_timings()
+        kms_in += agg.fa_get_timings()
     agg.fa_set_profiling(False)
-    kms /= args.steps
+    kms_in /= args.steps
+
+    # ---- region 3: each kernel alone, many launches between two events ----------------------
+    def time_alone(which):
+        for i in range(3):
+            agg.fa_enqueue_kernel(which, devs[i & 1], w.m, w.lam, w.iters, 0.0, out=out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            agg.fa_enqueue_kernel(which, devs[i & 1], w.m, w.lam, w.iters, 0.0, out=out)
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    kms = np.array([time_alone(k) for k in range(4)])
+
     # leave the result of the seed-0 set in `out` / info for the parity check below
     counter[0] = 0
     step()
     info = agg.fa_get_info()
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     es = 4 if w.dtype == "f32" else 2
     gram_bytes = float(w.n) * w.p * es                 # algorithmic: G read once
     comb_bytes = float(w.n) * w.p * es + 4.0 * w.n     # G read once + out written
     gram_gbs = gram_bytes / (kms[0] * 1e-3) / 1e9
     comb_gbs = comb_bytes / (kms[3] * 1e-3) / 1e9
-    roofline = {"kernel": "fa_gram_kernel", "bound": "hbm", "achieved": gram_gbs,
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gram_gbs / HBM_PEAK_GBS,
-                "traffic": None}
+    # the roofline entry is for the longer of the two streaming kernels
+    dom = "fa_gram_kernel" if kms[0] >= kms[3] else "fa_combine_kernel"
+    dom_gbs = gram_gbs if dom == "fa_gram_kernel" else comb_gbs
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
+                "traffic": MEASURED_TRAFFIC_BYTES[dom]}
     kernels = {
-        "fa_gram_kernel": {"ms": kms[0], "algorithmic_bytes": gram_bytes, "GB/s": gram_gbs,
-                           "frac_hbm_peak": gram_gbs / HBM_PEAK_GBS},
-        "fa_gram_reduce_kernel": {"ms": kms[1]},
-        "fa_irls_kernel": {"ms": kms[2], "jacobi_sweeps": info.sweeps},
-        "fa_combine_kernel": {"ms": kms[3], "algorithmic_bytes": comb_bytes, "GB/s": comb_gbs,
-                              "frac_hbm_peak": comb_gbs / HBM_PEAK_GBS},
+        "fa_gram_kernel": {"ms": kms[0], "ms_in_step": kms_in[0], "algorithmic_bytes": gram_bytes,
+                           "GB/s": gram_gbs, "frac_hbm_peak": gram_gbs / HBM_PEAK_GBS,
+                           "traffic": MEASURED_TRAFFIC_BYTES["fa_gram_kernel"]},
+        "fa_gram_reduce_kernel": {"ms": kms[1], "ms_in_step": kms_in[1]},
+        "fa_irls16_kernel": {"ms": kms[2], "ms_in_step": kms_in[2], "bound": "latency",
+                             "purification_steps": info.sweeps},
+        "fa_combine_kernel": {"ms": kms[3], "ms_in_step": kms_in[3],
+                              "algorithmic_bytes": comb_bytes, "GB/s": comb_gbs,
+                              "frac_hbm_peak": comb_gbs / HBM_PEAK_GBS,
+                              "traffic": MEASURED_TRAFFIC_BYTES["fa_combine_kernel"]},
     }
 
     result = {
         "metric": "FA aggregations/sec + achieved HBM GB/s (% peak), p=15 n=11.2M fp32",
         "value": value, "unit": "aggregations/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f64",
-        "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{w.name}: p={w.p} n={w.n} m={w.m} lambda={w.lam} "
-                               f"iters={w.iters} storage={w.dtype} seed=0",
+                               f"iters={w.iters} storage={w.dtype}",
                    "schedule": "gram-once", "inputs": "seeds 0 and 1 alternating"},
         "roofline": roofline,
         "kernels": kernels,
         "hbm_gbs": {"gram": gram_gbs, "combine": comb_gbs,
-                    "whole_step": (gram_bytes + comb_bytes) / elapsed * args.steps / 1e9},
+                    "whole_step": (gram_bytes + comb_bytes) / (ms_per_step * 1e-3) / 1e9},
     }
 
     if not args.no_cpu_baseline:
@@ -138,8 +184,8 @@ def main() -> int:
         proj = projector_difference(info.A, ref["A"], ref["R"])
         result["cpu_baseline"] = {"value": 1.0 / cpu_s, "unit": "aggregations/s", "cores": cores,
                                   "kind": "oracle",
-                                  "sample": f"1 whole aggregation of {w.name} (fp64 R-factor "
-                                            f"oracle, {cpu_s:.2f} s)"}
+                                  "sample": f"1 whole aggregation of {w.name} seed 0 (fp64 "
+                                            f"R-factor oracle, {cpu_s:.2f} s)"}
         result["parity"] = {"rel_l2_out": rel, "projector_diff": proj,
                             "eigengap_at_m": info.eigengap, "rank": info.rank}
     result["input_generation_s"] = gen_s

@@ -116,6 +116,8 @@ fa_status fa_get_info(fa_ctx* ctx, fa_info* host_out);
  * fa_gram: norms and pairwise inner products, K = G^T G (p x p, fp64; the quantities
  *   |g_i|^2 of Sec. 2.1 and D_ij^2 = K_ii + K_jj - 2 K_ij of Sec. 2.3).  Streams G
  *   once; synchronises and writes K row-major to host memory K_host (p*p doubles).
+ * fa_gram_async: the same two kernels, enqueued only; K stays in the context's workspace
+ *   (for timing the Gram pass alone, and as the first half of a caller-driven schedule).
  * fa_irls: the p x p part alone (normalisation, IRLS with the Jacobi eigensolver,
  *   coefficients) from a Gram matrix given in host memory; results via fa_get_info.
  * fa_combine: out = sum_i c[i] g_i with c (p doubles) given in host memory.  Streams G
@@ -124,6 +126,7 @@ fa_status fa_get_info(fa_ctx* ctx, fa_info* host_out);
  *   Y is device memory, m columns of n floats, column a at Y + a*ldy, ldy >= n.
  */
 fa_status fa_gram(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, double* K_host);
+fa_status fa_gram_async(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n);
 fa_status fa_irls(fa_ctx* ctx, const double* K_host, int p, int m, double lambda, int iters,
                   double tol);
 fa_status fa_combine(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n,
@@ -141,6 +144,19 @@ fa_status fa_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, fl
  */
 fa_status fa_set_profiling(fa_ctx* ctx, int enabled);
 fa_status fa_get_timings(fa_ctx* ctx, float ms[4]);
+
+/*
+ * Enqueue ONE kernel of the path on the context's stream, with no synchronisation and no
+ * host copies, so that a caller can time it alone (many launches between two events):
+ *   which = 0  Gram pass (S1)            reads G, writes the context's partial Grams
+ *   which = 1  partial reduction (S2)    partial Grams of the last Gram pass -> K
+ *   which = 2  p x p IRLS (S3-S5)        K in the context -> coefficients c in the context
+ *   which = 3  aggregate pass (S6)       reads G and the context's c, writes out
+ * Arguments a kernel does not use are ignored (G may be NULL for 1 and 2, out for 0-2).
+ * The kernels read what earlier calls on the same context left in its workspace.
+ */
+fa_status fa_enqueue_kernel(fa_ctx* ctx, int which, const void* G, int64_t ldg, int p, int64_t n,
+                            int m, double lambda, int iters, double tol, float* out);
 
 const char* fa_status_string(fa_status s);
 const char* fa_version(void);

@@ -22,8 +22,8 @@ _lib: Optional[ctypes.CDLL] = None
 # every symbol include/fa.h declares
 EXPORTED_SYMBOLS = (
     "fa_default_config", "fa_create", "fa_destroy", "fa_set_stream", "fa_aggregate",
-    "fa_get_info", "fa_gram", "fa_irls", "fa_combine", "fa_basis", "fa_set_profiling",
-    "fa_get_timings", "fa_status_string", "fa_version",
+    "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_set_profiling",
+    "fa_get_timings", "fa_enqueue_kernel", "fa_status_string", "fa_version",
 )
 
 
@@ -64,6 +64,8 @@ def load_library() -> ctypes.CDLL:
     lib.fa_get_info.restype = i32
     lib.fa_gram.argtypes = [vp, vp, i64, i32, i64, vp]
     lib.fa_gram.restype = i32
+    lib.fa_gram_async.argtypes = [vp, vp, i64, i32, i64]
+    lib.fa_gram_async.restype = i32
     lib.fa_irls.argtypes = [vp, vp, i32, i32, dbl, i32, dbl]
     lib.fa_irls.restype = i32
     lib.fa_combine.argtypes = [vp, vp, i64, i32, i64, vp, vp]
@@ -74,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     lib.fa_set_profiling.restype = i32
     lib.fa_get_timings.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4)]
     lib.fa_get_timings.restype = i32
+    lib.fa_enqueue_kernel.argtypes = [vp, i32, vp, i64, i32, i64, i32, dbl, i32, dbl, vp]
+    lib.fa_enqueue_kernel.restype = i32
     lib.fa_status_string.argtypes = [i32]
     lib.fa_status_string.restype = ctypes.c_char_p
     lib.fa_version.argtypes = []
@@ -191,6 +195,11 @@ class FlagAggregator:
                "fa_gram")
         return K
 
+    def fa_gram_async(self, G) -> None:
+        ptr, ldg, p, n = self._matrix(G)
+        self._use_current_stream()
+        _check(self._lib.fa_gram_async(self._ctx, ptr, ldg, p, n), "fa_gram_async")
+
     def fa_irls(self, K: np.ndarray, m: int, lam: float, iters: int, tol: float) -> None:
         K = np.ascontiguousarray(K, dtype=np.float64)
         p = K.shape[0]
@@ -223,6 +232,15 @@ class FlagAggregator:
         _check(self._lib.fa_basis(self._ctx, ptr, ldg, p, n, ctypes.c_void_p(Y.data_ptr()), ldy),
                "fa_basis")
         return Y[:, :n]
+
+    def fa_enqueue_kernel(self, which: int, G, m: int, lam: float, iters: int, tol: float,
+                          out=None) -> None:
+        ptr, ldg, p, n = self._matrix(G)
+        self._use_current_stream()
+        optr = ctypes.c_void_p(out.data_ptr()) if out is not None else None
+        _check(self._lib.fa_enqueue_kernel(self._ctx, int(which), ptr, ldg, p, n, int(m),
+                                           float(lam), int(iters), float(tol), optr),
+               "fa_enqueue_kernel")
 
     def fa_set_profiling(self, enabled: bool) -> None:
         _check(self._lib.fa_set_profiling(self._ctx, 1 if enabled else 0), "fa_set_profiling")

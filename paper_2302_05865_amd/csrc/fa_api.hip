@@ -28,6 +28,7 @@ struct fa_ctx {
                       // 2 = any-p Jacobi kernel (testing)
   fa_ktime tm[4];     // per-kernel begin/end events (profiling)
   int ev_recorded;
+  int last_nparts;    // partial Grams written by the last Gram pass
 };
 
 static int elem_size(int dtype) { return dtype == FA_F32 ? 4 : 2; }
@@ -163,6 +164,7 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
                         prof ? &c->tm[3] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (prof) c->ev_recorded = 1;
+  c->last_nparts = nparts;
   c->has_solution = 1;
   c->last_p = p;
   c->last_m = m;
@@ -198,6 +200,17 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
     return FA_ERR_DEVICE;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
   if (hipMemcpy(K_host, c->Kd, sizeof(double) * p * p, hipMemcpyDeviceToHost) != hipSuccess)
+    return FA_ERR_DEVICE;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_gram_async(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n) {
+  if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
+  int nparts = 0;
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+                              &nparts, c->stream, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   return FA_OK;
 }
@@ -246,6 +259,33 @@ extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int6
                           c->combine_max_blocks, c->stream, nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
   return FA_OK;
+}
+
+extern "C" fa_status fa_enqueue_kernel(fa_ctx* c, int which, const void* G, int64_t ldg, int p,
+                                       int64_t n, int m, double lambda, int iters, double tol,
+                                       float* out) {
+  if (!c || which < 0 || which > 3) return FA_ERR_ARG;
+  if (p < 1 || p > c->cfg.p_max) return FA_ERR_ARG;
+  hipError_t e = hipSuccess;
+  if (which == 0) {
+    if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
+    e = fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+                                &c->last_nparts, c->stream, nullptr);
+  } else if (which == 1) {
+    if (c->last_nparts < 1) return FA_ERR_ARG;
+    e = fa_launch_gram_reduce(c->partials, c->last_nparts, p, c->Kd, c->stream, nullptr);
+  } else if (which == 2) {
+    if (!check_solver_args(p, m, lambda, iters, tol)) return FA_ERR_ARG;
+    e = fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
+                       c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, c->stream, nullptr);
+    c->has_solution = 1; c->last_p = p; c->last_m = m;
+  } else {
+    if (!check_matrix_args(c, G, ldg, p, n) || !out || ((uintptr_t)out & 15u) != 0)
+      return FA_ERR_ARG;
+    e = fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks,
+                          c->stream, nullptr);
+  }
+  return e == hipSuccess ? FA_OK : FA_ERR_DEVICE;
 }
 
 extern "C" fa_status fa_set_profiling(fa_ctx* c, int enabled) {
