@@ -65,7 +65,8 @@ typedef struct {
   int p, m;        /* as passed */
   int rank;        /* numerical rank of G */
   int iters_done;  /* IRLS solves performed (<= iters; fewer if tol stopped it) */
-  int sweeps;      /* Jacobi sweeps spent in total (diagnostic) */
+  int sweeps;      /* eigen-iteration count in total (diagnostic): purification steps on the
+                      p <= 16 fast path, Jacobi sweeps otherwise */
   double eigengap; /* (mu_m - mu_{m+1}) / mu_1 of the last weighted PCA (inf if m >= rank) */
   double objective[FA_ITERS_MAX]; /* Eq. 5 value after each solve */
   double s[FA_P_MAX];  /* |g_i|^2 */
@@ -118,7 +119,7 @@ fa_status fa_get_info(fa_ctx* ctx, fa_info* host_out);
  *   once; synchronises and writes K row-major to host memory K_host (p*p doubles).
  * fa_gram_async: the same two kernels, enqueued only; K stays in the context's workspace
  *   (for timing the Gram pass alone, and as the first half of a caller-driven schedule).
- * fa_irls: the p x p part alone (normalisation, IRLS with the Jacobi eigensolver,
+ * fa_irls: the p x p part alone (normalisation, IRLS by repeated weighted PCA,
  *   coefficients) from a Gram matrix given in host memory; results via fa_get_info.
  * fa_combine: out = sum_i c[i] g_i with c (p doubles) given in host memory.  Streams G
  *   once.  Asynchronous.
