@@ -270,3 +270,53 @@ def test_argument_errors(agg_f32):
     small.close()
     with pytest.raises(TypeError):
         agg_f32.fa_aggregate(dev.double(), 2, 1.0, 3, 0.0)
+
+
+# ------------------------------------------------------------- solver paths of the p x p part
+@pytest.mark.parametrize("solver", ["1", "2"])
+def test_alternative_pxp_solvers_agree_with_the_oracle(monkeypatch, solver):
+    """p <= 16 has three p x p solvers (purification by default, the wave-level Jacobi
+    path, the generic Jacobi kernel); the environment variable read at fa_create picks one."""
+    announce("solver", solver)
+    monkeypatch.setenv("FA_IRLS_SOLVER", solver)
+    agg = FlagAggregator(n_max=1 << 20, p_max=16, dtype="f32")
+    monkeypatch.delenv("FA_IRLS_SOLVER")
+    _check_aggregate(agg, si.WORKLOADS["cfg2"].with_n(300_007), 5)
+    _check_aggregate(agg, si.WORKLOADS["cfg1"].with_n(40_001), 5)
+    agg.close()
+
+
+def test_tied_eigenvalues_fall_back_and_give_a_valid_subspace(agg_f32):
+    """Orthogonal gradients of equal norm: every eigenvalue of the weighted PCA ties, the
+    minimiser is not unique and purification cannot separate the spectrum.  What is unique
+    is checked (Y orthonormal, sum of explained variances = m, out = G c)."""
+    announce("tied eigenvalues")
+    p, n, m = 6, 6 * 1000, 3
+    Gw = np.zeros((p, n), dtype=np.float32)
+    for i in range(p):
+        Gw[i, i * 1000:(i + 1) * 1000] = 1.0
+    out = agg_f32.fa_aggregate(to_device(Gw), m, 1.0, 5, 0.0).cpu().numpy().astype(np.float64)
+    info = agg_f32.fa_get_info()
+    assert info.status == 0 and info.rank == p
+    K = as_f64_matrix(Gw).T @ as_f64_matrix(Gw)
+    assert np.abs(info.A.T @ K @ info.A - np.eye(m)).max() <= 1e-10
+    assert abs(info.v.sum() - m) <= 1e-9 and info.v.min() >= -1e-12 and info.v.max() <= 1 + 1e-12
+    assert rel_l2(out, as_f64_matrix(Gw) @ info.c) <= 1e-6
+    P = info.A @ info.A.T @ K                      # coefficients of Y Y^T G
+    assert np.allclose(info.c, P.sum(axis=1) / p, atol=1e-10)
+
+
+def test_single_kernels_enqueued_one_by_one_equal_the_whole_call(agg_f32):
+    announce("fa_gram_async / fa_enqueue_kernel")
+    w = si.WORKLOADS["cfg2"].with_n(123_457)
+    Gw, _ = si.make_inputs(w, 6)
+    dev = to_device(Gw)
+    whole = agg_f32.fa_aggregate(dev, w.m, w.lam, w.iters, 0.0).clone()
+    K_whole = agg_f32.fa_get_info().K.copy()
+    agg_f32.fa_gram_async(dev)
+    out = torch.zeros_like(whole)
+    agg_f32.fa_enqueue_kernel(2, dev, w.m, w.lam, w.iters, 0.0, out=out)
+    agg_f32.fa_enqueue_kernel(3, dev, w.m, w.lam, w.iters, 0.0, out=out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, whole)
+    assert np.array_equal(agg_f32.fa_gram(dev), K_whole)
