@@ -18,11 +18,13 @@
 typedef double v4f64 __attribute__((ext_vector_type(4)));
 
 // tuning of the p <= 16 fp32 Gram kernel: columns per load instruction and waves per CU
+// (measured at p = 15, n = 11.2M: CPL 4 x 12 waves 105 us; 2 x 12 111 us; 1 x 8 119 us; wave
+// counts that are not a multiple of the four SIMDs lose 10-20 us)
 #ifndef FA_GRAM_CPL1
-#define FA_GRAM_CPL1 1
+#define FA_GRAM_CPL1 4
 #endif
 #ifndef FA_GRAM_W1
-#define FA_GRAM_W1 8
+#define FA_GRAM_W1 12
 #endif
 
 // ------------------------------------------------------------------------------------------
@@ -38,13 +40,36 @@ struct ElemBF16 {
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
+// Streaming access to G and out: every byte is used once per pass, so the loads carry the
+// non-temporal hint (measured on MI355X: 15 column streams read at 7.0 TB/s with it, 6.2 TB/s
+// without) and the output is written through (one output stream beside the 15 input
+// streams: 114 us with write-through stores, 119 us with default ones, n = 11.2M).
+__device__ __forceinline__ uint4 load16_stream(const void* src) {
+  const uint32_t* s = reinterpret_cast<const uint32_t*>(src);
+  uint4 v;   // the four dword loads are merged into one global_load_dwordx4 nt
+  v.x = __builtin_nontemporal_load(s);
+  v.y = __builtin_nontemporal_load(s + 1);
+  v.z = __builtin_nontemporal_load(s + 2);
+  v.w = __builtin_nontemporal_load(s + 3);
+  return v;
+}
+
+typedef uint32_t fa_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store16_through(float* dst, float4 r) {
+  const fa_u32x4 v = {__float_as_uint(r.x), __float_as_uint(r.y), __float_as_uint(r.z),
+                      __float_as_uint(r.w)};
+  // the trailing s_nop covers the wait states a VALU write of the data registers needs
+  // after a store wider than 64 bits (the compiler cannot see inside the asm)
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 2" ::"v"(dst), "v"(v) : "memory");
+}
+
 // 16 bytes of column `base` starting at element row0, zero-filled past row n.
 template <typename E>
 __device__ __forceinline__ uint4 load16_guarded(const unsigned char* base, int64_t row0,
                                                 int64_t n) {
   uint4 v = make_uint4(0u, 0u, 0u, 0u);
   if (row0 + E::EPL <= n) {
-    v = *reinterpret_cast<const uint4*>(base + row0 * E::SIZE);
+    v = load16_stream(base + row0 * E::SIZE);
   } else if (row0 < n) {
     uint32_t w[4] = {0u, 0u, 0u, 0u};
     if constexpr (E::SIZE == 4) {
@@ -153,7 +178,7 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
     if ((tl + 1) * R <= n) {               // uniform: a full tile needs no row guards
 #pragma unroll
       for (int cg = 0; cg < NCG; ++cg)
-        regs[cg] = *reinterpret_cast<const uint4*>(colbase[cg] + row0 * E::SIZE);
+        regs[cg] = load16_stream(colbase[cg] + row0 * E::SIZE);
     } else {
 #pragma unroll
       for (int cg = 0; cg < NCG; ++cg) regs[cg] = load16_guarded<E>(colbase[cg], row0, n);
@@ -272,35 +297,49 @@ __global__ __launch_bounds__(1024) void fa_gram_reduce_kernel(const double* __re
 // ------------------------------------------------------------------------------------------
 // K4: out[k] = sum_i c[i] G[k][i]  (Alg. 1: d = (1/p) Y Y^T G 1 = G c).  Each thread owns 16
 // bytes of every column (coalesced), accumulates in fp64 and writes fp32.
-// Rows are walked from the end of G towards the beginning: the Gram pass walks them the
-// other way, so the rows it touched last are still in the memory-side cache when this pass
-// starts with them.
+#ifndef FA_COMBINE_NL
+#define FA_COMBINE_NL 8
+#endif
 template <typename E>
 __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __restrict__ G,
                                                          int64_t ldg, int p, int64_t n,
                                                          const double* __restrict__ c,
                                                          int cstride, float* __restrict__ out) {
   constexpr int EPL = E::EPL;
-  __shared__ double cs[FA_P_MAX + 8];
-  if (threadIdx.x < FA_P_MAX + 8)
+  constexpr int NL = FA_COMBINE_NL;   // columns in flight per thread
+  __shared__ double cs[FA_P_MAX + NL];
+  if (threadIdx.x < FA_P_MAX + NL)
     cs[threadIdx.x] = (int)threadIdx.x < p ? c[(int64_t)threadIdx.x * cstride] : 0.0;
   __syncthreads();
   const int64_t ngroups = (n + EPL - 1) / EPL;
-  for (int64_t gidx = (int64_t)blockIdx.x * 256 + threadIdx.x; gidx < ngroups;
-       gidx += (int64_t)gridDim.x * 256) {
-    const int64_t row0 = (ngroups - 1 - gidx) * EPL;
+  for (int64_t gbase = (int64_t)blockIdx.x * 256; gbase < ngroups;
+       gbase += (int64_t)gridDim.x * 256) {
+    const int64_t gidx = gbase + threadIdx.x;
+    const int64_t row0 = gidx * EPL;
+    const bool block_full = (gbase + 256) * EPL <= n;   // uniform: no row guards needed
+    if (!block_full && gidx >= ngroups) continue;
     double acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.0;
-    for (int c0 = 0; c0 < p; c0 += 8) {
-      uint4 v[8];
+    const unsigned char* src = G + row0 * E::SIZE;
+    for (int c0 = 0; c0 < p; c0 += NL) {
+      uint4 v[NL];
+      if (block_full) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        v[u] = make_uint4(0u, 0u, 0u, 0u);
-        if (c0 + u < p) v[u] = load16_guarded<E>(G + (int64_t)(c0 + u) * ldg * E::SIZE, row0, n);
+        for (int u = 0; u < NL; ++u) {
+          // columns past p re-read column p-1; their coefficient is zero
+          const int col = c0 + u < p ? c0 + u : p - 1;
+          v[u] = load16_stream(src + (int64_t)col * ldg * E::SIZE);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+          const int col = c0 + u < p ? c0 + u : p - 1;
+          v[u] = load16_guarded<E>(G + (int64_t)col * ldg * E::SIZE, row0, n);
+        }
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < NL; ++u) {
         const double cc = cs[c0 + u];
         if constexpr (E::SIZE == 4) {
           acc[0] += cc * (double)__uint_as_float(v[u].x);
@@ -323,8 +362,8 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
     if (row0 + EPL <= n) {
 #pragma unroll
       for (int e = 0; e < EPL; e += 4)
-        *reinterpret_cast<float4*>(dst + e) =
-            make_float4((float)acc[e], (float)acc[e + 1], (float)acc[e + 2], (float)acc[e + 3]);
+        store16_through(dst + e, make_float4((float)acc[e], (float)acc[e + 1], (float)acc[e + 2],
+                                             (float)acc[e + 3]));
     } else {
       for (int e = 0; e < EPL; ++e)
         if (row0 + e < n) dst[e] = (float)acc[e];
@@ -440,7 +479,7 @@ hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n,
     }
   } else {
     switch (T) {
-      case 1: e = launch_gram_t<1, 1, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
+      case 1: e = launch_gram_t<1, FA_GRAM_CPL1, ElemBF16, FA_GRAM_W1>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
       case 2: e = launch_gram_t<2, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
       case 3: e = launch_gram_t<3, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
       case 4: e = launch_gram_t<4, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
