@@ -473,7 +473,8 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   for (int r = 0; r < 4; ++r) isdiag[r] = (4 * r + q4) == c16;
   const bool livej = sj > 0.0;
   double wj = livej ? 1.0 : 0.0;                      // IRLS weight of this lane's column
-  double rhoj = 0.0;
+  double rhoj = 0.0, rsj = 0.0;
+  const double rs_delta = 1.0 / sqrt(delta);          // the weight floor, as a cap on 1/sqrt(rho)
   v4d cp;                                              // pair part of C, entry (4r+q4, c16)
 #pragma unroll
   for (int r = 0; r < 4; ++r) cp[r] = -2.0 * coef * d2inv[r];
@@ -503,43 +504,52 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
 #pragma unroll
       for (int r = 0; r < 4; ++r) tr += isdiag[r] ? mk[r] : 0.0;
       const double hi = wave_sum(tr);
-      const double sc = 1.0 / hi;
+      // any scale that keeps the eigenvalues in [0, 1] will do: the hardware reciprocal,
+      // shaded down by more than its error
+      const double sc = __builtin_amdgcn_rcp(hi) * (1.0 - 1e-7);
 #pragma unroll
       for (int r = 0; r < 4; ++r) x[r] = mk[r] * sc;
       // Steering: square when trace(X) > m, else X <- 2X - X^2.  trace(X) is carried along
       // (after a square it is the previous |X|_F^2, otherwise 2 trace(X) - |X|_F^2), so the
       // only reduction per step is |X|_F^2, and its result is not needed before the end of
-      // the *next* step: a wavefront issues in order and fp64 vector operations have a long
-      // dependent latency, so the reduction is split in two halves (second half for X_{k-1},
-      // first half for X_k) that sit beside the four matrix-core instructions of X_k^2.
-      double tXp = 2.0, tX = 1.0;          // trace(X_{k-1}) (dummy for k = 0), trace(X_k)
-      double pend = 1.0 / 16.0;            // stage-1 partial of |X_{k-1}|_F^2 (stage 2 sums to 1)
-      bool sqp = true;                     // with the above: trace(X_0) = 1 = trace(M/trace M)
-      bool conv = false;
-      bool near = false;                   // X_{k-2} was nearly idempotent
+      // the *next* step: the reduction is split in two halves (second half for X_{k-1},
+      // first half for X_k) issued beside the four matrix-core instructions of X_k^2.
+      // Convergence is read off the same numbers one step late: trace(X_{k-1}) - |X_{k-1}|_F^2
+      // is the distance of X_{k-1} from a projector.  The carried trace drifts by rounding
+      // (the error doubles along a run of non-squaring steps), so once that distance is below
+      // 1e-8 the trace of every iterate is measured exactly, and the final test uses two
+      // directly measured numbers.  Two steps after 1e-8 the iteration has converged (each
+      // step squares the error at one end of the spectrum and doubles it at the other).
+      double tXp = 2.0, tX = hi * sc;      // trace(X_{k-1}) (dummy for k = 0), trace(X_k)
+      double pend = tX * (1.0 / 16.0);     // stage-1 partial of |X_{k-1}|_F^2: stage 2 gives tX
+      bool sqp = true;                     // with the above, step 0 computes trace(X_0) = tX
+      bool conv = false, exact_p = false;   // exact_p: tXp was measured, not carried
+      int k_end = MAX_PURIFY;
       for (int k = 0; k < MAX_PURIFY; ++k) {
-        if (near) {
-          // measure the current X exactly (the carried trace drifts by rounding) and stop
-          // if it is a projector to working precision
+        const v4d y = mm16(x, x);
+        const double tYp = fro2_stage2(pend);              // |X_{k-1}|_F^2
+        pend = fro2_stage1(x);
+        tX = sqp ? tYp : fma(2.0, tXp, -tYp);              // trace(X_k)
+        const double idem = tXp - tYp;                     // trace(X_{k-1} - X_{k-1}^2)
+#ifdef FA_K3_DEBUG
+        if (it == 0 && k < 120 && lane == 0) { info->objective[k] = tX; info->objective[120 + k] = idem; }
+#endif
+        bool exact = false;
+        if (idem < 1e-8) {
+          if (exact_p && idem < 1e-12) {
+            // X_{k-1} is a projector to working precision and x = X_k is its successor; it
+            // is the wanted projector only if the trace is m (the maps are monotone, so
+            // the eigenvalue order is kept whatever the steering did)
+            conv = fabs(tXp - (double)mm) < 0.25;
+            k_end = k;
+            break;
+          }
           double td = 0.0;
 #pragma unroll
           for (int r = 0; r < 4; ++r) td += isdiag[r] ? x[r] : 0.0;
           tX = wave_sum(td);
-          pend = fro2_stage1(x);
-          if (tX - fro2_stage2(pend) < 1e-13) {
-            // idempotent; it is the wanted projector only if its trace is m (the maps are
-            // monotone, so the eigenvalue order is kept whatever the steering did)
-            conv = fabs(tX - (double)mm) < 0.25;
-            break;
-          }
-          // resynchronise the carried quantities on the exact values
-          tXp = 2.0; sqp = true; pend = tX * (1.0 / 16.0);
+          exact = true;
         }
-        const v4d y = mm16(x, x);
-        const double tYp = fro2_stage2(pend);              // |X_{k-1}|_F^2
-        pend = fro2_stage1(x);
-        tX = sqp ? tYp : fma(2.0, tXp, -tYp);
-        near = (tXp - tYp < 1e-8);
         const bool sq = tX > (double)mm;
         if (sq) {
 #pragma unroll
@@ -550,9 +560,10 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
         }
         tXp = tX;
         sqp = sq;
+        exact_p = exact;
         steps = steps + 1;
       }
-      if (!conv) return 0;
+      if (!conv) return -(1000 + it * 1000 + k_end);
     } else {
       // m >= rank: Y spans all of span(G)
 #pragma unroll
@@ -571,27 +582,31 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     for (int r = 0; r < 4; ++r) fm.Zs[c16 * LDZ + 4 * r + q4] = z[r];
     wave_fence();
     double zj[16];
-    double nrm = 0.0;
+    double nr4[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int a = 0; a < 16; ++a) {
       zj[a] = fm.Zs[c16 * LDZ + a];
-      nrm = fma(zj[a], zj[a], nrm);
+      nr4[a & 3] = fma(zj[a], zj[a], nr4[a & 3]);
     }
-    rhoj = nrm * dj * dj;                               // 1 - v_j
-    double part = (q4 == 0 && livej) ? sqrt(rhoj) : 0.0;
+    rhoj = ((nr4[0] + nr4[1]) + (nr4[2] + nr4[3])) * dj * dj;      // 1 - v_j
+    // sqrt(rho) = rho * rsqrt(rho) and max(rho, delta)^(-1/2) = min(rsqrt(rho), delta^(-1/2)):
+    // one reciprocal square root per residual, no division
+    rsj = rsq_nr<2>(rhoj > 1e-300 ? rhoj : 1e-300);
+    double part = (q4 == 0 && livej) ? rhoj * rsj : 0.0;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int i = 4 * r + q4;
-      double acc = 0.0;
+      double ac2[2] = {0.0, 0.0};
 #pragma unroll
       for (int a = 0; a < 16; ++a) {
         const double df = fm.Zs[i * LDZ + a] - zj[a];
-        acc = fma(df, df, acc);
+        ac2[a & 1] = fma(df, df, ac2[a & 1]);
       }
-      const double rho = acc * d2inv[r];
+      const double rho = (ac2[0] + ac2[1]) * d2inv[r];
       const bool lp = d2inv[r] > 0.0;
-      part += lp ? coef * sqrt(rho) : 0.0;            // ordered pair (i, j)
-      cp[r] = lp ? -2.0 * coef * d2inv[r] / sqrt(rho > delta ? rho : delta) : 0.0;
+      const double rs = rsq_nr<2>(rho > 1e-300 ? rho : 1e-300);
+      part += lp ? coef * (rho * rs) : 0.0;            // ordered pair (i, j)
+      cp[r] = lp ? -2.0 * coef * d2inv[r] * (rs < rs_delta ? rs : rs_delta) : 0.0;
     }
     wave_fence();
     const double obj = wave_sum(part);
@@ -603,7 +618,7 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     const bool stop = it > 0 && fabs(prev_obj - obj) < tol;
     prev_obj = obj;
     if (stop) break;
-    wj = livej ? 1.0 / sqrt(rhoj > delta ? rhoj : delta) : 0.0;
+    wj = livej ? (rsj < rs_delta ? rsj : rs_delta) : 0.0;
   }
 
   // ---- epilogue: basis of range(P), A = B U_m, c = A (U_m^T R 1) / p ---------------------
@@ -616,7 +631,7 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   wave_fence();
   // P = U U^T with orthonormal U: the rows produced by the pivoted Cholesky of a projector
   const int nb = pivoted_cholesky(fm.Ps, fm.Um, fm.piv, 1e-6, mm, lane);
-  if (nb != mm) return 0;
+  if (nb != mm) return -2;
   v4d ba, ub;   // B as A operand: B[c16][4s+q4];  U_m as B operand: U[a = 4s+q4][k = c16]
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
@@ -685,7 +700,10 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
       if (tid == 0) fast_done = ok;
     }
     __syncthreads();
-    if (fast_done) return;
+#ifdef FA_K3_TIMING
+    if (tid == 0 && fast_done <= 0) info->objective[250] = (double)fast_done;
+#endif
+    if (fast_done > 0) return;
   }
   const int ri = tid >> 4, ci = tid & 15;       // this thread's entry of a 16 x 16 matrix
   const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
