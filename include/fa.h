@@ -108,6 +108,34 @@ fa_status fa_set_stream(fa_ctx* ctx, void* stream);
 fa_status fa_aggregate(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, int m,
                        double lambda, int iters, double tol, float* out);
 
+/*
+ * The same aggregation under the re-streaming schedule, for measurement: every IRLS solve
+ * passes over G twice, the way an implementation that re-does an n-sized decomposition per
+ * iteration does (Sec. 3 "Implementation Details"; the cost discussed in Sec. 4).  Per solve:
+ *   pass 1  weighted Gram matrix  G^T W G  with W = diag(w_i / |g_i|^2) applied as column
+ *           scales inside the Gram kernel (plain G^T G for the first, uniform-weight solve),
+ *   then one weighted PCA in p x p space (the pairwise terms of Eq. 5 are linear in G^T G),
+ *   pass 2  projections Y^T g_i of all gradients on the new basis by streaming G (Y = G A is
+ *           formed tile by tile in registers and never stored), from which the explained
+ *           variances of Sec. 2.1, the residuals of Eq. 5 and the next weights are taken.
+ * After `iters` solves the direction of Alg. 1 is written as in fa_aggregate.  The stop rule is
+ * not available (tol = 0).  Results agree with fa_aggregate to rounding (about 1e-7: residuals
+ * are formed as 1 - v from streamed projections); fa_get_info reports the p x p solver's own
+ * record, fa_get_restream_info the streamed quantities.
+ * HBM traffic: (2 iters + 1) n p elem_size + 4 n bytes, against 2 n p elem_size + 4 n of
+ * fa_aggregate: this entry point exists to time the two per-iteration passes, not to be fast.
+ */
+fa_status fa_aggregate_restream(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, int m,
+                                double lambda, int iters, float* out);
+
+/* After fa_aggregate_restream: waits for the stream; ms (may be NULL; needs
+ * fa_set_profiling) receives the durations of the last solve's two passes in milliseconds
+ * (ms[0] weighted Gram pass, ms[1] projection pass); v_streamed (NULL or FA_P_MAX doubles)
+ * the explained variances measured by the last projection pass; objective_streamed (NULL or
+ * FA_ITERS_MAX doubles) Eq. 5 after each solve, from streamed projections.  Host pointers. */
+fa_status fa_get_restream_info(fa_ctx* ctx, float ms[2], double* v_streamed,
+                               double* objective_streamed);
+
 /* Wait for the context's stream and copy the record of the last solve to host memory. */
 fa_status fa_get_info(fa_ctx* ctx, fa_info* host_out);
 

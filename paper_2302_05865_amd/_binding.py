@@ -23,7 +23,8 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTED_SYMBOLS = (
     "fa_default_config", "fa_create", "fa_destroy", "fa_set_stream", "fa_aggregate",
     "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_set_profiling",
-    "fa_get_timings", "fa_enqueue_kernel", "fa_status_string", "fa_version",
+    "fa_get_timings", "fa_enqueue_kernel", "fa_aggregate_restream", "fa_get_restream_info",
+    "fa_status_string", "fa_version",
 )
 
 
@@ -78,6 +79,10 @@ def load_library() -> ctypes.CDLL:
     lib.fa_get_timings.restype = i32
     lib.fa_enqueue_kernel.argtypes = [vp, i32, vp, i64, i32, i64, i32, dbl, i32, dbl, vp]
     lib.fa_enqueue_kernel.restype = i32
+    lib.fa_aggregate_restream.argtypes = [vp, vp, i64, i32, i64, i32, dbl, i32, vp]
+    lib.fa_aggregate_restream.restype = i32
+    lib.fa_get_restream_info.argtypes = [vp, vp, vp, vp]
+    lib.fa_get_restream_info.restype = i32
     lib.fa_status_string.argtypes = [i32]
     lib.fa_status_string.restype = ctypes.c_char_p
     lib.fa_version.argtypes = []
@@ -172,6 +177,31 @@ class FlagAggregator:
         _check(self._lib.fa_aggregate(self._ctx, ptr, ldg, p, n, int(m), float(lam), int(iters),
                                       float(tol), ctypes.c_void_p(out.data_ptr())), "fa_aggregate")
         return out
+
+    def fa_aggregate_restream(self, G, m: int, lam: float, iters: int, out=None):
+        ptr, ldg, p, n = self._matrix(G)
+        torch = self._torch
+        if out is None:
+            out = torch.empty(n, dtype=torch.float32, device=G.device)
+        if not out.is_cuda or out.dtype != torch.float32 or out.numel() != n or not out.is_contiguous():
+            raise TypeError("out must be a contiguous float32 device tensor of n elements")
+        self._use_current_stream()
+        _check(self._lib.fa_aggregate_restream(self._ctx, ptr, ldg, p, n, int(m), float(lam),
+                                               int(iters), ctypes.c_void_p(out.data_ptr())),
+               "fa_aggregate_restream")
+        self._restream_p = p
+        return out
+
+    def fa_get_restream_info(self, timings: bool = False):
+        """(ms[2] or None, v_streamed[p], objective_streamed[FA_ITERS_MAX])"""
+        ms = (ctypes.c_float * 2)()
+        v = np.zeros(64, dtype=np.float64)
+        obj = np.zeros(256, dtype=np.float64)
+        _check(self._lib.fa_get_restream_info(
+            self._ctx, ctypes.cast(ms, ctypes.c_void_p) if timings else None,
+            v.ctypes.data_as(ctypes.c_void_p), obj.ctypes.data_as(ctypes.c_void_p)),
+            "fa_get_restream_info")
+        return (np.array(ms[:]) if timings else None), v[:getattr(self, "_restream_p", 64)], obj
 
     def fa_get_info(self) -> FaInfoResult:
         info = FaInfo()

@@ -13,7 +13,16 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libfa.so")
-SOURCES = ["fa_kernels.hip", "fa_irls16.hip", "fa_api.hip"]
+# source file -> extra device-compiler flags
+SOURCES = {
+    "fa_kernels.hip": [],
+    # matrix-core results straight into VGPRs: no accumulator-register copies in the
+    # purification loop of the p x p kernel (236 -> 222 us at p = 15).  Not for the streaming
+    # kernels, whose larger tilings need the accumulator registers as extra space.
+    "fa_irls16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "fa_api.hip": [],
+}
+OBJ_DIR = os.path.join(HERE, "_build")
 
 
 def hipcc_path() -> str:
@@ -23,18 +32,7 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = True) -> str:
-    cmd = [hipcc_path(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
-           "-fgpu-rdc" if False else "-fno-gpu-rdc",
-           # no packed-fp32 instruction forms on the test machines
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           # matrix-core results straight into VGPRs (no accumulator-register copies in the
-           # purification loop of the p x p kernel: 236 -> 222 us at p = 15)
-           "-mllvm", "-amdgpu-mfma-vgpr-form",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-Wall", "-Wno-unused-function"]
-    cmd += [os.path.join(CSRC, s) for s in SOURCES]
-    cmd += ["-o", LIB_PATH]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -44,6 +42,21 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError(f"hipcc failed ({proc.returncode}):\n{proc.stdout}\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
+
+
+def build(verbose: bool = True) -> str:
+    common = [hipcc_path(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
+              # no packed-fp32 instruction forms on the test machines
+              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-function"]
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = []
+    for src, extra in SOURCES.items():
+        obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+        _run(common + extra + ["-c", os.path.join(CSRC, src), "-o", obj], verbose)
+        objs.append(obj)
+    _run([hipcc_path(), "--offload-arch=gfx950", "-fno-gpu-rdc", "-shared", "-fPIC"] + objs +
+         ["-o", LIB_PATH], verbose)
     return LIB_PATH
 
 

@@ -26,7 +26,12 @@ struct fa_ctx {
   int profiling;
   int solver;         // FA_IRLS_SOLVER in the environment: 0 default, 1 = p<=16 Jacobi path,
                       // 2 = any-p Jacobi kernel (testing)
+  fa_resume* rs_d;    // IRLS state of the re-streaming schedule
+  double* Pd;         // streamed projections, FA_P_MAX^2
   fa_ktime tm[4];     // per-kernel begin/end events (profiling)
+  fa_ktime tm_r[2];   // re-streaming schedule: weighted Gram pass and projection pass of the
+                      // last iteration
+  int ev_recorded_r;
   int ev_recorded;
   int last_nparts;    // partial Grams written by the last Gram pass
 };
@@ -81,7 +86,7 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   c->gram_max_blocks = c->num_cus;                 // one Gram workgroup per compute unit
   c->combine_max_blocks = 1 << 20;
   const int T = (cfg->p_max + 15) / 16;
-  const size_t ntp = (size_t)T * (T + 1) / 2;
+  const size_t ntp = (size_t)T * T;   // tile pairs of the Gram pass, T x TM tiles of the projections
   const size_t part_bytes = (size_t)c->gram_max_blocks * ntp * 256 * sizeof(double);
   bool ok = true;
   ok = ok && hipMalloc((void**)&c->partials, part_bytes) == hipSuccess;
@@ -90,11 +95,16 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   ok = ok && hipMalloc((void**)&c->gws, sizeof(double) * (2 * FA_P_MAX * (FA_P_MAX + 1) + 258)) ==
                  hipSuccess;
   ok = ok && hipMalloc((void**)&c->info_d, sizeof(fa_info)) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->rs_d, sizeof(fa_resume)) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->Pd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;
   if (!ok) { fa_destroy(c); return FA_ERR_ALLOC; }
   if (hipMemset(c->info_d, 0, sizeof(fa_info)) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
   for (int i = 0; i < 4; ++i)
     if (hipEventCreate(&c->tm[i].start) != hipSuccess ||
         hipEventCreate(&c->tm[i].stop) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
+  for (int i = 0; i < 2; ++i)
+    if (hipEventCreate(&c->tm_r[i].start) != hipSuccess ||
+        hipEventCreate(&c->tm_r[i].stop) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
   if (fa_irls_prepare() != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
   *out_ctx = c;
   return FA_OK;
@@ -108,9 +118,15 @@ extern "C" void fa_destroy(fa_ctx* c) {
   if (c->cd) (void)hipFree(c->cd);
   if (c->gws) (void)hipFree(c->gws);
   if (c->info_d) (void)hipFree(c->info_d);
+  if (c->rs_d) (void)hipFree(c->rs_d);
+  if (c->Pd) (void)hipFree(c->Pd);
   for (int i = 0; i < 4; ++i) {
     if (c->tm[i].start) (void)hipEventDestroy(c->tm[i].start);
     if (c->tm[i].stop) (void)hipEventDestroy(c->tm[i].stop);
+  }
+  for (int i = 0; i < 2; ++i) {
+    if (c->tm_r[i].start) (void)hipEventDestroy(c->tm_r[i].start);
+    if (c->tm_r[i].stop) (void)hipEventDestroy(c->tm_r[i].stop);
   }
   delete c;
 }
@@ -149,14 +165,14 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   // S1: norms and Gram matrix, per-workgroup partials;  S2: their fixed-order sum
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
-                              &nparts, st, prof ? &c->tm[0] : nullptr) != hipSuccess)
+                              &nparts, nullptr, st, prof ? &c->tm[0] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, prof ? &c->tm[1] : nullptr) !=
       hipSuccess)
     return FA_ERR_DEVICE;
   // S3-S5: p x p IRLS and coefficients
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, st,
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, nullptr, st,
                      prof ? &c->tm[2] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   // S6: out = G c
@@ -168,6 +184,79 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   c->has_solution = 1;
   c->last_p = p;
   c->last_m = m;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n,
+                                           int m, double lambda, int iters, float* out) {
+  if (!check_matrix_args(c, G, ldg, p, n) || !out || ((uintptr_t)out & 15u) != 0)
+    return FA_ERR_ARG;
+  if (!check_solver_args(p, m, lambda, iters, 0.0)) return FA_ERR_ARG;
+  hipStream_t st = c->stream;
+  const bool prof = c->profiling != 0;
+  c->ev_recorded = 0;
+  c->ev_recorded_r = 0;
+  if (hipMemsetAsync(c->rs_d, 0, sizeof(fa_resume), st) != hipSuccess) return FA_ERR_DEVICE;
+  const double* A_d = reinterpret_cast<const double*>(reinterpret_cast<const char*>(c->info_d) +
+                                                      offsetof(fa_info, A));
+  const double* u_d = reinterpret_cast<const double*>(reinterpret_cast<const char*>(c->rs_d) +
+                                                      offsetof(fa_resume, u));
+  int nparts = 0;
+  for (int it = 0; it < iters; ++it) {
+    const bool last = it == iters - 1;
+    // pass 1 over G: Gram matrix of the columns scaled by sqrt(w_i)/|g_i| (plain at first)
+    if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+                                &nparts, it == 0 ? nullptr : u_d, st,
+                                (prof && last) ? &c->tm_r[0] : nullptr) != hipSuccess)
+      return FA_ERR_DEVICE;
+    if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, nullptr) != hipSuccess)
+      return FA_ERR_DEVICE;
+    // one weighted PCA with the current weights
+    if (fa_launch_irls(c->Kd, p, m, lambda, 1, 0.0, c->cfg.clamp_delta, c->cfg.rank_tol,
+                       c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, c->rs_d, st,
+                       nullptr) != hipSuccess)
+      return FA_ERR_DEVICE;
+    // pass 2 over G: projections on the new basis, then the next weights from them
+    if (fa_launch_proj_partials(G, ldg, p, m, n, c->cfg.dtype, c->gram_max_blocks, A_d,
+                                c->partials, &nparts, st,
+                                (prof && last) ? &c->tm_r[1] : nullptr) != hipSuccess)
+      return FA_ERR_DEVICE;
+    if (fa_launch_proj_reduce(c->partials, nparts, p, m, c->Pd, st, nullptr) != hipSuccess)
+      return FA_ERR_DEVICE;
+    if (fa_launch_restream_weights(c->info_d, c->Pd, p, m, lambda, c->cfg.clamp_delta,
+                                   c->cfg.pair_tol, c->rs_d, st) != hipSuccess)
+      return FA_ERR_DEVICE;
+  }
+  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks, st,
+                        nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (prof) c->ev_recorded_r = 1;
+  c->last_nparts = 0;
+  c->has_solution = 1;
+  c->last_p = p;
+  c->last_m = m;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_get_restream_info(fa_ctx* c, float ms[2], double* v_streamed,
+                                          double* objective_streamed) {
+  if (!c) return FA_ERR_ARG;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
+  if (ms) {
+    if (!c->ev_recorded_r) return FA_ERR_ARG;
+    for (int k = 0; k < 2; ++k)
+      if (hipEventElapsedTime(&ms[k], c->tm_r[k].start, c->tm_r[k].stop) != hipSuccess)
+        return FA_ERR_DEVICE;
+  }
+  const char* base = reinterpret_cast<const char*>(c->rs_d);
+  if (v_streamed &&
+      hipMemcpy(v_streamed, base + offsetof(fa_resume, v_streamed), sizeof(double) * FA_P_MAX,
+                hipMemcpyDeviceToHost) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (objective_streamed &&
+      hipMemcpy(objective_streamed, base + offsetof(fa_resume, obj_streamed),
+                sizeof(double) * FA_ITERS_MAX, hipMemcpyDeviceToHost) != hipSuccess)
+    return FA_ERR_DEVICE;
   return FA_OK;
 }
 
@@ -194,7 +283,7 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
   if (!check_matrix_args(c, G, ldg, p, n) || !K_host) return FA_ERR_ARG;
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
-                              &nparts, c->stream, nullptr) != hipSuccess)
+                              &nparts, nullptr, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
@@ -208,7 +297,7 @@ extern "C" fa_status fa_gram_async(fa_ctx* c, const void* G, int64_t ldg, int p,
   if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
-                              &nparts, c->stream, nullptr) != hipSuccess)
+                              &nparts, nullptr, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
@@ -223,8 +312,8 @@ extern "C" fa_status fa_irls(fa_ctx* c, const double* K_host, int p, int m, doub
   if (hipMemcpy(c->Kd, K_host, sizeof(double) * p * p, hipMemcpyHostToDevice) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, c->stream, nullptr) !=
-      hipSuccess)
+                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, nullptr, c->stream,
+                     nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   c->has_solution = 1;
   c->last_p = p;
@@ -270,14 +359,15 @@ extern "C" fa_status fa_enqueue_kernel(fa_ctx* c, int which, const void* G, int6
   if (which == 0) {
     if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
     e = fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
-                                &c->last_nparts, c->stream, nullptr);
+                                &c->last_nparts, nullptr, c->stream, nullptr);
   } else if (which == 1) {
     if (c->last_nparts < 1) return FA_ERR_ARG;
     e = fa_launch_gram_reduce(c->partials, c->last_nparts, p, c->Kd, c->stream, nullptr);
   } else if (which == 2) {
     if (!check_solver_args(p, m, lambda, iters, tol)) return FA_ERR_ARG;
     e = fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                       c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, c->stream, nullptr);
+                       c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, nullptr, c->stream,
+                       nullptr);
     c->has_solution = 1; c->last_p = p; c->last_m = m;
   } else {
     if (!check_matrix_args(c, G, ldg, p, n) || !out || ((uintptr_t)out & 15u) != 0)

@@ -9,6 +9,7 @@
 #include <stdint.h>
 
 #include "fa.h"
+#include "fa_resume.h"
 
 #define FA_IRLS_THREADS 256   // workgroup size of the p x p solver
 
@@ -20,10 +21,11 @@ typedef struct { hipEvent_t start, stop; } fa_ktime;
 
 // K1: partial Grams of G, one per launched workgroup, into `partials` (up to max_blocks *
 // T(T+1)/2 * 256 doubles, T = ceil(p/16)); max_blocks = workgroups (one per compute unit);
-// *nparts receives how many partials were written.
+// *nparts receives how many partials were written.  colscale (device, p doubles, may be
+// null): column i is scaled by colscale[i], i.e. the result is diag(u) K diag(u).
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int max_blocks, double* partials, int* nparts,
-                                   hipStream_t st, const fa_ktime* tm);
+                                   const double* colscale, hipStream_t st, const fa_ktime* tm);
 // K2: their fixed-order sum into Kd (p*p doubles, row-major).
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
                                  hipStream_t st, const fa_ktime* tm);
@@ -31,10 +33,12 @@ hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, doub
 // K3: p x p solver.  Kd p*p doubles; cd p doubles out; info_d device fa_info; gws global
 // workspace of 2*FA_P_MAX*(FA_P_MAX+1) + 258 doubles.  solver: 0 = default (p <= 16:
 // purification with Jacobi fallback), 1 = p <= 16 Jacobi path, 2 = any-p Jacobi kernel.
+// rs (device, may be null): continue the IRLS from the weights left there by an earlier
+// launch and leave the next ones (see fa_resume.h).
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double* cd,
-                          fa_info* info_d, double* gws, int solver, hipStream_t st,
-                          const fa_ktime* tm);
+                          fa_info* info_d, double* gws, int solver, fa_resume* rs,
+                          hipStream_t st, const fa_ktime* tm);
 hipError_t fa_irls_prepare(void);
 // K3 for p <= 16 (latency-tuned single-workgroup solver, static LDS).
 // mlast: 258 doubles; the fast path leaves the last weighted-PCA matrix there (16 x 16, then
@@ -42,9 +46,22 @@ hipError_t fa_irls_prepare(void);
 hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int iters, double tol,
                             double delta, double rank_tol, double pair_tol, double* cd,
                             fa_info* info_d, double* mlast, int use_purification,
-                            hipStream_t st, const fa_ktime* tm);
+                            fa_resume* rs, hipStream_t st, const fa_ktime* tm);
 // eigengap (mu_m - mu_{m+1}) / mu_1 of the matrix left in mlast, into info_d->eigengap.
 hipError_t fa_launch_gap(const double* mlast, fa_info* info_d, hipStream_t st);
+
+// K5: partial results of P = G^T (G A) (p x m), A row-major p x m in device memory; one
+// partial of ceil(p/16) * ceil(m/16) * 256 doubles per workgroup; then their fixed-order sum
+// into Pd (p*m doubles, row-major).
+hipError_t fa_launch_proj_partials(const void* G, int64_t ldg, int p, int m, int64_t n, int dtype,
+                                   int max_blocks, const double* Acoef, double* partials,
+                                   int* nparts, hipStream_t st, const fa_ktime* tm);
+hipError_t fa_launch_proj_reduce(const double* partials, int nparts, int p, int m, double* Pd,
+                                 hipStream_t st, const fa_ktime* tm);
+// K6: IRLS weights, objective and next column scales from the streamed projections.
+hipError_t fa_launch_restream_weights(const fa_info* info_d, const double* Pd, int p, int m,
+                                      double lambda, double delta, double pair_tol, fa_resume* rs,
+                                      hipStream_t st);
 
 // K4: out = sum_i c[i*cstride] g_i.
 hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,

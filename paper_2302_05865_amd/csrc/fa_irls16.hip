@@ -367,10 +367,12 @@ __device__ int pivoted_cholesky(const double* S, double* rows, int* piv, double 
 __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, double lambda,
                      double tol, double delta, double rank_tol, double pair_tol,
                      double* __restrict__ cg, fa_info* __restrict__ info,
-                     double* __restrict__ mlast, Fmem& fm) {
+                     double* __restrict__ mlast, Fmem& fm, fa_resume* rs) {
   const int lane = threadIdx.x & 63;
   const int c16 = lane & 15, q4 = lane >> 4;
   const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
+  const int it0 = rs ? rs->it0 : 0;                    // solves done by earlier launches
+  const bool scaled = rs && rs->scaled;
 #ifdef FA_K3_TIMING
   const long long tk0 = clock64();
   long long tk_pur = 0, tk_res = 0, tk_mm = 0, tk_setup = 0;
@@ -382,7 +384,8 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   for (int r = 0; r < 4; ++r) {
     const int i = 4 * r + q4;
     const bool in = i < p && c16 < p;
-    const double kv = in ? Kg[i * p + c16] : 0.0;
+    double kv = in ? Kg[i * p + c16] : 0.0;
+    if (in && scaled) kv *= rs->uinv[i] * rs->uinv[c16];   // Gram of scaled columns
     fm.Kt[i * LDF + c16] = kv;
     if (in) info->K[i * p + c16] = kv;
     bad = bad || !(fabs(kv) <= 1.79e308);
@@ -478,8 +481,18 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   v4d cp;                                              // pair part of C, entry (4r+q4, c16)
 #pragma unroll
   for (int r = 0; r < 4; ++r) cp[r] = -2.0 * coef * d2inv[r];
-  v4d x = {0.0, 0.0, 0.0, 0.0}, mk = {0.0, 0.0, 0.0, 0.0};
   double prev_obj = 0.0;
+  if (it0 > 0) {
+    // continue from the weights the previous launch (or the streamed residuals) left
+    wj = (livej && c16 < p) ? rs->w[c16] : 0.0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = 4 * r + q4;
+      cp[r] = (i < p && c16 < p && i != c16) ? rs->cp[i * p + c16] : 0.0;
+    }
+    prev_obj = rs->prev_obj;
+  }
+  v4d x = {0.0, 0.0, 0.0, 0.0}, mk = {0.0, 0.0, 0.0, 0.0};
   int iters_done = 0, steps = 0;
   for (int it = 0; it < iters; ++it) {
 #ifdef FA_K3_TIMING
@@ -613,9 +626,9 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
 #ifdef FA_K3_TIMING
     tk_res += clock64() - tc;
 #endif
-    if (lane == 0) info->objective[it] = obj;
+    if (lane == 0 && it0 + it < FA_ITERS_MAX) info->objective[it0 + it] = obj;
     iters_done = it + 1;
-    const bool stop = it > 0 && fabs(prev_obj - obj) < tol;
+    const bool stop = it0 + it > 0 && fabs(prev_obj - obj) < tol;
     prev_obj = obj;
     if (stop) break;
     wj = livej ? (rsj < rs_delta ? rsj : rs_delta) : 0.0;
@@ -664,7 +677,7 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   if (lane == 0) {
     info->status = 0;
     info->p = p; info->m = m; info->rank = rank;
-    info->iters_done = iters_done;
+    info->iters_done = it0 + iters_done;
     info->sweeps = steps;
     info->eigengap = nan("");        // filled in on demand by fa_get_info (needs eigenvalues)
     mlast[256] = (double)rank;
@@ -677,6 +690,17 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     info->objective[FA_ITERS_MAX - 5] = (double)tk_setup;
 #endif
   }
+  // weights for the solve that would come next (only once nothing above can fail any more:
+  // the Jacobi path restarts from the state as this launch found it)
+  if (rs) {
+    if (lane < 16 && c16 < p) rs->w[c16] = wj;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = 4 * r + q4;
+      if (i < p && c16 < p) rs->cp[i * p + c16] = i != c16 ? cp[r] : 0.0;
+    }
+    if (lane == 0) { rs->prev_obj = prev_obj; rs->it0 = it0 + iters_done; }
+  }
   return 1;
 }
 
@@ -688,7 +712,7 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
                                                         double pair_tol, double* __restrict__ cg,
                                                         fa_info* __restrict__ info,
                                                         double* __restrict__ mlast,
-                                                        int use_purification) {
+                                                        int use_purification, fa_resume* rs) {
   __shared__ Smem sm;
   __shared__ fastp::Fmem fm;
   __shared__ int fast_done;
@@ -696,7 +720,7 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
   if (use_purification) {
     if (tid < 64) {
       const int ok = fastp::solve(Kg, p, m, iters, lambda, tol, delta, rank_tol, pair_tol, cg,
-                                  info, mlast, fm);
+                                  info, mlast, fm, rs);
       if (tid == 0) fast_done = ok;
     }
     __syncthreads();
@@ -714,8 +738,11 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
   const long long t_start = clock64();
   if (tid == 0) { sm.t_master = 0; sm.t_tail = 0; sm.t_jacobi = 0; }
 #endif
+  const int it0 = rs ? rs->it0 : 0;
+  const bool scaled = rs && rs->scaled;
   if (tid < NP) {
-    const double si = tid < p ? Kg[tid * p + tid] : 0.0;
+    double si = tid < p ? Kg[tid * p + tid] : 0.0;
+    if (tid < p && scaled) si *= rs->uinv[tid] * rs->uinv[tid];
     sm.s[tid] = si;
     sm.dinv[tid] = si > 0.0 ? 1.0 / sqrt(si) : 0.0;
     sm.w[tid] = si > 0.0 ? 1.0 : 0.0;
@@ -723,7 +750,8 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
   }
   __syncthreads();
   const bool in = ri < p && ci < p;
-  const double kij = in ? Kg[ri * p + ci] : 0.0;
+  double kij = in ? Kg[ri * p + ci] : 0.0;
+  if (in && scaled) kij *= rs->uinv[ri] * rs->uinv[ci];
   if (in) info->K[ri * p + ci] = kij;
   {
     const bool bad = !(fabs(kij) <= 1.79e308);
@@ -787,11 +815,15 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
   // pair part of C for the first, uniform-weight solve (PCA of the normalised gradients);
   // kept per thread for entry (ri, ci): C_ij = -2 coef w_ij / D_ij^2
   double cpair = (ri != ci) ? -2.0 * coef * sm.D2inv[ri * LD + ci] : 0.0;
+  if (it0 > 0) {
+    cpair = (in && ri != ci) ? rs->cp[ri * p + ci] : 0.0;
+    if (tid < p) sm.w[tid] = sm.s[tid] > 0.0 ? rs->w[tid] : 0.0;
+  }
   __syncthreads();
 
   // ---- IRLS ----------------------------------------------------------------------------
   const int mm = m < r ? m : r;
-  double prev_obj = 0.0;
+  double prev_obj = it0 > 0 ? rs->prev_obj : 0.0;
   int iters_done = 0;
   for (int it = 0; it < iters; ++it) {
     // T = R C with the diagonal of C folded in:
@@ -852,9 +884,9 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
       }
     }
     const double obj = block_sum(part, sm);
-    if (tid == 0) info->objective[it] = obj;
+    if (tid == 0 && it0 + it < FA_ITERS_MAX) info->objective[it0 + it] = obj;
     iters_done = it + 1;
-    const bool stop = it > 0 && fabs(prev_obj - obj) < tol;
+    const bool stop = it0 + it > 0 && fabs(prev_obj - obj) < tol;
     prev_obj = obj;
     if (stop) break;
     if (tid < p) {
@@ -864,6 +896,11 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
     __syncthreads();
   }
   __syncthreads();
+  if (rs) {
+    if (in) rs->cp[ri * p + ci] = ri != ci ? cpair : 0.0;
+    if (tid < p) rs->w[tid] = sm.w[tid];
+    if (tid == 0) { rs->prev_obj = prev_obj; rs->it0 = it0 + iters_done; }
+  }
 
   // ---- epilogue: A = D^-1/2 V L^-1/2 U_m,  c = (1/p) A (Y^T G 1) --------------------------
   if (tid < NP) {
@@ -904,7 +941,7 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
   if (tid == 0) {
     info->status = 0;
     info->p = p; info->m = m; info->rank = r;
-    info->iters_done = iters_done;
+    info->iters_done = it0 + iters_done;
     info->sweeps = sm.sweeps;
     double gap = __builtin_inf();
     if (m < r) gap = (sm.mu[sm.order[m - 1]] - sm.mu[sm.order[m]]) / sm.mu[sm.order[0]];
@@ -920,8 +957,8 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
 hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int iters, double tol,
                             double delta, double rank_tol, double pair_tol, double* cd,
                             fa_info* info_d, double* mlast, int use_purification,
-                            hipStream_t st, const fa_ktime* tm) {
+                            fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
   FA_LAUNCH(tm, fa_irls16_kernel, dim3(1), dim3(256), 0, st, Kd, p, m, iters, lambda, tol, delta,
-            rank_tol, pair_tol, cd, info_d, mlast, use_purification);
+            rank_tol, pair_tol, cd, info_d, mlast, use_purification, rs);
   return hipGetLastError();
 }

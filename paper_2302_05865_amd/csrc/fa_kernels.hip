@@ -129,12 +129,15 @@ __device__ __forceinline__ void unpack4(const unsigned char* src, double* x) {
   }
 }
 
-template <int T, int CPL, typename E, int WAVES>
+// SCALED: column i is multiplied by colscale[i] on its way into the matrix core, so the
+// result is diag(u) G^T G diag(u) (the weighted Gram matrix of a re-weighted PCA).
+template <int T, int CPL, typename E, int WAVES, bool SCALED>
 __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
                                                      const unsigned char* __restrict__ G,
                                                      int64_t ldg, int p, int64_t n,
                                                      int64_t ntiles,
-                                                     double* __restrict__ partials) {
+                                                     double* __restrict__ partials,
+                                                     const double* __restrict__ colscale) {
   constexpr int EPL = E::EPL;
   constexpr int LPC = 64 / CPL;            // lanes per column in one load instruction
   constexpr int R = LPC * EPL;             // rows per tile
@@ -172,6 +175,13 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
     colbase[cg] = G + (int64_t)(colon[cg] ? col : p - 1) * ldg * E::SIZE;
   }
 
+  double us[T];                            // scale of this lane's operand column in block tt
+#pragma unroll
+  for (int tt = 0; tt < T; ++tt) {
+    us[tt] = 1.0;
+    if constexpr (SCALED) us[tt] = (tt * 16 + c16 < p) ? colscale[tt * 16 + c16] : 0.0;
+  }
+
   uint4 regs[NCG];
   auto load_tile = [&](int64_t tl) {
     const int64_t row0 = tl * R + lrow;
@@ -182,6 +192,13 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
     } else {
 #pragma unroll
       for (int cg = 0; cg < NCG; ++cg) regs[cg] = load16_guarded<E>(colbase[cg], row0, n);
+    }
+  };
+  auto operand = [&](const unsigned char* src, int tt, double* x) {
+    unpack4<E>(src, x);
+    if constexpr (SCALED) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) x[j] *= us[tt];
     }
   };
 
@@ -201,13 +218,13 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
     const unsigned char* src = lds + c16 * CS + 4 * kq * E::SIZE;
     double xc[T][4], xn[T][4];
 #pragma unroll
-    for (int tt = 0; tt < T; ++tt) unpack4<E>(src + tt * 16 * CS, xc[tt]);
+    for (int tt = 0; tt < T; ++tt) operand(src + tt * 16 * CS, tt, xc[tt]);
 #pragma unroll 4
     for (int t = 0; t < NSTEP; ++t) {
       // operands of the next step (the last step re-reads step 0; harmless)
       const int tn = (t + 1 < NSTEP) ? t + 1 : 0;
 #pragma unroll
-      for (int tt = 0; tt < T; ++tt) unpack4<E>(src + tt * 16 * CS + 16 * tn * E::SIZE, xn[tt]);
+      for (int tt = 0; tt < T; ++tt) operand(src + tt * 16 * CS + 16 * tn * E::SIZE, tt, xn[tt]);
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         int tp = 0;
@@ -247,13 +264,215 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// K5: the projections of the gradients on the current basis, measured by streaming G:
+//   P = G^T (G A)   (p x m; row i is Y^T g_i for Y = G A, the quantity in the explained
+//   variance |Y^T g_i|^2 / |g_i|^2 of Sec. 2.1).
+// Same data path as the Gram kernel (coalesced loads -> LDS [column][row] -> matrix core), two
+// contractions per 16 rows: first Y_blk = G_blk A (16 rows x m) with the rows of the block as
+// the M index of the product, permuted so that the accumulator registers of Y_blk are at once
+// the B operand of the second product P += G_blk^T Y_blk (contraction over the 16 rows).
+// Y is never written anywhere.  A sits in LDS, zero-padded to 16 T x 16 TM.
+template <typename E>
+__device__ __forceinline__ double lds_elem(const unsigned char* src) {
+  if constexpr (E::SIZE == 4) return (double)*reinterpret_cast<const float*>(src);
+  else return (double)bf16_bits_to_f32(*reinterpret_cast<const uint16_t*>(src));
+}
+
+template <int T, int TM, int CPL, typename E, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void fa_proj_kernel(
+                                                     const unsigned char* __restrict__ G,
+                                                     int64_t ldg, int p, int m, int64_t n,
+                                                     int64_t ntiles,
+                                                     const double* __restrict__ Acoef,
+                                                     double* __restrict__ partials) {
+  constexpr int EPL = E::EPL;
+  constexpr int LPC = 64 / CPL;
+  constexpr int R = LPC * EPL;
+  constexpr int NCG = T * 16 / CPL;
+  constexpr int CS = R * E::SIZE + 16;
+  constexpr int NSTEP = R / 16;
+  constexpr int NTILE = T * TM;
+  constexpr int ALD = TM * 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
+  double* Alds = reinterpret_cast<double*>(lds_all);
+  unsigned char* tiles = lds_all + (size_t)T * 16 * ALD * sizeof(double);
+  const int wave = threadIdx.x >> 6;
+  unsigned char* lds = tiles + wave * (T * 16 * CS);
+  const int64_t wid = (int64_t)blockIdx.x * WAVES + wave;
+  const int64_t nwaves = (int64_t)gridDim.x * WAVES;
+  const int lane = threadIdx.x & 63;
+  const int lcol = lane / LPC;
+  const int lrow = (lane % LPC) * EPL;
+  const int c16 = lane & 15, kq = lane >> 4;
+
+  for (int idx = threadIdx.x; idx < T * 16 * ALD; idx += 64 * WAVES) {
+    const int i = idx / ALD, a = idx - i * ALD;
+    Alds[idx] = (i < p && a < m) ? Acoef[i * m + a] : 0.0;
+  }
+  for (int off = lane * 16; off < T * 16 * CS; off += 64 * 16)
+    *reinterpret_cast<uint4*>(lds + off) = make_uint4(0u, 0u, 0u, 0u);
+  __syncthreads();
+
+  v4f64 acc[NTILE];
+#pragma unroll
+  for (int i = 0; i < NTILE; ++i) acc[i] = v4f64{0.0, 0.0, 0.0, 0.0};
+
+  const unsigned char* colbase[NCG];
+  bool colon[NCG];
+#pragma unroll
+  for (int cg = 0; cg < NCG; ++cg) {
+    const int col = cg * CPL + lcol;
+    colon[cg] = col < p;
+    colbase[cg] = G + (int64_t)(colon[cg] ? col : p - 1) * ldg * E::SIZE;
+  }
+  uint4 regs[NCG];
+  auto load_tile = [&](int64_t tl) {
+    const int64_t row0 = tl * R + lrow;
+    if ((tl + 1) * R <= n) {
+#pragma unroll
+      for (int cg = 0; cg < NCG; ++cg) regs[cg] = load16_stream(colbase[cg] + row0 * E::SIZE);
+    } else {
+#pragma unroll
+      for (int cg = 0; cg < NCG; ++cg) regs[cg] = load16_guarded<E>(colbase[cg], row0, n);
+    }
+  };
+
+  // first product: lane (i = c16, k = kq) supplies G[row(i)][4 s + k] with
+  // row(i) = 4 (i mod 4) + i / 4, so that register r of lane (kq, a) of the result holds
+  // Y[4 kq + r][a]: exactly what the second product wants from that lane for its step j = r
+  const int rowA = 4 * (c16 & 3) + (c16 >> 2);
+  int64_t tile = wid;
+  if (tile < ntiles) load_tile(tile);
+  for (; tile < ntiles; tile += nwaves) {
+    wave_lds_fence();
+#pragma unroll
+    for (int cg = 0; cg < NCG; ++cg)
+      if (colon[cg])
+        *reinterpret_cast<uint4*>(lds + (cg * CPL + lcol) * CS + lrow * E::SIZE) = regs[cg];
+    wave_lds_fence();
+    const int64_t next = tile + nwaves;
+    if (next < ntiles) load_tile(next);
+
+#pragma unroll 2
+    for (int t = 0; t < NSTEP; ++t) {
+      v4f64 y[TM];
+#pragma unroll
+      for (int ta = 0; ta < TM; ++ta) y[ta] = v4f64{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const int col = 16 * tt + 4 * s + kq;
+          const double a1 = lds_elem<E>(lds + col * CS + (16 * t + rowA) * E::SIZE);
+#pragma unroll
+          for (int ta = 0; ta < TM; ++ta)
+            y[ta] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, Alds[col * ALD + 16 * ta + c16],
+                                                         y[ta], 0, 0, 0);
+        }
+      double xc[T][4];
+#pragma unroll
+      for (int tt = 0; tt < T; ++tt)
+        unpack4<E>(lds + (16 * tt + c16) * CS + (16 * t + 4 * kq) * E::SIZE, xc[tt]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int tt = 0; tt < T; ++tt)
+#pragma unroll
+          for (int ta = 0; ta < TM; ++ta)
+            acc[tt * TM + ta] = __builtin_amdgcn_mfma_f64_16x16x4f64(xc[tt][j], y[ta][j],
+                                                                     acc[tt * TM + ta], 0, 0, 0);
+    }
+  }
+
+  // one partial result per workgroup, summed over its wavefronts in wave order
+  __syncthreads();
+  double* red = reinterpret_cast<double*>(tiles);
+  double* dst = partials + (int64_t)blockIdx.x * NTILE * 256;
+#pragma unroll
+  for (int tp = 0; tp < NTILE; ++tp) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave * 256 + r * 64 + lane] = acc[tp][r];
+    __syncthreads();
+    for (int e = threadIdx.x; e < 256; e += 64 * WAVES) {
+      double tot = 0.0;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) tot += red[w * 256 + e];
+      dst[tp * 256 + e] = tot;
+    }
+    __syncthreads();
+  }
+}
+
+// K6: IRLS weights from the streamed projections (the re-streaming schedule's counterpart of
+// the residual step inside the p x p kernel): explained variances v_i = |P_i|^2 / |g_i|^2,
+// residuals 1 - v_i and 1 - |P_i - P_j|^2 / D_ij^2 (Eq. 5), the objective, the weights
+// max(residual, delta)^(-1/2), and the column scales sqrt(w_i) / |g_i| of the next weighted
+// Gram pass.  One workgroup.
+__global__ __launch_bounds__(256) void fa_restream_weights_kernel(const fa_info* __restrict__ info,
+                                                                  const double* __restrict__ P,
+                                                                  int p, int m, double coef,
+                                                                  double delta, double pair_tol,
+                                                                  fa_resume* __restrict__ rs) {
+  __shared__ double red[256];
+  const int tid = threadIdx.x;
+  const double* K = info->K;
+  double part = 0.0;
+  for (int i = tid; i < p; i += 256) {
+    const double si = K[i * p + i];
+    double pr = 0.0;
+    for (int a = 0; a < m; ++a) pr = fma(P[i * m + a], P[i * m + a], pr);
+    const double v = si > 0.0 ? pr / si : 0.0;
+    const double rho = v < 1.0 ? 1.0 - v : 0.0;
+    const double w = si > 0.0 ? 1.0 / sqrt(rho > delta ? rho : delta) : 0.0;
+    const double u = si > 0.0 ? sqrt(w / si) : 0.0;
+    rs->w[i] = w;
+    rs->v_streamed[i] = v;
+    rs->u[i] = u;
+    rs->uinv[i] = u > 0.0 ? 1.0 / u : 1.0;
+    if (si > 0.0) part += sqrt(rho);
+  }
+  for (int idx = tid; idx < p * p; idx += 256) {
+    const int i = idx / p, j = idx - i * p;
+    double cpv = 0.0;
+    if (i != j && coef > 0.0) {
+      const double si = K[i * p + i], sj = K[j * p + j];
+      const double d2 = si + sj - 2.0 * K[idx];
+      if (d2 > pair_tol * (si + sj)) {
+        double pr = 0.0;
+        for (int a = 0; a < m; ++a) {
+          const double df = P[i * m + a] - P[j * m + a];
+          pr = fma(df, df, pr);
+        }
+        const double q = pr / d2;
+        const double rho = q < 1.0 ? 1.0 - q : 0.0;
+        part += coef * sqrt(rho);                       // ordered pair (i, j)
+        cpv = -2.0 * coef / (d2 * sqrt(rho > delta ? rho : delta));
+      }
+    }
+    rs->cp[idx] = cpv;
+  }
+  red[tid] = part;
+  __syncthreads();
+  if (tid == 0) {
+    double tot = 0.0;
+    for (int t = 0; t < 256; ++t) tot += red[t];
+    const int it = rs->it0 - 1;                         // the solve whose basis was measured
+    if (it >= 0 && it < FA_ITERS_MAX) rs->obj_streamed[it] = tot;
+    rs->scaled = 1;                                     // the next Gram pass uses rs->u
+  }
+}
+
 // K2: K = sum over workgroups of their partial Grams, in a fixed order (sixteen interleaved
 // strands, each summed in four interleaved sub-strands, then combined in a fixed tree), so the
 // result does not depend on timing.  One 1024-thread block per 64 entries.
+// TM = 0: the tiles are the upper-triangular tile pairs of a symmetric p x p matrix.
+// TM > 0: the tiles are the T x TM blocks of a p x m matrix (row-major, leading dimension m).
 __global__ __launch_bounds__(1024) void fa_gram_reduce_kernel(const double* __restrict__ partials,
                                                               int nparts, int T, int p,
-                                                              double* __restrict__ K) {
-  const int NTP = T * (T + 1) / 2;
+                                                              double* __restrict__ K, int TM,
+                                                              int m) {
+  const int NTP = TM > 0 ? T * TM : T * (T + 1) / 2;
   const int ei = threadIdx.x & 63, g = threadIdx.x >> 6;   // entry, strand 0..15
   const int E = blockIdx.x * 64 + ei;                      // entry in [0, NTP*256)
   const int64_t stride = (int64_t)NTP * 256;
@@ -282,6 +501,11 @@ __global__ __launch_bounds__(1024) void fa_gram_reduce_kernel(const double* __re
     const double tot = t[0];
     const int tp = E >> 8, e = E & 255;
     const int r = e >> 6, l = e & 63;
+    if (TM > 0) {
+      const int gi = (tp / TM) * 16 + 4 * r + (l >> 4), ga = (tp % TM) * 16 + (l & 15);
+      if (gi < p && ga < m) K[gi * m + ga] = tot;
+      return;
+    }
     int ta = 0, tb = 0;
     for (int aa = 0, k = 0; aa < T; ++aa)
       for (int bb = aa; bb < T; ++bb, ++k)
@@ -383,7 +607,8 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
 __global__ __launch_bounds__(FA_IRLS_THREADS) void fa_irls_kernel(const double* __restrict__ Kg,
                                                                   fa_irls_args ar, double* cg,
                                                                   fa_info* info, double* gws,
-                                                                  int big_in_global) {
+                                                                  int big_in_global,
+                                                                  fa_resume* rs) {
   extern __shared__ __attribute__((aligned(16))) double dyn[];
   const int p = ar.p;
   const int ld = p | 1;
@@ -419,7 +644,7 @@ __global__ __launch_bounds__(FA_IRLS_THREADS) void fa_irls_kernel(const double* 
   sm.pos = qi; qi += FA_P_MAX;
   sm.order = qi; qi += FA_P_MAX;
   sm.flag = qi; qi += 8;
-  fa_irls_solve(Kg, ar, sm, cg, info);
+  fa_irls_solve(Kg, ar, sm, cg, info, rs);
 }
 
 size_t fa_irls_lds_bytes(int p, int* big_in_global) {
@@ -437,10 +662,10 @@ size_t fa_irls_lds_bytes(int p, int* big_in_global) {
 
 // ------------------------------------------------------------------------------------------
 // launchers (host).  Shapes are validated by the callers in fa_api.cpp.
-template <int T, int CPL, typename E, int WAVES>
+template <int T, int CPL, typename E, int WAVES, bool SCALED>
 static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
-                                double* partials, int* nparts, hipStream_t st,
-                                const fa_ktime* tm) {
+                                double* partials, int* nparts, const double* colscale,
+                                hipStream_t st, const fa_ktime* tm) {
   static_assert(WAVES <= FA_GRAM_WAVES_PER_CU, "partials buffer is sized for this many");
   constexpr int R = (64 / CPL) * E::EPL;
   constexpr int CS = R * E::SIZE + 16;
@@ -450,8 +675,78 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
   const size_t lds_bytes = WAVES * tile_bytes > 84 * 1024 ? WAVES * tile_bytes : 84 * 1024;
   static bool prepared = false;
   if (!prepared) {
+    hipError_t e = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(fa_gram_kernel<T, CPL, E, WAVES, SCALED>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    prepared = true;
+  }
+  const int64_t ntiles = (n + R - 1) / R;
+  int64_t wgs = (ntiles + WAVES - 1) / WAVES;
+  if (wgs > max_blocks) wgs = max_blocks;
+  *nparts = (int)wgs;
+  FA_LAUNCH(tm, (fa_gram_kernel<T, CPL, E, WAVES, SCALED>), dim3((unsigned)wgs),
+            dim3(64 * WAVES), lds_bytes, st, (const unsigned char*)G, ldg, p, n, ntiles, partials,
+            colscale);
+  return hipGetLastError();
+}
+
+template <typename E, bool SCALED>
+static hipError_t launch_gram_e(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
+                                double* partials, int* nparts, const double* colscale,
+                                hipStream_t st, const fa_ktime* tm) {
+  switch ((p + 15) / 16) {
+    case 1: return launch_gram_t<1, FA_GRAM_CPL1, E, FA_GRAM_W1, SCALED>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+    case 2: return launch_gram_t<2, 4, E, 8, SCALED>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+    case 3: return launch_gram_t<3, 4, E, 8, SCALED>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+    case 4: return launch_gram_t<4, 4, E, 8, SCALED>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                                   int max_blocks, double* partials, int* nparts,
+                                   const double* colscale, hipStream_t st, const fa_ktime* tm) {
+  if (dtype == FA_F32)
+    return colscale ? launch_gram_e<ElemF32, true>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm)
+                    : launch_gram_e<ElemF32, false>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
+  return colscale ? launch_gram_e<ElemBF16, true>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm)
+                  : launch_gram_e<ElemBF16, false>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
+}
+
+hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
+                                 hipStream_t st, const fa_ktime* tm) {
+  const int T = (p + 15) / 16;
+  const int NTP = T * (T + 1) / 2;
+  FA_LAUNCH(tm, fa_gram_reduce_kernel, dim3(NTP * 4), dim3(1024), 0, st, partials, nparts, T, p,
+            Kd, 0, 0);
+  return hipGetLastError();
+}
+
+hipError_t fa_launch_proj_reduce(const double* partials, int nparts, int p, int m, double* Td,
+                                 hipStream_t st, const fa_ktime* tm) {
+  const int T = (p + 15) / 16, TM = (m + 15) / 16;
+  FA_LAUNCH(tm, fa_gram_reduce_kernel, dim3(T * TM * 4), dim3(1024), 0, st, partials, nparts, T,
+            p, Td, TM, m);
+  return hipGetLastError();
+}
+
+template <int T, int TM, int CPL, typename E, int WAVES>
+static hipError_t launch_proj_t(const void* G, int64_t ldg, int p, int m, int64_t n,
+                                int max_blocks, const double* Acoef, double* partials,
+                                int* nparts, hipStream_t st, const fa_ktime* tm) {
+  constexpr int R = (64 / CPL) * E::EPL;
+  constexpr int CS = R * E::SIZE + 16;
+  constexpr size_t a_bytes = (size_t)T * 16 * TM * 16 * sizeof(double);
+  constexpr size_t tile_bytes = (size_t)T * 16 * CS;
+  constexpr size_t need = a_bytes + (WAVES * tile_bytes > WAVES * 2048u ? WAVES * tile_bytes
+                                                                        : WAVES * 2048u);
+  static_assert(need <= 160 * 1024, "LDS of one workgroup must fit a CU");
+  const size_t lds_bytes = need > 84 * 1024 ? need : 84 * 1024;   // one workgroup per CU
+  static bool prepared = false;
+  if (!prepared) {
     hipError_t e =
-        hipFuncSetAttribute(reinterpret_cast<const void*>(fa_gram_kernel<T, CPL, E, WAVES>),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(fa_proj_kernel<T, TM, CPL, E, WAVES>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     prepared = true;
@@ -460,57 +755,60 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
   int64_t wgs = (ntiles + WAVES - 1) / WAVES;
   if (wgs > max_blocks) wgs = max_blocks;
   *nparts = (int)wgs;
-  FA_LAUNCH(tm, (fa_gram_kernel<T, CPL, E, WAVES>), dim3((unsigned)wgs), dim3(64 * WAVES),
-            lds_bytes, st, (const unsigned char*)G, ldg, p, n, ntiles, partials);
+  FA_LAUNCH(tm, (fa_proj_kernel<T, TM, CPL, E, WAVES>), dim3((unsigned)wgs), dim3(64 * WAVES),
+            lds_bytes, st, (const unsigned char*)G, ldg, p, m, n, ntiles, Acoef, partials);
   return hipGetLastError();
 }
 
-hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
-                                   int max_blocks, double* partials, int* nparts,
-                                   hipStream_t st, const fa_ktime* tm) {
-  const int T = (p + 15) / 16;
-  hipError_t e = hipErrorInvalidValue;
-  if (dtype == FA_F32) {
-    switch (T) {
-      case 1: e = launch_gram_t<1, FA_GRAM_CPL1, ElemF32, FA_GRAM_W1>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
-      case 2: e = launch_gram_t<2, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
-      case 3: e = launch_gram_t<3, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
-      case 4: e = launch_gram_t<4, 4, ElemF32, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
-    }
-  } else {
-    switch (T) {
-      case 1: e = launch_gram_t<1, FA_GRAM_CPL1, ElemBF16, FA_GRAM_W1>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
-      case 2: e = launch_gram_t<2, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
-      case 3: e = launch_gram_t<3, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
-      case 4: e = launch_gram_t<4, 4, ElemBF16, 8>(G, ldg, p, n, max_blocks, partials, nparts, st, tm); break;
-    }
-  }
-  return e;
+template <typename E>
+static hipError_t launch_proj_e(const void* G, int64_t ldg, int p, int m, int64_t n,
+                                int max_blocks, const double* Acoef, double* partials,
+                                int* nparts, hipStream_t st, const fa_ktime* tm) {
+  const int T = (p + 15) / 16, TM = (m + 15) / 16;
+#define FA_PROJ_CASE(t, tmm, cpl, w)                                                            \
+  if (T == t && TM == tmm)                                                                      \
+    return launch_proj_t<t, tmm, cpl, E, w>(G, ldg, p, m, n, max_blocks, Acoef, partials, nparts, \
+                                            st, tm);
+  FA_PROJ_CASE(1, 1, 4, 12)
+  FA_PROJ_CASE(2, 1, 4, 8) FA_PROJ_CASE(2, 2, 4, 8)
+  // the larger tilings run four wavefronts per CU: they need more than 256 registers a lane
+  FA_PROJ_CASE(3, 1, 4, 8) FA_PROJ_CASE(3, 2, 4, 8) FA_PROJ_CASE(3, 3, 4, 4)
+  FA_PROJ_CASE(4, 1, 8, 8) FA_PROJ_CASE(4, 2, 8, 4) FA_PROJ_CASE(4, 3, 8, 4) FA_PROJ_CASE(4, 4, 8, 4)
+#undef FA_PROJ_CASE
+  return hipErrorInvalidValue;
 }
 
-hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
-                                 hipStream_t st, const fa_ktime* tm) {
-  const int T = (p + 15) / 16;
-  const int NTP = T * (T + 1) / 2;
-  FA_LAUNCH(tm, fa_gram_reduce_kernel, dim3(NTP * 4), dim3(1024), 0, st, partials, nparts, T, p,
-            Kd);
+hipError_t fa_launch_proj_partials(const void* G, int64_t ldg, int p, int m, int64_t n, int dtype,
+                                   int max_blocks, const double* Acoef, double* partials,
+                                   int* nparts, hipStream_t st, const fa_ktime* tm) {
+  if (dtype == FA_F32)
+    return launch_proj_e<ElemF32>(G, ldg, p, m, n, max_blocks, Acoef, partials, nparts, st, tm);
+  return launch_proj_e<ElemBF16>(G, ldg, p, m, n, max_blocks, Acoef, partials, nparts, st, tm);
+}
+
+hipError_t fa_launch_restream_weights(const fa_info* info_d, const double* Pd, int p, int m,
+                                      double lambda, double delta, double pair_tol, fa_resume* rs,
+                                      hipStream_t st) {
+  const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
+  hipLaunchKernelGGL(fa_restream_weights_kernel, dim3(1), dim3(256), 0, st, info_d, Pd, p, m, coef,
+                     delta, pair_tol, rs);
   return hipGetLastError();
 }
 
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double* cd,
-                          fa_info* info_d, double* gws, int solver, hipStream_t st,
-                          const fa_ktime* tm) {
+                          fa_info* info_d, double* gws, int solver, fa_resume* rs,
+                          hipStream_t st, const fa_ktime* tm) {
   if (p <= 16 && solver != 2)
     return fa_launch_irls16(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d,
-                            gws + 2 * FA_P_MAX * (FA_P_MAX + 1), solver == 0 ? 1 : 0, st, tm);
+                            gws + 2 * FA_P_MAX * (FA_P_MAX + 1), solver == 0 ? 1 : 0, rs, st, tm);
   fa_irls_args ar;
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
   ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
   int big = 0;
   const size_t lds = fa_irls_lds_bytes(p, &big);
   FA_LAUNCH(tm, fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d, gws,
-            big);
+            big, rs);
   return hipGetLastError();
 }
 

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include "fa.h"
+#include "fa_resume.h"
 
 #define FA_FN static
 #define FA_TID 0
@@ -15,9 +16,11 @@
 #define FA_SYNC() ((void)0)
 #include "fa_irls_core.inc"
 
-extern "C" int fa_irls_emulate(const double* K, int p, int m, double lambda, int iters, double tol,
-                               double delta, double rank_tol, double pair_tol, double* c,
-                               fa_info* info) {
+// launches = 1: the whole IRLS in one call of the solver.  launches > 1: the same IRLS driven
+// one solve per call through the resume state, as the re-streaming schedule drives it.
+static int emulate(const double* K, int p, int m, double lambda, int iters, double tol,
+                   double delta, double rank_tol, double pair_tol, double* c, fa_info* info,
+                   int stepwise) {
   if (p < 1 || p > FA_P_MAX || m < 1 || m > p || iters < 1 || iters > FA_ITERS_MAX) return 1;
   const int ld = p | 1;
   const size_t msz = (size_t)p * ld;
@@ -40,7 +43,31 @@ extern "C" int fa_irls_emulate(const double* K, int p, int m, double lambda, int
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol; ar.delta = delta;
   ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
   memset(info, 0, sizeof(*info));
-  fa_irls_solve(K, ar, sm, c, info);
+  if (!stepwise) {
+    fa_irls_solve(K, ar, sm, c, info, (fa_resume*)0);
+  } else {
+    fa_resume* rs = (fa_resume*)calloc(1, sizeof(fa_resume));
+    if (!rs) return 2;
+    ar.iters = 1;
+    for (int it = 0; it < iters; ++it) {
+      fa_irls_solve(K, ar, sm, c, info, rs);
+      if (info->iters_done < it + 1) break;   // cannot happen: one solve per call
+      if (it > 0 && tol > 0.0 && fabs(info->objective[it - 1] - info->objective[it]) < tol) break;
+    }
+    free(rs);
+  }
   free(buf); free(ibuf);
   return 0;
+}
+
+extern "C" int fa_irls_emulate(const double* K, int p, int m, double lambda, int iters, double tol,
+                               double delta, double rank_tol, double pair_tol, double* c,
+                               fa_info* info) {
+  return emulate(K, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, c, info, 0);
+}
+
+extern "C" int fa_irls_emulate_stepwise(const double* K, int p, int m, double lambda, int iters,
+                                        double tol, double delta, double rank_tol,
+                                        double pair_tol, double* c, fa_info* info) {
+  return emulate(K, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, c, info, 1);
 }

@@ -320,3 +320,52 @@ def test_single_kernels_enqueued_one_by_one_equal_the_whole_call(agg_f32):
     torch.cuda.synchronize()
     assert torch.equal(out, whole)
     assert np.array_equal(agg_f32.fa_gram(dev), K_whole)
+
+
+# ---------------------------------------------------------------- re-streaming schedule
+def _check_restream(agg, w, seed, n_gate=GATE):
+    Gw, _ = si.make_inputs(w, seed)
+    ref = fa_scaled(Gw, w.m, w.lam, w.iters, 0.0)
+    dev = to_device(Gw)
+    once = agg.fa_aggregate(dev, w.m, w.lam, w.iters, 0.0).clone()
+    out = agg.fa_aggregate_restream(dev, w.m, w.lam, w.iters)
+    info = agg.fa_get_info()
+    _, v_s, obj_s = agg.fa_get_restream_info()
+    got = out.cpu().numpy().astype(np.float64)
+    e_once = rel_l2(got, once.cpu().numpy().astype(np.float64))
+    e_out = rel_l2(got, ref["out"])
+    e_proj = projector_difference(info.A, ref["A"], ref["R"])
+    announce("restream", w.name, "vs gram-once", e_once, "vs oracle", e_out, "proj", e_proj,
+             "max |v_streamed - v|", np.abs(v_s - ref["v"]).max())
+    assert info.status == 0 and info.iters_done == w.iters
+    assert e_once <= 1e-5 and e_out <= n_gate and e_proj <= n_gate
+    # the streamed explained variances and the streamed objective are the oracle's
+    assert np.allclose(v_s, ref["v"], atol=1e-6)
+    assert np.allclose(obj_s[:w.iters], ref["objective"], atol=1e-5)
+    assert np.allclose(info.objective, ref["objective"], atol=1e-5)
+
+
+@pytest.mark.parametrize("name,n", [("cfg1", 100_000), ("cfg2", 300_007), ("cfg3", 200_001)])
+def test_restream_schedule_matches_gram_once_and_oracle(agg_f32, name, n):
+    """Two passes over G per IRLS solve (weighted Gram, streamed projections) must give what
+    the two-pass default schedule gives."""
+    _check_restream(agg_f32, si.WORKLOADS[name].with_n(n), 0)
+
+
+def test_restream_schedule_largest_p(agg_f32):
+    _check_restream(agg_f32, si.WORKLOADS["cfg5"].with_n(60_001).with_lam(1.0), 0)
+
+
+def test_restream_schedule_bf16(agg_bf16):
+    _check_restream(agg_bf16, si.WORKLOADS["cfg4"].with_n(80_003), 0)
+
+
+def test_restream_with_duplicate_and_zero_columns(agg_f32):
+    announce("restream: zero column + duplicates")
+    Gw = si.random_dense(7, 30_001, seed=13)
+    Gw[2] = 0.0
+    Gw[5] = Gw[1]
+    ref = fa_scaled(Gw, 3, 1.0, 6, 0.0)
+    out = agg_f32.fa_aggregate_restream(to_device(Gw), 3, 1.0, 6).cpu().numpy()
+    assert agg_f32.fa_get_info().rank == 5
+    assert rel_l2(out, ref["out"]) <= GATE

@@ -27,15 +27,16 @@ def emul(tmp_path_factory):
                            os.path.join(ROOT, "tests", "emul", "irls_emul.cpp"), "-o", str(out)])
     lib = ctypes.CDLL(str(out))
 
-    def run(K, m, lam, iters, tol, delta=1e-6, rank_tol=1e-12, pair_tol=1e-12):
+    def run(K, m, lam, iters, tol, delta=1e-6, rank_tol=1e-12, pair_tol=1e-12, stepwise=False):
         K = np.ascontiguousarray(K, dtype=np.float64)
         p = K.shape[0]
         info = FaInfo()
         c = np.zeros(p)
         d = ctypes.c_double
-        rc = lib.fa_irls_emulate(K.ctypes.data_as(ctypes.c_void_p), p, m, d(lam), iters, d(tol),
-                                 d(delta), d(rank_tol), d(pair_tol),
-                                 c.ctypes.data_as(ctypes.c_void_p), ctypes.byref(info))
+        fn = lib.fa_irls_emulate_stepwise if stepwise else lib.fa_irls_emulate
+        rc = fn(K.ctypes.data_as(ctypes.c_void_p), p, m, d(lam), iters, d(tol),
+                d(delta), d(rank_tol), d(pair_tol),
+                c.ctypes.data_as(ctypes.c_void_p), ctypes.byref(info))
         assert rc == 0
         return c, info
     return run
@@ -105,3 +106,20 @@ def test_solver_text_stop_rule(emul):
     assert np.allclose(np.array(info.w[:7]), early["w"], rtol=1e-8)
     c, info = emul(G.T @ G, 3, 1.0, 30, 0.0)
     assert np.allclose(np.array(info.w[:7]), full["w"], rtol=1e-6)
+
+
+@pytest.mark.parametrize("name,n", [("cfg1", 20000), ("cfg2", 50000), ("cfg5", 20000)])
+def test_one_solve_per_call_through_the_resume_state_equals_one_call(emul, name, n):
+    """The re-streaming schedule drives the IRLS one solve per launch; the weights travel
+    through the resume state.  Same iterates as the single call (the eigenbasis restarts, so
+    equal to rounding, not bitwise)."""
+    w = si.WORKLOADS[name].with_n(n)
+    Gw, _ = si.make_inputs(w, 0)
+    G = as_f64_matrix(Gw)
+    K = G.T @ G
+    c1, i1 = emul(K, w.m, w.lam, w.iters, 0.0)
+    c2, i2 = emul(K, w.m, w.lam, w.iters, 0.0, stepwise=True)
+    assert i2.iters_done == w.iters == i1.iters_done
+    assert np.allclose(np.array(i2.objective[:w.iters]), np.array(i1.objective[:w.iters]),
+                       rtol=0, atol=1e-10)
+    assert np.linalg.norm(G @ (c1 - c2)) <= 1e-10 * np.linalg.norm(G @ c1)
