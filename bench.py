@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # HBM traffic of the two streaming kernels per launch, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script (profiles/pmc_cfg2.md: counter values, calibration
 # against a plain copy of known size, and the commands).
-MEASURED_TRAFFIC_BYTES = {"fa_gram_kernel": 6.726e8, "fa_combine_kernel": 7.168e8}
+MEASURED_TRAFFIC_BYTES = {"fa_gram_kernel": 6.726e8, "fa_combine_kernel": 7.183e8}
 
 
 def main() -> int:
@@ -45,6 +45,9 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--n", type=int, default=0, help="override n (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--schedule", choices=["both", "gram-once", "restream"], default="both",
+                    help="which schedules to run: the default two-pass one (the metric), the "
+                         "re-streaming one (extra figures in the 'restream' object), or both")
     ap.add_argument("--alone", action="store_true",
                     help="also time each kernel in a back-to-back loop of its own")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -90,26 +93,29 @@ def main() -> int:
         counter[0] += 1
         agg.fa_aggregate(g, w.m, w.lam, w.iters, 0.0, out=out)
 
+    do_main = args.schedule in ("both", "gram-once")
+    do_rs = args.schedule in ("both", "restream")
     # ---- region 1: whole aggregations -------------------------------------------------------
-    for _ in range(args.warmup):
+    main_steps = args.steps if do_main else 1
+    for _ in range(args.warmup if do_main else 1):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(main_steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
-    value = args.steps / elapsed
+    ms_per_step = 1e3 * elapsed / main_steps
+    value = main_steps / elapsed
 
     # ---- region 2: per-dispatch events inside the step --------------------------------------
     agg.fa_set_profiling(True)
     kms_in = np.zeros(4)
-    for _ in range(args.steps):
+    for _ in range(main_steps):
         step()
         kms_in += agg.fa_get_timings()
     agg.fa_set_profiling(False)
-    kms_in /= args.steps
+    kms_in /= main_steps
 
     # ---- region 3: each kernel alone, many launches between two events ----------------------
     def time_alone(which):
@@ -123,26 +129,30 @@ def main() -> int:
         e1.synchronize()
         return e0.elapsed_time(e1) / args.steps
 
-    kms_alone = np.array([time_alone(k) for k in range(4)]) if args.alone else None
+    kms_alone = np.array([time_alone(k) for k in range(4)]) if (args.alone and do_main) else None
     kms = kms_in
 
     # ---- the re-streaming schedule (measurement only: two passes over G per IRLS solve) ------
-    rsteps = max(2, args.steps // 10)
-    for i in range(2):
-        agg.fa_aggregate_restream(devs[i & 1], w.m, w.lam, w.iters, out=out)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(rsteps):
-        agg.fa_aggregate_restream(devs[i & 1], w.m, w.lam, w.iters, out=out)
-    torch.cuda.synchronize()
-    r_elapsed = time.perf_counter() - t0
-    agg.fa_set_profiling(True)
-    rms = np.zeros(2)
-    for i in range(rsteps):
-        agg.fa_aggregate_restream(devs[i & 1], w.m, w.lam, w.iters, out=out)
-        rms += agg.fa_get_restream_info(timings=True)[0]
-    agg.fa_set_profiling(False)
-    rms /= rsteps
+    def time_restream():
+        rsteps = max(2, args.steps // 10)
+        for i in range(2):
+            agg.fa_aggregate_restream(devs[i & 1], w.m, w.lam, w.iters, out=out)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(rsteps):
+            agg.fa_aggregate_restream(devs[i & 1], w.m, w.lam, w.iters, out=out)
+        torch.cuda.synchronize()
+        r_elapsed = time.perf_counter() - t0
+        agg.fa_set_profiling(True)
+        rms = np.zeros(2)
+        for i in range(rsteps):
+            agg.fa_aggregate_restream(devs[i & 1], w.m, w.lam, w.iters, out=out)
+            rms += agg.fa_get_restream_info(timings=True)[0]
+        agg.fa_set_profiling(False)
+        return rsteps, r_elapsed, rms / rsteps
+
+    if do_rs:
+        rsteps, r_elapsed, rms = time_restream()
 
     # leave the result of the seed-0 set in `out` / info for the parity check below
     counter[0] = 0
@@ -181,7 +191,7 @@ def main() -> int:
                               "traffic": MEASURED_TRAFFIC_BYTES["fa_combine_kernel"]},
     }
 
-    restream = {
+    restream = None if not do_rs else {
         "aggregations_per_s": rsteps / r_elapsed, "ms_per_aggregation": 1e3 * r_elapsed / rsteps,
         "ms_per_irls_iteration": 1e3 * r_elapsed / rsteps / w.iters, "steps": rsteps,
         "algorithmic_bytes_per_aggregation": (2 * w.iters + 1) * gram_bytes + 4.0 * w.n,
@@ -198,7 +208,7 @@ def main() -> int:
 
     result = {
         "metric": "FA aggregations/sec + achieved HBM GB/s (% peak), p=15 n=11.2M fp32",
-        "value": value, "unit": "aggregations/s", "n_gpus": 1, "steps": args.steps,
+        "value": value, "unit": "aggregations/s", "n_gpus": 1, "steps": main_steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{w.name}: p={w.p} n={w.n} m={w.m} lambda={w.lam} "
@@ -208,8 +218,11 @@ def main() -> int:
         "kernels": kernels,
         "hbm_gbs": {"gram": gram_gbs, "combine": comb_gbs,
                     "whole_step": (gram_bytes + comb_bytes) / (ms_per_step * 1e-3) / 1e9},
-        "restream": restream,
     }
+    if do_rs:
+        result["restream"] = restream
+    if not do_main:
+        result["note"] = "--schedule restream: value/kernels come from a single default step"
 
     if not args.no_cpu_baseline:
         from oracle import fa_scaled, projector_difference
