@@ -266,7 +266,7 @@ struct Fmem {
   double Um[16 * LDF];   // orthonormal basis of range(P) (r x mm), as rows: Um[k][a]
   double Am[16 * LDF];   // A (p x m)
   __attribute__((aligned(16))) double Zs[16 * LDZ];   // (I-P) R by columns
-  double s[16], dinv[16], r1[16], beta[16];
+  double s[16], dinv[16], r1[16], beta[16], rinv[16];
   int piv[16];
 };
 
@@ -327,36 +327,62 @@ __device__ __forceinline__ v4d mm16(const v4d& a, const v4d& b) {
   return acc;
 }
 
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_u32(unsigned x) {
+  return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+
 // Greedy diagonal-pivoted Cholesky of the PSD matrix S (16 x 16 in LDS): rows[k][j] with
-// rows^T rows = S.  Stops at max_rank rows or when the largest remaining diagonal entry is
-// <= tol.  Executed by all 64 lanes (the four 16-lane rows do the same work).  Returns the
-// number of rows; piv[k] is the column chosen at step k.
-__device__ int pivoted_cholesky(const double* S, double* rows, int* piv, double tol, int max_rank,
-                                int lane) {
+// rows^T rows = S.  Stops at max_rank rows or when the chosen remaining diagonal entry is
+// <= tol.  Executed by all 64 lanes (the four 16-lane rows do the same work).  The pivot is
+// the largest remaining diagonal entry as seen in fp32 (any near-largest pivot serves; ties go
+// to the lowest index).  The loops are kept rolled on purpose: this code runs once per call,
+// and straight-line code that is executed once costs more in instruction fetch than it
+// saves.  It must be inlined: as a called function it slowed the whole solver by 10 %.
+// Returns the number of rows; piv[k] is the column chosen at step k, rinv[k] = 1/rows[k][piv[k]].
+#ifndef FA_CHOL_ATTR
+#define FA_CHOL_ATTR __forceinline__
+#endif
+__device__ FA_CHOL_ATTR int pivoted_cholesky(const double* S, double* rows, int* piv, double* rinv,
+                                             double tol, int max_rank, int lane) {
   const int j = lane & 15;
   double d = S[j * LDF + j];
   bool used = false;
   int rank = 0;
+#pragma unroll 1
   for (int k = 0; k < max_rank; ++k) {
-    const double mx = lane_bcast(row_max(used ? -1.0 : d), 0);
-    if (!(mx > tol)) break;
-    const unsigned long long bal = __ballot(!used && d == mx) & 0xffffull;
-    const int pv = __ffsll((long long)bal) - 1;
-    double acc = S[pv * LDF + j];
-    for (int a = 0; a < k; ++a) acc -= rows[a * LDF + pv] * rows[a * LDF + j];
+    const float df = (!used && d > 0.0) ? (float)d : 0.0f;
+    unsigned key = (__float_as_uint(df) & ~15u) | (unsigned)(15 - j);
+    key = max(key, dpp_u32<0x128>(key));   // row_ror:8
+    key = max(key, dpp_u32<0x124>(key));   // row_ror:4
+    key = max(key, dpp_u32<0x122>(key));   // row_ror:2
+    key = max(key, dpp_u32<0x121>(key));   // row_ror:1
+    const int pv = 15 - (int)(__builtin_amdgcn_readfirstlane((int)key) & 15);
+    const double dpv = lane_bcast(used ? -1.0 : d, pv);
+    if (!(dpv > tol)) break;
+    double a0 = S[pv * LDF + j], a1 = 0.0;
+    int a = 0;
+#pragma unroll 1
+    for (; a + 1 < k; a += 2) {
+      a0 = fma(-rows[a * LDF + pv], rows[a * LDF + j], a0);
+      a1 = fma(-rows[(a + 1) * LDF + pv], rows[(a + 1) * LDF + j], a1);
+    }
+    if (a < k) a0 = fma(-rows[a * LDF + pv], rows[a * LDF + j], a0);
+    const double acc = a0 + a1;
     const double dp = lane_bcast(acc, pv);           // recomputed pivot value S_k[pv][pv]
     if (!(dp > 0.0)) break;
-    const double rk = used ? 0.0 : acc / sqrt(dp);
+    const double rs = rsq_nr<2>(dp);
+    const double rk = used ? 0.0 : acc * rs;
     if (lane < 16) rows[k * LDF + j] = rk;
-    if (lane == 0) piv[k] = pv;
-    d -= rk * rk;
+    if (lane == 0) { piv[k] = pv; rinv[k] = rs; }
+    d = fma(-rk, rk, d);
     if (j == pv) used = true;
     rank = k + 1;
     wave_fence();
   }
   for (int k = rank; k < 16; ++k) {
     if (lane < 16) rows[k * LDF + j] = 0.0;
-    if (lane == 0) piv[k] = 0;
+    if (lane == 0) { piv[k] = 0; rinv[k] = 0.0; }
   }
   wave_fence();
   return rank;
@@ -430,16 +456,40 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   wave_fence();
 
   // ---- R from the pivoted Cholesky factorisation of K~; rank; right inverse --------------
-  const int rank = pivoted_cholesky(fm.Kt, fm.Rt, fm.piv, rank_tol, 16, lane);
-  // Xi = inverse of the (upper triangular, in pivot order) block R~[:, piv]; lane c16 solves
-  // for column c16 by back substitution
-  for (int k = rank - 1; k >= 0; --k) {
-    double acc = (k == c16) ? 1.0 : 0.0;
-    for (int l = k + 1; l < rank; ++l) acc -= fm.Rt[k * LDF + fm.piv[l]] * fm.Xi[l * LDF + c16];
-    const double xv = acc / fm.Rt[k * LDF + fm.piv[k]];
-    if (lane < 16) fm.Xi[k * LDF + c16] = (c16 < rank) ? xv : 0.0;
+#ifdef FA_K3_TIMING
+  const long long ts1 = clock64();
+#endif
+  const int rank = pivoted_cholesky(fm.Kt, fm.Rt, fm.piv, fm.rinv, rank_tol, 16, lane);
+#ifdef FA_K3_TIMING
+  const long long ts2 = clock64();
+#endif
+  // Xi = inverse of the (upper triangular, in pivot order) block U = R~[:, piv]; lane c16
+  // solves U x = e_c16 by back substitution, column-oriented: once x_k is known it is taken
+  // out of all earlier equations at once (independent multiply-adds, no dependent chain)
+  {
+    double bcol[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) bcol[i] = (i == c16) ? 1.0 : 0.0;
+#pragma unroll
+    for (int k = 15; k >= 0; --k) {
+      if (k < rank) {
+        const double xk = bcol[k] * fm.rinv[k];
+        const int pk = fm.piv[k];
+#pragma unroll
+        for (int i = 0; i < k; ++i) bcol[i] = fma(-fm.Rt[i * LDF + pk], xk, bcol[i]);
+        bcol[k] = xk;
+      } else {
+        bcol[k] = 0.0;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (lane < 16) fm.Xi[k * LDF + c16] = (c16 < rank) ? bcol[k] : 0.0;
     wave_fence();
   }
+#ifdef FA_K3_TIMING
+  const long long ts3 = clock64();
+#endif
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int i = 4 * r + q4;
@@ -460,9 +510,10 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     rb[s] = fm.Rr[(4 * s + q4) * LDF + c16];
   }
   if (lane < 16) {
-    double acc = 0.0;
-    for (int jj = 0; jj < 16; ++jj) acc += fm.Rr[lane * LDF + jj];
-    fm.r1[lane] = acc;                                 // R 1
+    double a4[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) a4[jj & 3] += fm.Rr[lane * LDF + jj];
+    fm.r1[lane] = (a4[0] + a4[1]) + (a4[2] + a4[3]);   // R 1
   }
   wave_fence();
 
@@ -527,42 +578,39 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
       // only reduction per step is |X|_F^2, and its result is not needed before the end of
       // the *next* step: the reduction is split in two halves (second half for X_{k-1},
       // first half for X_k) issued beside the four matrix-core instructions of X_k^2.
-      // Convergence is read off the same numbers one step late: trace(X_{k-1}) - |X_{k-1}|_F^2
-      // is the distance of X_{k-1} from a projector.  The carried trace drifts by rounding
-      // (the error doubles along a run of non-squaring steps), so once that distance is below
-      // 1e-8 the trace of every iterate is measured exactly, and the final test uses two
-      // directly measured numbers.  Two steps after 1e-8 the iteration has converged (each
-      // step squares the error at one end of the spectrum and doubles it at the other).
+      // The same numbers, one step late, say when X is nearly a projector:
+      // trace(X_{k-1}) - |X_{k-1}|_F^2 is the distance of X_{k-1} from idempotency.  The flag
+      // is acted upon at the top of the next step (a branch on a value computed long before
+      // costs nothing; a branch on the end of the reduction chain would stall every step):
+      // two steps after the distance fell below 1e-8 the iterate has converged (each step
+      // squares the error at one end of the spectrum and doubles it at the other), and there
+      // trace and |X|_F^2 are measured exactly, because the carried trace drifts by rounding.
       double tXp = 2.0, tX = hi * sc;      // trace(X_{k-1}) (dummy for k = 0), trace(X_k)
       double pend = tX * (1.0 / 16.0);     // stage-1 partial of |X_{k-1}|_F^2: stage 2 gives tX
       bool sqp = true;                     // with the above, step 0 computes trace(X_0) = tX
-      bool conv = false, exact_p = false;   // exact_p: tXp was measured, not carried
+      bool conv = false, near = false;
       int k_end = MAX_PURIFY;
       for (int k = 0; k < MAX_PURIFY; ++k) {
-        const v4d y = mm16(x, x);
-        const double tYp = fro2_stage2(pend);              // |X_{k-1}|_F^2
-        pend = fro2_stage1(x);
-        tX = sqp ? tYp : fma(2.0, tXp, -tYp);              // trace(X_k)
-        const double idem = tXp - tYp;                     // trace(X_{k-1} - X_{k-1}^2)
-#ifdef FA_K3_DEBUG
-        if (it == 0 && k < 120 && lane == 0) { info->objective[k] = tX; info->objective[120 + k] = idem; }
-#endif
-        bool exact = false;
-        if (idem < 1e-8) {
-          if (exact_p && idem < 1e-12) {
-            // X_{k-1} is a projector to working precision and x = X_k is its successor; it
-            // is the wanted projector only if the trace is m (the maps are monotone, so
-            // the eigenvalue order is kept whatever the steering did)
-            conv = fabs(tXp - (double)mm) < 0.25;
-            k_end = k;
-            break;
-          }
+        if (near) {
           double td = 0.0;
 #pragma unroll
           for (int r = 0; r < 4; ++r) td += isdiag[r] ? x[r] : 0.0;
           tX = wave_sum(td);
-          exact = true;
+          if (tX - fro2_stage2(fro2_stage1(x)) < 1e-12) {
+            // idempotent; it is the wanted projector only if its trace is m (the maps are
+            // monotone, so the eigenvalue order is kept whatever the steering did)
+            conv = fabs(tX - (double)mm) < 0.25;
+            k_end = k;
+            break;
+          }
+          // not yet: go on from the exact trace
+          tXp = 2.0; sqp = true; pend = tX * (1.0 / 16.0);
         }
+        const v4d y = mm16(x, x);
+        const double tYp = fro2_stage2(pend);              // |X_{k-1}|_F^2
+        pend = fro2_stage1(x);
+        tX = sqp ? tYp : fma(2.0, tXp, -tYp);              // trace(X_k)
+        near = (tXp - tYp < 1e-8);
         const bool sq = tX > (double)mm;
         if (sq) {
 #pragma unroll
@@ -573,7 +621,6 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
         }
         tXp = tX;
         sqp = sq;
-        exact_p = exact;
         steps = steps + 1;
       }
       if (!conv) return -(1000 + it * 1000 + k_end);
@@ -643,7 +690,13 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   }
   wave_fence();
   // P = U U^T with orthonormal U: the rows produced by the pivoted Cholesky of a projector
-  const int nb = pivoted_cholesky(fm.Ps, fm.Um, fm.piv, 1e-6, mm, lane);
+#ifdef FA_K3_TIMING
+  const long long te1 = clock64();
+#endif
+  const int nb = pivoted_cholesky(fm.Ps, fm.Um, fm.piv, fm.rinv, 1e-6, mm, lane);
+#ifdef FA_K3_TIMING
+  const long long te2 = clock64();
+#endif
   if (nb != mm) return -2;
   v4d ba, ub;   // B as A operand: B[c16][4s+q4];  U_m as B operand: U[a = 4s+q4][k = c16]
 #pragma unroll
@@ -653,9 +706,10 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   }
   const v4d am = mm16(ba, ub);                           // A[4r+q4][c16]
   if (lane < 16) {
-    double acc = 0.0;
-    for (int a = 0; a < 16; ++a) acc += fm.Um[lane * LDF + a] * fm.r1[a];
-    fm.beta[lane] = acc;                                 // (U_m^T R 1)[k]
+    double a4[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int a = 0; a < 16; ++a) a4[a & 3] = fma(fm.Um[lane * LDF + a], fm.r1[a], a4[a & 3]);
+    fm.beta[lane] = (a4[0] + a4[1]) + (a4[2] + a4[3]);   // (U_m^T R 1)[k]
   }
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -665,8 +719,10 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   }
   wave_fence();
   if (lane < 16 && lane < p) {
-    double acc = 0.0;
-    for (int k = 0; k < 16; ++k) acc += fm.Am[lane * LDF + k] * fm.beta[k];
+    double a4[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int k = 0; k < 16; ++k) a4[k & 3] = fma(fm.Am[lane * LDF + k], fm.beta[k], a4[k & 3]);
+    double acc = (a4[0] + a4[1]) + (a4[2] + a4[3]);
     acc /= (double)p;
     cg[lane] = acc;
     info->c[lane] = acc;
@@ -688,6 +744,10 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     info->objective[FA_ITERS_MAX - 3] = (double)tk_res;
     info->objective[FA_ITERS_MAX - 4] = (double)tk_mm;
     info->objective[FA_ITERS_MAX - 5] = (double)tk_setup;
+    info->objective[FA_ITERS_MAX - 6] = (double)(ts1 - tk0);      // before the first Cholesky
+    info->objective[FA_ITERS_MAX - 7] = (double)(ts2 - ts1);      // Cholesky of the Gram
+    info->objective[FA_ITERS_MAX - 8] = (double)(ts3 - ts2);      // triangular inverse
+    info->objective[FA_ITERS_MAX - 9] = (double)(te2 - te1);      // Cholesky of the projector
 #endif
   }
   // weights for the solve that would come next (only once nothing above can fail any more:
