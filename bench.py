@@ -30,6 +30,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+FP64_MFMA_PEAK_TFLOPS = 78.6   # MI355X fp64 matrix, published
 
 # HBM traffic of the two streaming kernels per launch, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script (profiles/pmc_cfg2.md: counter values, calibration
@@ -45,6 +46,11 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--n", type=int, default=0, help="override n (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--device-inputs", action="store_true",
+                    help="performance only: draw the gradient sets on the GPU (same recipe shapes, "
+                         "torch's generator instead of the seeded NumPy stream the parity tests "
+                         "use); for the configurations whose host generation takes minutes.  "
+                         "No oracle comparison is made.")
     ap.add_argument("--schedule", choices=["both", "gram-once", "restream"], default="both",
                     help="which schedules to run: the default two-pass one (the metric), the "
                          "re-streaming one (extra figures in the 'restream' object), or both")
@@ -78,12 +84,70 @@ def main() -> int:
     # Two different gradient sets (seeds 0 and 1) are aggregated alternately, so that no step
     # finds its input in a cache because the previous step left it there; within one step
     # the second pass over G may reuse what the first one left, as it would in production.
+    def draw_on_device(seed):
+        """The workload's recipe with torch's device generator (shapes, scales and attack
+        styles of synth_inputs.make_inputs; not the same numbers)."""
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed)
+        rn = lambda: torch.randn(w.n, device="cuda", generator=g)
+        tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+        G = torch.empty((w.p, w.n), dtype=tdt, device="cuda")
+        mu = rn()
+        sigma = 0.5 * float(mu.square().mean().sqrt())
+        byz = set(torch.randperm(w.p, generator=torch.Generator().manual_seed(seed))[:w.f].tolist())
+        if w.recipe == "lowrank_noise":
+            U = [rn() for _ in range(4)]
+        if w.recipe == "two_cluster":
+            mu2 = rn()
+        for i in range(w.p):
+            if w.recipe == "signflip10":
+                col = -10.0 * mu if i in byz else mu + 0.1 * rn()
+            elif w.recipe == "mixed_attack":
+                if i in byz:
+                    kind = i % 3
+                    if kind == 0:
+                        col = 10.0 * sigma * rn()
+                    elif kind == 1:
+                        col = -4.0 * mu
+                    else:
+                        u = rn()
+                        col = u * (1000.0 / float(u.norm()))
+                else:
+                    col = mu + sigma * rn()
+            elif w.recipe == "student_collude":
+                if i in byz:
+                    col = -mu + 0.1 * rn()
+                else:
+                    chi2 = rn().square() + rn().square() + rn().square()
+                    col = mu + sigma * rn() / (chi2 / 3.0).sqrt()
+            elif w.recipe == "lowrank_noise":
+                if i in byz:
+                    col = 10.0 * sigma * rn()
+                else:
+                    z = torch.randn(4, generator=torch.Generator().manual_seed(1000 * seed + i))
+                    col = mu + sigma * rn()
+                    for k in range(4):
+                        col += float(z[k]) * U[k]
+            else:   # two_cluster
+                if i in byz:
+                    col = -4.0 * mu if (i % 2 == 0) else 10.0 * sigma * rn()
+                else:
+                    col = (mu if (i % 10) < 7 else mu2) + sigma * rn()
+            G[i] = col.to(tdt)
+        return G
+
     t0 = time.time()
-    Gw, _ = si.make_inputs(w, 0)
-    Gw1, _ = si.make_inputs(w, 1)
+    if args.device_inputs:
+        devs = [draw_on_device(0), draw_on_device(1)]
+        torch.cuda.synchronize()
+        Gw = None
+        args.no_cpu_baseline = True
+    else:
+        Gw, _ = si.make_inputs(w, 0)
+        Gw1, _ = si.make_inputs(w, 1)
+        devs = [upload(Gw), upload(Gw1)]
+        del Gw1
     gen_s = time.time() - t0
-    devs = [upload(Gw), upload(Gw1)]
-    del Gw1
     out = torch.empty(w.n, dtype=torch.float32, device="cuda")
     agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype)
     counter = [0]
@@ -175,20 +239,31 @@ def main() -> int:
     # the roofline entry is for the longer of the two streaming kernels
     dom = "fa_gram_kernel" if kms[0] >= kms[3] else "fa_combine_kernel"
     dom_gbs = gram_gbs if dom == "fa_gram_kernel" else comb_gbs
+    traffic = MEASURED_TRAFFIC_BYTES if w.name == "cfg2" and not args.n else {}
     roofline = {"kernel": dom, "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
-                "traffic": MEASURED_TRAFFIC_BYTES[dom]}
+                "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic.get(dom)}
+    # the Gram pass of a wide problem is bound by the fp64 matrix core, not by HBM: price it
+    # against that roof when it is the nearer one (algorithmic flops: n p (p + 1), the
+    # symmetric half of G^T G, one multiply and one add per term)
+    gram_tflops = float(w.n) * w.p * (w.p + 1) / (kms[0] * 1e-3) / 1e12
+    if dom == "fa_gram_kernel" and gram_tflops / FP64_MFMA_PEAK_TFLOPS > gram_gbs / HBM_PEAK_GBS:
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": gram_tflops,
+                    "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": gram_tflops / FP64_MFMA_PEAK_TFLOPS, "traffic": traffic.get(dom)}
+    k3_name = "fa_irls16_kernel" if w.p <= 16 else "fa_irls_kernel"
     kernels = {
         "fa_gram_kernel": {"ms_in_step": kms_in[0], "algorithmic_bytes": gram_bytes,
                            "GB/s": gram_gbs, "frac_hbm_peak": gram_gbs / HBM_PEAK_GBS,
-                           "traffic": MEASURED_TRAFFIC_BYTES["fa_gram_kernel"]},
+                           "TFLOP/s": gram_tflops,
+                           "frac_fp64_mfma_peak": gram_tflops / FP64_MFMA_PEAK_TFLOPS,
+                           "traffic": traffic.get("fa_gram_kernel")},
         "fa_gram_reduce_kernel": {"ms_in_step": kms_in[1]},
-        "fa_irls16_kernel": {"ms_in_step": kms_in[2], "bound": "latency",
-                             "purification_steps": info.sweeps},
+        k3_name: {"ms_in_step": kms_in[2], "bound": "latency",
+                  ("purification_steps" if w.p <= 16 else "jacobi_sweeps"): info.sweeps},
         "fa_combine_kernel": {"ms_in_step": kms_in[3],
                               "algorithmic_bytes": comb_bytes, "GB/s": comb_gbs,
                               "frac_hbm_peak": comb_gbs / HBM_PEAK_GBS,
-                              "traffic": MEASURED_TRAFFIC_BYTES["fa_combine_kernel"]},
+                              "traffic": traffic.get("fa_combine_kernel")},
     }
 
     restream = None if not do_rs else {
@@ -207,10 +282,13 @@ def main() -> int:
             kernels[name]["ms_alone"] = kms_alone[k]
 
     result = {
-        "metric": "FA aggregations/sec + achieved HBM GB/s (% peak), p=15 n=11.2M fp32",
+        "metric": "FA aggregations/sec + achieved HBM GB/s (% peak), p=15 n=11.2M fp32"
+                  if w.name == "cfg2" and not args.n else
+                  f"FA aggregations/sec + achieved HBM GB/s (% peak), {w.name}",
         "value": value, "unit": "aggregations/s", "n_gpus": 1, "steps": main_steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic (drawn on the device)" if args.device_inputs else "synthetic",
         "config": {"workload": f"{w.name}: p={w.p} n={w.n} m={w.m} lambda={w.lam} "
                                f"iters={w.iters} storage={w.dtype}",
                    "schedule": "gram-once", "inputs": "seeds 0 and 1 alternating"},

@@ -1,10 +1,14 @@
 // HIP kernels of the Flag Aggregator hot path for gfx950 (MI355X), and their launchers.
 //
 //   K1 fa_gram_kernel        norms + Gram matrix K = G^T G, one streaming pass over G
-//   K2 fa_gram_reduce_kernel fixed-order reduction of the per-wave partial Grams
-//   K3 fa_irls_kernel        the p x p part: normalisation, IRLS (weighted PCA by Jacobi),
-//                            coefficients c with out = G c
+//                            (optionally of scaled columns: diag(u) K diag(u))
+//   K2 fa_gram_reduce_kernel fixed-order reduction of the per-workgroup partial results
+//   K3 fa_irls_kernel        the p x p part for any p <= 64: normalisation, IRLS (weighted
+//                            PCA by Jacobi), coefficients c with out = G c
+//                            (p <= 16 has its own kernel, fa_irls16.hip)
 //   K4 fa_combine_kernel     out = G c, second streaming pass over G
+//   K5 fa_proj_kernel        projections G^T (G A) by streaming (re-streaming schedule)
+//   K6 fa_restream_weights_kernel  IRLS weights from the streamed projections
 //
 // Paper: Sec. 2.1 (explained variance needs |g_i|^2 and Y^T g_i), Sec. 2.3 (D_ij^2),
 // Eq. 5 (objective), Alg. 1 (IRLS step and d = (1/p) Y Y^T G 1).
@@ -89,22 +93,22 @@ __device__ __forceinline__ uint4 load16_guarded(const unsigned char* base, int64
 // ------------------------------------------------------------------------------------------
 // K1: Gram matrix by fp64 matrix-core accumulation.
 //
-// One wavefront per workgroup; each wavefront owns a private LDS tile and walks row tiles
-// blockIdx.x, blockIdx.x + gridDim.x, ...  (a fixed assignment, so results are reproducible).
-// Per tile: 16-byte coalesced global loads (next tile's loads are in flight while this
+// Each wavefront owns a private LDS tile and walks the row tiles w, w + W, w + 2W, ... (w its
+// index among the W wavefronts of the launch: a fixed assignment, so results are
+// reproducible).  Per tile: 16-byte coalesced global loads (next tile's loads are in flight while this
 // tile is multiplied) -> LDS laid out [column][row] -> each lane reads the four rows of "its"
 // column -> v_mfma_f64_16x16x4_f64, whose A and B operands are the same register for a
 // diagonal 16x16 block of G^T G: lane (c, k) supplies G[row_k][c].
 // Products of fp32 (or bf16) inputs are exact in fp64 and the accumulation is fp64, which the
 // small differences 1 - v_i of the IRLS weights need.
 //
-// The operands of step t+1 are read from LDS and converted while the matrix core works on
-// step t (a wavefront issues in order; the dependent v_mfma leave room for exactly that).
+// The operands of step t+1 are read from LDS and converted before the matrix instructions
+// of step t are issued, so their LDS latency is hidden behind those.
 // LDS columns p..16T-1 are zeroed once and never written, so no masking is needed.
 //
-// Launch shape: one workgroup of FA_GRAM_WAVES_PER_CU wavefronts per compute unit, each
-// wavefront with its private LDS tile; the workgroup's LDS request is sized so that exactly
-// one fits per CU.  The tile assignment is static (reproducible sums), so an uneven placement
+// Launch shape: one workgroup of WAVES wavefronts (a multiple of the four SIMDs) per compute
+// unit, each wavefront with its private LDS tile; the workgroup's LDS request is sized so
+// that exactly one fits per CU.  The tile assignment is static (reproducible sums), so an uneven placement
 // of workgroups would last for the whole kernel; this shape leaves the dispatcher no choice.
 //
 // T   = number of 16-column blocks (p <= 16 T)
