@@ -20,6 +20,7 @@ SOURCES = {
     # purification loop of the p x p kernel (236 -> 222 us at p = 15).  Not for the streaming
     # kernels, whose larger tilings need the accumulator registers as extra space.
     "fa_irls16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "fa_irls64.hip": [],
     "fa_api.hip": [],
 }
 OBJ_DIR = os.path.join(HERE, "_build")

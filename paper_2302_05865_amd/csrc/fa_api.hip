@@ -19,7 +19,7 @@ struct fa_ctx {
   double* partials;   // gram_max_blocks * NTP(p_max) * 256
   double* Kd;         // FA_P_MAX^2
   double* cd;         // FA_P_MAX
-  double* gws;        // 2 * FA_P_MAX * (FA_P_MAX + 1)
+  double* gws;        // FA_GWS_DOUBLES: the p x p solvers' global workspace
   fa_info* info_d;
   int has_solution;   // info_d holds an A from a completed fa_aggregate / fa_irls
   int last_p, last_m;
@@ -92,8 +92,7 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   ok = ok && hipMalloc((void**)&c->partials, part_bytes) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->Kd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->cd, sizeof(double) * (FA_P_MAX + 8)) == hipSuccess;
-  ok = ok && hipMalloc((void**)&c->gws, sizeof(double) * (2 * FA_P_MAX * (FA_P_MAX + 1) + 258)) ==
-                 hipSuccess;
+  ok = ok && hipMalloc((void**)&c->gws, sizeof(double) * FA_GWS_DOUBLES) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->info_d, sizeof(fa_info)) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->rs_d, sizeof(fa_resume)) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->Pd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;
@@ -267,7 +266,8 @@ extern "C" fa_status fa_get_info(fa_ctx* c, fa_info* host_out) {
     return FA_ERR_DEVICE;
   if (host_out->status == FA_OK && host_out->eigengap != host_out->eigengap) {
     // the purification path needs no eigenvalues; get the diagnostic gap now, off the hot path
-    if (fa_launch_gap(c->gws + 2 * FA_P_MAX * (FA_P_MAX + 1), c->info_d, c->stream) != hipSuccess)
+    const int N = 16 * ((host_out->p + 15) / 16);
+    if (fa_launch_gap(c->gws + FA_GWS_MLAST_OFF, N, c->info_d, c->stream) != hipSuccess)
       return FA_ERR_DEVICE;
     if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
     if (hipMemcpy(&host_out->eigengap,

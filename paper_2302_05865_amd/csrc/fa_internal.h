@@ -12,6 +12,13 @@
 #include "fa_resume.h"
 
 #define FA_IRLS_THREADS 256   // workgroup size of the p x p solver
+#define FA_ST_RETRY (-1)      // device-side status: the matrix-core solver gave up, run Jacobi
+
+// layout of the p x p solvers' global workspace (doubles)
+#define FA_GWS_GENERIC (2 * FA_P_MAX * (FA_P_MAX + 1))    // any-p Jacobi kernel: D2inv, Vt
+#define FA_GWS_TILES (3 * FA_P_MAX * FA_P_MAX)            // 16 < p <= 64 matrix-core kernel
+#define FA_GWS_MLAST_OFF (FA_GWS_GENERIC + FA_GWS_TILES)  // last weighted-PCA matrix N x N, rank, m
+#define FA_GWS_DOUBLES (FA_GWS_MLAST_OFF + FA_P_MAX * FA_P_MAX + 2)
 
 // Optional per-kernel timing: when a launcher gets a non-null fa_ktime, the kernel is
 // launched with these events attached to the dispatch itself (they carry the kernel's own
@@ -31,8 +38,8 @@ hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, doub
                                  hipStream_t st, const fa_ktime* tm);
 
 // K3: p x p solver.  Kd p*p doubles; cd p doubles out; info_d device fa_info; gws global
-// workspace of 2*FA_P_MAX*(FA_P_MAX+1) + 258 doubles.  solver: 0 = default (p <= 16:
-// purification with Jacobi fallback), 1 = p <= 16 Jacobi path, 2 = any-p Jacobi kernel.
+// workspace of FA_GWS_DOUBLES doubles.  solver: 0 = default (matrix-core purification, with
+// the Jacobi solvers as fallback), 1 = p <= 16 Jacobi path, 2 = any-p Jacobi kernel.
 // rs (device, may be null): continue the IRLS from the weights left there by an earlier
 // launch and leave the next ones (see fa_resume.h).
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
@@ -47,8 +54,16 @@ hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int i
                             double delta, double rank_tol, double pair_tol, double* cd,
                             fa_info* info_d, double* mlast, int use_purification,
                             fa_resume* rs, hipStream_t st, const fa_ktime* tm);
-// eigengap (mu_m - mu_{m+1}) / mu_1 of the matrix left in mlast, into info_d->eigengap.
-hipError_t fa_launch_gap(const double* mlast, fa_info* info_d, hipStream_t st);
+// K3 for 16 < p <= 64 (sixteen wavefronts, tiled matrix-core products).  tiles_ws:
+// FA_GWS_TILES doubles; mlast as above with N = 16 ceil(p/16).  May leave
+// info_d->status = FA_ST_RETRY, in which case the any-p kernel must run next.
+hipError_t fa_launch_irls64(const double* Kd, int p, int m, double lambda, int iters, double tol,
+                            double delta, double rank_tol, double pair_tol, double* cd,
+                            fa_info* info_d, double* tiles_ws, double* mlast, fa_resume* rs,
+                            hipStream_t st, const fa_ktime* tm);
+// eigengap (mu_m - mu_{m+1}) / mu_1 of the N x N matrix left in mlast (then rank, m), into
+// info_d->eigengap.
+hipError_t fa_launch_gap(const double* mlast, int N, fa_info* info_d, hipStream_t st);
 
 // K5: partial results of P = G^T (G A) (p x m), A row-major p x m in device memory; one
 // partial of ceil(p/16) * ceil(m/16) * 256 doubles per workgroup; then their fixed-order sum

@@ -612,7 +612,9 @@ __global__ __launch_bounds__(FA_IRLS_THREADS) void fa_irls_kernel(const double* 
                                                                   fa_irls_args ar, double* cg,
                                                                   fa_info* info, double* gws,
                                                                   int big_in_global,
-                                                                  fa_resume* rs) {
+                                                                  fa_resume* rs, int retry_only) {
+  // as the stand-by of the matrix-core solver: nothing to do unless that one gave up
+  if (retry_only && info->status != FA_ST_RETRY) return;
   extern __shared__ __attribute__((aligned(16))) double dyn[];
   const int p = ar.p;
   const int ld = p | 1;
@@ -805,35 +807,54 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
                           hipStream_t st, const fa_ktime* tm) {
   if (p <= 16 && solver != 2)
     return fa_launch_irls16(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d,
-                            gws + 2 * FA_P_MAX * (FA_P_MAX + 1), solver == 0 ? 1 : 0, rs, st, tm);
+                            gws + FA_GWS_MLAST_OFF, solver == 0 ? 1 : 0, rs, st, tm);
+  int retry_only = 0;
+  if (p > 16 && solver == 0) {
+    hipError_t e = fa_launch_irls64(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd,
+                                    info_d, gws + FA_GWS_GENERIC, gws + FA_GWS_MLAST_OFF, rs, st,
+                                    tm);
+    if (e != hipSuccess) return e;
+    retry_only = 1;   // the Jacobi kernel below runs only if the one above gave up
+    tm = nullptr;
+  }
   fa_irls_args ar;
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
   ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
   int big = 0;
   const size_t lds = fa_irls_lds_bytes(p, &big);
   FA_LAUNCH(tm, fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d, gws,
-            big, rs);
+            big, rs, retry_only);
   return hipGetLastError();
 }
 
-// Eigenvalues of the last weighted-PCA matrix (16 x 16, left by the purification path) by the
-// Jacobi routine above; writes the relative gap between eigenvalues m and m+1.
-__global__ __launch_bounds__(64) void fa_gap_kernel(const double* __restrict__ mlast,
-                                                    fa_info* __restrict__ info) {
-  __shared__ double A[16 * 17];
-  __shared__ double vals[16], rc[8], rs[8], red[64];
-  __shared__ int rp[8], rq[8], pos[16], order[16], flag[8];
+// Eigenvalues of the last weighted-PCA matrix (N x N row-major, then rank and m, left by the
+// purification paths) by the Jacobi routine above; writes the relative gap between
+// eigenvalues m and m+1.
+__global__ __launch_bounds__(256) void fa_gap_kernel(const double* __restrict__ mlast, int N,
+                                                     fa_info* __restrict__ info) {
+  extern __shared__ __attribute__((aligned(16))) double gl[];
+  const int ld = N + 1;
+  double* A = gl;                       // N x ld
+  double* vals = A + N * ld;            // 64
+  double* rc = vals + 64;               // 32
+  double* rsn = rc + 32;                // 32
+  double* red = rsn + 32;               // 256
+  int* rp = reinterpret_cast<int*>(red + 256);
+  int* rq = rp + 32;
+  int* pos = rq + 32;
+  int* order = pos + 64;
+  int* flag = order + 64;
   fa_irls_mem sm;
-  sm.ld = 17;
-  sm.rot_c = rc; sm.rot_s = rs; sm.rot_p = rp; sm.rot_q = rq; sm.red = red; sm.flag = flag;
+  sm.ld = ld;
+  sm.rot_c = rc; sm.rot_s = rsn; sm.rot_p = rp; sm.rot_q = rq; sm.red = red; sm.flag = flag;
   sm.pos = pos; sm.order = order;
-  const int r = (int)mlast[256], m = (int)mlast[257];
-  for (int idx = threadIdx.x; idx < 256; idx += 64) A[(idx >> 4) * 17 + (idx & 15)] = mlast[idx];
+  const int r = (int)mlast[N * N], m = (int)mlast[N * N + 1];
+  for (int idx = threadIdx.x; idx < N * N; idx += 256) A[(idx / N) * ld + (idx % N)] = mlast[idx];
   if (threadIdx.x == 0) flag[4] = 0;
   __syncthreads();
-  if (r < 1 || r > 16) return;
+  if (r < 1 || r > N) return;
   fa_jacobi(A, r, (double*)0, 0, (double*)0, 0, sm, 60);
-  FA_FOR(a, r) vals[a] = A[a * 17 + a];
+  FA_FOR(a, r) vals[a] = A[a * ld + a];
   FA_SYNC();
   fa_rank_desc(vals, r, pos, order);
   if (threadIdx.x == 0) {
@@ -843,8 +864,10 @@ __global__ __launch_bounds__(64) void fa_gap_kernel(const double* __restrict__ m
   }
 }
 
-hipError_t fa_launch_gap(const double* mlast, fa_info* info_d, hipStream_t st) {
-  hipLaunchKernelGGL(fa_gap_kernel, dim3(1), dim3(64), 0, st, mlast, info_d);
+hipError_t fa_launch_gap(const double* mlast, int N, fa_info* info_d, hipStream_t st) {
+  const size_t lds = ((size_t)N * (N + 1) + 64 + 32 + 32 + 256) * sizeof(double) +
+                     (32 + 32 + 64 + 64 + 8) * sizeof(int);
+  hipLaunchKernelGGL(fa_gap_kernel, dim3(1), dim3(256), lds, st, mlast, N, info_d);
   return hipGetLastError();
 }
 
