@@ -369,3 +369,67 @@ def test_restream_with_duplicate_and_zero_columns(agg_f32):
     out = agg_f32.fa_aggregate_restream(to_device(Gw), 3, 1.0, 6).cpu().numpy()
     assert agg_f32.fa_get_info().rank == 5
     assert rel_l2(out, ref["out"]) <= GATE
+
+
+# ------------------------------------------------- the 16 < p <= 64 matrix-core p x p solver
+@pytest.mark.parametrize("p,m", [(17, 9), (24, 5), (33, 17), (40, 20), (48, 47), (64, 32)])
+@pytest.mark.parametrize("lam", [0.0, 1.0])
+def test_wide_problems_all_tile_counts(agg_f32, p, m, lam):
+    """Orders 32, 48 and 64 of the tiled solver (2 x 2, 3 x 3, 4 x 4 tiles), ragged p."""
+    announce("wide", p, m, lam)
+    rng = np.random.default_rng(p)
+    n = 20_011
+    mu = rng.standard_normal(n)
+    Gw = (mu[None, :] + 0.7 * rng.standard_normal((p, n))).astype(np.float32)
+    Gw[1] = -3.0 * mu                      # a Byzantine column
+    Gw[p - 1] = Gw[2]                      # a duplicate: rank p - 1
+    ref = fa_scaled(Gw, m, lam, 8, 0.0)
+    out = agg_f32.fa_aggregate(to_device(Gw), m, lam, 8, 0.0).cpu().numpy().astype(np.float64)
+    info = agg_f32.fa_get_info()
+    assert info.status == 0 and info.rank == p - 1 and info.iters_done == 8
+    assert rel_l2(out, ref["out"]) <= 1e-6
+    assert projector_difference(info.A, ref["A"], ref["R"]) <= 1e-6
+    # (with m = rank every residual is exactly zero here; the oracle's SVD leaves square
+    # roots of rounding noise, ~1e-6 in total)
+    assert np.allclose(info.objective, ref["objective"], atol=5e-6)
+    assert np.allclose(info.v, ref["v"], atol=1e-6)
+
+
+def test_wide_problem_with_tied_eigenvalues_uses_the_standby_solver(agg_f32):
+    """p = 20 orthogonal gradients of equal norm: the purification cannot converge, the
+    Jacobi kernel takes over; what is unique is checked."""
+    announce("wide, tied eigenvalues")
+    p, m = 20, 7
+    Gw = np.zeros((p, p * 500), dtype=np.float32)
+    for i in range(p):
+        Gw[i, i * 500:(i + 1) * 500] = 1.0
+    out = agg_f32.fa_aggregate(to_device(Gw), m, 1.0, 4, 0.0).cpu().numpy().astype(np.float64)
+    info = agg_f32.fa_get_info()
+    G = as_f64_matrix(Gw)
+    K = G.T @ G
+    assert info.status == 0 and info.rank == p
+    assert np.abs(info.A.T @ K @ info.A - np.eye(m)).max() <= 1e-10
+    assert abs(info.v.sum() - m) <= 1e-9
+    assert rel_l2(out, G @ info.c) <= 1e-6
+
+
+def test_wide_problem_on_the_jacobi_kernel(monkeypatch):
+    announce("wide, Jacobi kernel")
+    monkeypatch.setenv("FA_IRLS_SOLVER", "2")
+    agg = FlagAggregator(n_max=1 << 20, p_max=64, dtype="f32")
+    monkeypatch.delenv("FA_IRLS_SOLVER")
+    _check_aggregate(agg, si.WORKLOADS["cfg5"].with_n(30_001).with_lam(1.0), 3)
+    agg.close()
+
+
+def test_wide_problem_nonfinite_and_tol(agg_f32):
+    announce("wide: nan, tol")
+    Gw = si.random_dense(33, 5_000, seed=21)
+    ref = fa_scaled(Gw, 12, 1.0, 40, 1e-5)
+    out = agg_f32.fa_aggregate(to_device(Gw), 12, 1.0, 40, 1e-5).cpu().numpy()
+    info = agg_f32.fa_get_info()
+    assert info.iters_done == ref["iters_done"] < 40 and rel_l2(out, ref["out"]) <= GATE
+    assert np.isfinite(info.eigengap) and info.eigengap > 0
+    Gw[5, 17] = np.inf
+    out = agg_f32.fa_aggregate(to_device(Gw), 12, 1.0, 3, 0.0).cpu().numpy()
+    assert agg_f32.fa_get_info().status == 4 and np.all(np.isnan(out))
