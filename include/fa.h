@@ -57,6 +57,10 @@ typedef struct {
                          treated as zero; default 1e-12 */
   double pair_tol;    /* a pair with D_ij^2 <= pair_tol*(|g_i|^2+|g_j|^2) counts as
                          D_ij = 0 and its term is dropped; default 1e-12 */
+  double exponent_a;  /* the constant a >= 1 of the Taylor step in Sec. 2.2 ("Step 2"): every
+                         term of the objective is (1 - v)^(1/a).  Default 2 = the Flag
+                         Aggregator's square roots (Eq. 5).  Other values run on the any-p
+                         Jacobi kernel (slower p x p part, same passes over G). */
 } fa_config;
 
 /* What the last fa_aggregate / fa_irls call on the context found (all fp64). */
@@ -78,12 +82,13 @@ typedef struct {
 } fa_info;
 
 /* Fill *cfg with the defaults (n_max = 0, p_max = FA_P_MAX, FA_F32, NULL stream,
- * delta 1e-6, rank_tol 1e-12, pair_tol 1e-12). */
+ * delta 1e-6, rank_tol 1e-12, pair_tol 1e-12, exponent_a 2). */
 void fa_default_config(fa_config* cfg);
 
 /* Allocate a context on the current HIP device: the per-block Gram partials
  * (sized from n_max, p_max) and the small p x p workspace.  Returns FA_ERR_ARG for
- * n_max < 1, p_max outside 1..FA_P_MAX or an unknown dtype. */
+ * n_max < 1, p_max outside 1..FA_P_MAX, an unknown dtype, or tolerances / exponent out of
+ * range. */
 fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx);
 
 /* Free everything the context owns (synchronises its stream first).  NULL is ignored. */

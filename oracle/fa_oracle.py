@@ -75,10 +75,14 @@ def as_f64_matrix(Gw: np.ndarray) -> np.ndarray:
 
 def fa_literal(G: np.ndarray, m: int, lam: float, iters: int, tol: float,
                delta: float = DELTA_DEFAULT,
-               tau_pair: float = TAU_PAIR_DEFAULT) -> Dict[str, object]:
+               tau_pair: float = TAU_PAIR_DEFAULT, a: float = 2.0) -> Dict[str, object]:
     """FA by IRLS, taken literally on the n x p matrix ``G`` (use for small n).
 
     Follows Eq. 5 / Sec. 2.3 option (2) for the objective, Alg. 1 for the output.
+    ``a`` is the constant of the Taylor step in Sec. 2.2 ("Step 2"): every term of the
+    objective is ``(1 - v)^(1/a)``; FA proper is ``a = 2`` (the square roots of Eq. 5).
+    The IRLS weight of a term is the slope of ``rho^(1/a)`` at the current residual,
+    ``max(rho, delta)^(1/a - 1)`` up to the common factor ``1/a``.
     Returns a dict with ``out`` (n), ``Y`` (n x m), ``v`` (p), ``w`` (p),
     ``u``/``w_pair`` (p x p, zero diagonal), ``objective`` (list), ``iters_done``.
     """
@@ -88,7 +92,7 @@ def fa_literal(G: np.ndarray, m: int, lam: float, iters: int, tol: float,
         raise ValueError("need 1 <= m <= p")
     if n < m:
         raise ValueError("need n >= m")
-    if iters < 1 or lam < 0 or tol < 0:
+    if iters < 1 or lam < 0 or tol < 0 or not (a >= 1.0):
         raise ValueError("bad solver arguments")
 
     # Explained-variance denominators ||g_i||^2 (Sec. 2.1) and normalised gradients
@@ -133,12 +137,12 @@ def fa_literal(G: np.ndarray, m: int, lam: float, iters: int, tol: float,
         u = np.sum((Y.T @ Dn) ** 2, axis=0)
         rho = np.maximum(1.0 - v, 0.0)
         rho_p = np.maximum(1.0 - u, 0.0)
-        obj = float(np.sum(np.sqrt(rho)[live]) + coef * np.sum(np.sqrt(rho_p)[live_pair]))
+        obj = float(np.sum((rho ** (1.0 / a))[live]) + coef * np.sum((rho_p ** (1.0 / a))[live_pair]))
         objective.append(obj)
         if k > 0 and abs(objective[-2] - obj) < tol:
             break
-        w = np.where(live, np.maximum(rho, delta) ** -0.5, 0.0)
-        wp = np.where(live_pair, np.maximum(rho_p, delta) ** -0.5, 0.0)
+        w = np.where(live, np.maximum(rho, delta) ** (1.0 / a - 1.0), 0.0)
+        wp = np.where(live_pair, np.maximum(rho_p, delta) ** (1.0 / a - 1.0), 0.0)
 
     # d = (1/p) Y Y^T G 1 with the raw G (Alg. 1)
     out = Y @ (Y.T @ G.sum(axis=1)) / p
@@ -188,7 +192,7 @@ def tsqr_r(Gw: np.ndarray, chunk_rows: int = 1 << 20) -> np.ndarray:
 
 def fa_scaled(Gw: np.ndarray, m: int, lam: float, iters: int, tol: float,
               delta: float = DELTA_DEFAULT, tau_pair: float = TAU_PAIR_DEFAULT,
-              chunk_rows: int = 1 << 20) -> Dict[str, object]:
+              chunk_rows: int = 1 << 20, a: float = 2.0) -> Dict[str, object]:
     """FA for large n: the literal IRLS run on the ``R`` factor of ``G = Q R``.
 
     ``Q`` has orthonormal columns, so norms, pairwise distances and explained
@@ -203,7 +207,7 @@ def fa_scaled(Gw: np.ndarray, m: int, lam: float, iters: int, tol: float,
     """
     p, n = Gw.shape
     R = tsqr_r(Gw, chunk_rows)
-    res = fa_literal(R, m, lam, iters, tol, delta, tau_pair)
+    res = fa_literal(R, m, lam, iters, tol, delta, tau_pair, a)
     U = res["Y"]                                   # p x m, orthonormal
     t = U @ (U.T @ R.sum(axis=1)) / p
     c = np.linalg.lstsq(R, t, rcond=None)[0]

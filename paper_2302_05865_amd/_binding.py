@@ -123,7 +123,8 @@ class FlagAggregator:
     """
 
     def __init__(self, n_max: int, p_max: int = FA_P_MAX, dtype: str = "f32",
-                 clamp_delta: float = 1e-6, rank_tol: float = 1e-12, pair_tol: float = 1e-12):
+                 clamp_delta: float = 1e-6, rank_tol: float = 1e-12, pair_tol: float = 1e-12,
+                 exponent_a: float = 2.0):
         import torch  # device memory and streams only
         self._torch = torch
         self._lib = load_library()
@@ -136,6 +137,7 @@ class FlagAggregator:
         cfg.clamp_delta = clamp_delta
         cfg.rank_tol = rank_tol
         cfg.pair_tol = pair_tol
+        cfg.exponent_a = exponent_a
         self.dtype = dtype
         self._ctx = ctypes.c_void_p()
         _check(self._lib.fa_create(ctypes.byref(cfg), ctypes.byref(self._ctx)), "fa_create")

@@ -11,7 +11,8 @@ FA_F32, FA_BF16 = 0, 1
 class FaConfig(ctypes.Structure):
     _fields_ = [("n_max", ctypes.c_int64), ("p_max", ctypes.c_int), ("dtype", ctypes.c_int),
                 ("stream", ctypes.c_void_p), ("clamp_delta", ctypes.c_double),
-                ("rank_tol", ctypes.c_double), ("pair_tol", ctypes.c_double)]
+                ("rank_tol", ctypes.c_double), ("pair_tol", ctypes.c_double),
+                ("exponent_a", ctypes.c_double)]
 
 
 class FaInfo(ctypes.Structure):

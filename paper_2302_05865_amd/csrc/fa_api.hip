@@ -47,6 +47,7 @@ extern "C" void fa_default_config(fa_config* cfg) {
   cfg->clamp_delta = 1e-6;
   cfg->rank_tol = 1e-12;
   cfg->pair_tol = 1e-12;
+  cfg->exponent_a = 2.0;
 }
 
 extern "C" const char* fa_status_string(fa_status s) {
@@ -68,7 +69,8 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   *out_ctx = nullptr;
   if (cfg->n_max < 1 || cfg->p_max < 1 || cfg->p_max > FA_P_MAX) return FA_ERR_ARG;
   if (cfg->dtype != FA_F32 && cfg->dtype != FA_BF16) return FA_ERR_ARG;
-  if (!(cfg->clamp_delta > 0.0) || !(cfg->rank_tol >= 0.0) || !(cfg->pair_tol >= 0.0))
+  if (!(cfg->clamp_delta > 0.0) || !(cfg->rank_tol >= 0.0) || !(cfg->pair_tol >= 0.0) ||
+      !(cfg->exponent_a >= 1.0) || !(cfg->exponent_a <= 1e6))
     return FA_ERR_ARG;
   fa_ctx* c = new (std::nothrow) fa_ctx;
   if (!c) return FA_ERR_ALLOC;
@@ -171,7 +173,7 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
     return FA_ERR_DEVICE;
   // S3-S5: p x p IRLS and coefficients
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, nullptr, st,
+                     c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->solver, nullptr, st,
                      prof ? &c->tm[2] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   // S6: out = G c
@@ -212,7 +214,7 @@ extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg
       return FA_ERR_DEVICE;
     // one weighted PCA with the current weights
     if (fa_launch_irls(c->Kd, p, m, lambda, 1, 0.0, c->cfg.clamp_delta, c->cfg.rank_tol,
-                       c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, c->rs_d, st,
+                       c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->solver, c->rs_d, st,
                        nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
     // pass 2 over G: projections on the new basis, then the next weights from them
@@ -223,7 +225,7 @@ extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg
     if (fa_launch_proj_reduce(c->partials, nparts, p, m, c->Pd, st, nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
     if (fa_launch_restream_weights(c->info_d, c->Pd, p, m, lambda, c->cfg.clamp_delta,
-                                   c->cfg.pair_tol, c->rs_d, st) != hipSuccess)
+                                   c->cfg.pair_tol, c->cfg.exponent_a, c->rs_d, st) != hipSuccess)
       return FA_ERR_DEVICE;
   }
   if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks, st,
@@ -312,7 +314,7 @@ extern "C" fa_status fa_irls(fa_ctx* c, const double* K_host, int p, int m, doub
   if (hipMemcpy(c->Kd, K_host, sizeof(double) * p * p, hipMemcpyHostToDevice) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, nullptr, c->stream,
+                     c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->solver, nullptr, c->stream,
                      nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   c->has_solution = 1;
@@ -366,7 +368,7 @@ extern "C" fa_status fa_enqueue_kernel(fa_ctx* c, int which, const void* G, int6
   } else if (which == 2) {
     if (!check_solver_args(p, m, lambda, iters, tol)) return FA_ERR_ARG;
     e = fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                       c->cfg.pair_tol, c->cd, c->info_d, c->gws, c->solver, nullptr, c->stream,
+                       c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->solver, nullptr, c->stream,
                        nullptr);
     c->has_solution = 1; c->last_p = p; c->last_m = m;
   } else {

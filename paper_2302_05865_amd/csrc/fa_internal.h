@@ -40,10 +40,12 @@ hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, doub
 // K3: p x p solver.  Kd p*p doubles; cd p doubles out; info_d device fa_info; gws global
 // workspace of FA_GWS_DOUBLES doubles.  solver: 0 = default (matrix-core purification, with
 // the Jacobi solvers as fallback), 1 = p <= 16 Jacobi path, 2 = any-p Jacobi kernel.
+// exponent_a other than 2 always runs on the any-p kernel.
 // rs (device, may be null): continue the IRLS from the weights left there by an earlier
 // launch and leave the next ones (see fa_resume.h).
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                          double delta, double rank_tol, double pair_tol, double* cd,
+                          double delta, double rank_tol, double pair_tol, double exponent_a,
+                          double* cd,
                           fa_info* info_d, double* gws, int solver, fa_resume* rs,
                           hipStream_t st, const fa_ktime* tm);
 hipError_t fa_irls_prepare(void);
@@ -75,8 +77,8 @@ hipError_t fa_launch_proj_reduce(const double* partials, int nparts, int p, int 
                                  hipStream_t st, const fa_ktime* tm);
 // K6: IRLS weights, objective and next column scales from the streamed projections.
 hipError_t fa_launch_restream_weights(const fa_info* info_d, const double* Pd, int p, int m,
-                                      double lambda, double delta, double pair_tol, fa_resume* rs,
-                                      hipStream_t st);
+                                      double lambda, double delta, double pair_tol,
+                                      double exponent_a, fa_resume* rs, hipStream_t st);
 
 // K4: out = sum_i c[i*cstride] g_i.
 hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,

@@ -408,6 +408,15 @@ __global__ __launch_bounds__(64 * WAVES) void fa_proj_kernel(
   }
 }
 
+// The p x p solver text (any p): parallel-for phases over one workgroup.  Included here
+// because the kernel below shares its term / weight functions.
+#define FA_FN __device__
+#define FA_TID ((int)threadIdx.x)
+#define FA_NT ((int)blockDim.x)
+#define FA_FOR(i, n) for (int i = FA_TID; i < (n); i += FA_NT)
+#define FA_SYNC() __syncthreads()
+#include "fa_irls_core.inc"
+
 // K6: IRLS weights from the streamed projections (the re-streaming schedule's counterpart of
 // the residual step inside the p x p kernel): explained variances v_i = |P_i|^2 / |g_i|^2,
 // residuals 1 - v_i and 1 - |P_i - P_j|^2 / D_ij^2 (Eq. 5), the objective, the weights
@@ -417,6 +426,7 @@ __global__ __launch_bounds__(256) void fa_restream_weights_kernel(const fa_info*
                                                                   const double* __restrict__ P,
                                                                   int p, int m, double coef,
                                                                   double delta, double pair_tol,
+                                                                  double expo,
                                                                   fa_resume* __restrict__ rs) {
   __shared__ double red[256];
   const int tid = threadIdx.x;
@@ -428,13 +438,13 @@ __global__ __launch_bounds__(256) void fa_restream_weights_kernel(const fa_info*
     for (int a = 0; a < m; ++a) pr = fma(P[i * m + a], P[i * m + a], pr);
     const double v = si > 0.0 ? pr / si : 0.0;
     const double rho = v < 1.0 ? 1.0 - v : 0.0;
-    const double w = si > 0.0 ? 1.0 / sqrt(rho > delta ? rho : delta) : 0.0;
+    const double w = si > 0.0 ? fa_weight(rho, delta, expo) : 0.0;
     const double u = si > 0.0 ? sqrt(w / si) : 0.0;
     rs->w[i] = w;
     rs->v_streamed[i] = v;
     rs->u[i] = u;
     rs->uinv[i] = u > 0.0 ? 1.0 / u : 1.0;
-    if (si > 0.0) part += sqrt(rho);
+    if (si > 0.0) part += fa_term(rho, expo);
   }
   for (int idx = tid; idx < p * p; idx += 256) {
     const int i = idx / p, j = idx - i * p;
@@ -450,8 +460,8 @@ __global__ __launch_bounds__(256) void fa_restream_weights_kernel(const fa_info*
         }
         const double q = pr / d2;
         const double rho = q < 1.0 ? 1.0 - q : 0.0;
-        part += coef * sqrt(rho);                       // ordered pair (i, j)
-        cpv = -2.0 * coef / (d2 * sqrt(rho > delta ? rho : delta));
+        part += coef * fa_term(rho, expo);              // ordered pair (i, j)
+        cpv = -2.0 * coef * fa_weight(rho, delta, expo) / d2;
       }
     }
     rs->cp[idx] = cpv;
@@ -601,12 +611,6 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
 
 // ------------------------------------------------------------------------------------------
 // K3: the p x p solver, one workgroup, matrices in LDS.
-#define FA_FN __device__
-#define FA_TID ((int)threadIdx.x)
-#define FA_NT ((int)blockDim.x)
-#define FA_FOR(i, n) for (int i = FA_TID; i < (n); i += FA_NT)
-#define FA_SYNC() __syncthreads()
-#include "fa_irls_core.inc"
 
 __global__ __launch_bounds__(FA_IRLS_THREADS) void fa_irls_kernel(const double* __restrict__ Kg,
                                                                   fa_irls_args ar, double* cg,
@@ -793,18 +797,20 @@ hipError_t fa_launch_proj_partials(const void* G, int64_t ldg, int p, int m, int
 }
 
 hipError_t fa_launch_restream_weights(const fa_info* info_d, const double* Pd, int p, int m,
-                                      double lambda, double delta, double pair_tol, fa_resume* rs,
-                                      hipStream_t st) {
+                                      double lambda, double delta, double pair_tol,
+                                      double exponent_a, fa_resume* rs, hipStream_t st) {
   const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
   hipLaunchKernelGGL(fa_restream_weights_kernel, dim3(1), dim3(256), 0, st, info_d, Pd, p, m, coef,
-                     delta, pair_tol, rs);
+                     delta, pair_tol, 1.0 / exponent_a, rs);
   return hipGetLastError();
 }
 
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                          double delta, double rank_tol, double pair_tol, double* cd,
+                          double delta, double rank_tol, double pair_tol, double exponent_a,
+                          double* cd,
                           fa_info* info_d, double* gws, int solver, fa_resume* rs,
                           hipStream_t st, const fa_ktime* tm) {
+  if (exponent_a != 2.0) solver = 2;   // only the any-p kernel knows other exponents
   if (p <= 16 && solver != 2)
     return fa_launch_irls16(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d,
                             gws + FA_GWS_MLAST_OFF, solver == 0 ? 1 : 0, rs, st, tm);
@@ -820,6 +826,7 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
   fa_irls_args ar;
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
   ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
+  ar.expo = 1.0 / exponent_a;
   int big = 0;
   const size_t lds = fa_irls_lds_bytes(p, &big);
   FA_LAUNCH(tm, fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d, gws,

@@ -20,7 +20,7 @@
 // one solve per call through the resume state, as the re-streaming schedule drives it.
 static int emulate(const double* K, int p, int m, double lambda, int iters, double tol,
                    double delta, double rank_tol, double pair_tol, double* c, fa_info* info,
-                   int stepwise) {
+                   int stepwise, double a) {
   if (p < 1 || p > FA_P_MAX || m < 1 || m > p || iters < 1 || iters > FA_ITERS_MAX) return 1;
   const int ld = p | 1;
   const size_t msz = (size_t)p * ld;
@@ -41,7 +41,7 @@ static int emulate(const double* K, int p, int m, double lambda, int iters, doub
   sm.order = qi; qi += FA_P_MAX; sm.flag = qi; qi += 8;
   fa_irls_args ar;
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol; ar.delta = delta;
-  ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
+  ar.rank_tol = rank_tol; ar.pair_tol = pair_tol; ar.expo = 1.0 / a;
   memset(info, 0, sizeof(*info));
   if (!stepwise) {
     fa_irls_solve(K, ar, sm, c, info, (fa_resume*)0);
@@ -63,11 +63,17 @@ static int emulate(const double* K, int p, int m, double lambda, int iters, doub
 extern "C" int fa_irls_emulate(const double* K, int p, int m, double lambda, int iters, double tol,
                                double delta, double rank_tol, double pair_tol, double* c,
                                fa_info* info) {
-  return emulate(K, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, c, info, 0);
+  return emulate(K, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, c, info, 0, 2.0);
 }
 
 extern "C" int fa_irls_emulate_stepwise(const double* K, int p, int m, double lambda, int iters,
                                         double tol, double delta, double rank_tol,
                                         double pair_tol, double* c, fa_info* info) {
-  return emulate(K, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, c, info, 1);
+  return emulate(K, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, c, info, 1, 2.0);
+}
+
+extern "C" int fa_irls_emulate_exponent(const double* K, int p, int m, double lambda, int iters,
+                                        double tol, double delta, double rank_tol,
+                                        double pair_tol, double a, double* c, fa_info* info) {
+  return emulate(K, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, c, info, 0, a);
 }

@@ -433,3 +433,27 @@ def test_wide_problem_nonfinite_and_tol(agg_f32):
     Gw[5, 17] = np.inf
     out = agg_f32.fa_aggregate(to_device(Gw), 12, 1.0, 3, 0.0).cpu().numpy()
     assert agg_f32.fa_get_info().status == 4 and np.all(np.isnan(out))
+
+
+# ------------------------------------------------------------ general exponent (Sec. 2.2)
+@pytest.mark.parametrize("a", [1.0, 1.5, 4.0])
+@pytest.mark.parametrize("name,n", [("cfg2", 100_003), ("cfg5", 20_001)])
+def test_general_exponent(name, n, a):
+    """Terms (1 - v)^(1/a) with the Taylor constant a of Sec. 2.2 other than FA's a = 2."""
+    announce("exponent", a, name)
+    w = si.WORKLOADS[name].with_n(n).with_lam(1.0)
+    Gw, _ = si.make_inputs(w, 2)
+    iters = 10
+    ref = fa_scaled(Gw, w.m, w.lam, iters, 0.0, a=a)
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, exponent_a=a)
+    dev = to_device(Gw)
+    out = agg.fa_aggregate(dev, w.m, w.lam, iters, 0.0).cpu().numpy().astype(np.float64)
+    info = agg.fa_get_info()
+    assert info.status == 0
+    assert rel_l2(out, ref["out"]) <= GATE
+    assert projector_difference(info.A, ref["A"], ref["R"]) <= GATE
+    assert np.allclose(info.objective, ref["objective"], atol=1e-6)
+    if name == "cfg2":
+        out2 = agg.fa_aggregate_restream(dev, w.m, w.lam, iters).cpu().numpy().astype(np.float64)
+        assert rel_l2(out2, ref["out"]) <= GATE
+    agg.close()

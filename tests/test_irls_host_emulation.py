@@ -27,12 +27,20 @@ def emul(tmp_path_factory):
                            os.path.join(ROOT, "tests", "emul", "irls_emul.cpp"), "-o", str(out)])
     lib = ctypes.CDLL(str(out))
 
-    def run(K, m, lam, iters, tol, delta=1e-6, rank_tol=1e-12, pair_tol=1e-12, stepwise=False):
+    def run(K, m, lam, iters, tol, delta=1e-6, rank_tol=1e-12, pair_tol=1e-12, stepwise=False,
+            a=None):
         K = np.ascontiguousarray(K, dtype=np.float64)
         p = K.shape[0]
         info = FaInfo()
         c = np.zeros(p)
         d = ctypes.c_double
+        if a is not None:
+            rc = lib.fa_irls_emulate_exponent(
+                K.ctypes.data_as(ctypes.c_void_p), p, m, d(lam), iters, d(tol), d(delta),
+                d(rank_tol), d(pair_tol), d(a), c.ctypes.data_as(ctypes.c_void_p),
+                ctypes.byref(info))
+            assert rc == 0
+            return c, info
         fn = lib.fa_irls_emulate_stepwise if stepwise else lib.fa_irls_emulate
         rc = fn(K.ctypes.data_as(ctypes.c_void_p), p, m, d(lam), iters, d(tol),
                 d(delta), d(rank_tol), d(pair_tol),
@@ -123,3 +131,15 @@ def test_one_solve_per_call_through_the_resume_state_equals_one_call(emul, name,
     assert np.allclose(np.array(i2.objective[:w.iters]), np.array(i1.objective[:w.iters]),
                        rtol=0, atol=1e-10)
     assert np.linalg.norm(G @ (c1 - c2)) <= 1e-10 * np.linalg.norm(G @ c1)
+
+
+@pytest.mark.parametrize("a", [1.0, 1.5, 3.0])
+def test_general_exponent_in_the_solver_text(emul, a):
+    """Sec. 2.2, Step 2: terms (1 - v)^(1/a) with a other than 2 (the any-p solver only)."""
+    w = si.WORKLOADS["cfg2"].with_n(30000)
+    Gw, _ = si.make_inputs(w, 1)
+    ref = fa_scaled(Gw, w.m, w.lam, 12, 0.0, a=a)
+    G = as_f64_matrix(Gw)
+    c, info = emul(G.T @ G, w.m, w.lam, 12, 0.0, a=a)
+    assert np.linalg.norm(G @ c - ref["out"]) <= 1e-8 * np.linalg.norm(ref["out"])
+    assert np.allclose(np.array(info.objective[:12]), ref["objective"], atol=1e-6)

@@ -26,13 +26,13 @@ def _principal_cosines(Y1, Y2):
 
 # Independent statement of the FA objective (Eq. 5 + Sec. 2.3 option (2)), with explicit
 # loops over workers and over ordered pairs i != j.
-def eq5_objective(Y, G, lam, pair_factor=None):
+def eq5_objective(Y, G, lam, pair_factor=None, a=2.0):
     n, p = G.shape
     total = 0.0
     for i in range(p):
         g = G[:, i]
         z = Y.T @ g
-        total += math.sqrt(max(1.0 - float(z @ z) / float(g @ g), 0.0))
+        total += max(1.0 - float(z @ z) / float(g @ g), 0.0) ** (1.0 / a)
     if lam > 0:
         fac = lam / (p - 1) if pair_factor is None else pair_factor
         for i in range(p):
@@ -41,7 +41,7 @@ def eq5_objective(Y, G, lam, pair_factor=None):
                     continue
                 d = G[:, i] - G[:, j]
                 z = Y.T @ d
-                total += fac * math.sqrt(max(1.0 - float(z @ z) / float(d @ d), 0.0))
+                total += fac * max(1.0 - float(z @ z) / float(d @ d), 0.0) ** (1.0 / a)
     return total
 
 
@@ -206,6 +206,47 @@ def test_converged_point_is_stationary_for_eq5(seed):
         worst_wrong_factor = max(worst_wrong_factor, abs(dw))
     assert worst < 1e-6
     assert worst_wrong_factor > 1e-3      # the check has power
+
+
+@pytest.mark.parametrize("a", [1.5, 3.0, 6.0])
+@pytest.mark.parametrize("seed", [1, 2])
+def test_general_exponent_fixed_point_is_stationary(seed, a):
+    """Sec. 2.2, Step 2: with the Taylor constant a every term is (1 - v)^(1/a).  The IRLS
+    fixed point must be stationary for that objective (written out independently), and not
+    for the a = 2 objective: pins the weight exponent 1/a - 1."""
+    rng = np.random.default_rng(seed)
+    n, p, m, lam = 12, 8, 2, 1.0
+    G = rng.standard_normal((n, p)) * rng.uniform(0.5, 3, p)[None, :]
+    res = fa_literal(G, m, lam, 1500, 0.0, a=a)
+    Y = res["Y"]
+    off = ~np.eye(p, dtype=bool)
+    if min((1 - res["v"]).min(), (1 - res["u"][off]).min()) < 1e-3:
+        pytest.skip("converged to a vertex, where the objective is not differentiable")
+    assert abs(res["objective"][-1] - eq5_objective(Y, G, lam, a=a)) < 1e-7
+    worst = worst_other = 0.0
+    h = 1e-5
+    for _ in range(6):
+        D = rng.standard_normal((n, m))
+        D -= Y @ (Y.T @ D)
+        D /= np.linalg.norm(D)
+        dd = (eq5_objective(_retract(Y, D, h), G, lam, a=a)
+              - eq5_objective(_retract(Y, D, -h), G, lam, a=a)) / (2 * h)
+        worst = max(worst, abs(dd))
+        do = (eq5_objective(_retract(Y, D, h), G, lam, a=2.0 if a != 2.0 else 3.0)
+              - eq5_objective(_retract(Y, D, -h), G, lam, a=2.0 if a != 2.0 else 3.0)) / (2 * h)
+        worst_other = max(worst_other, abs(do))
+    assert worst < 1e-5
+    assert worst_other > 1e-3
+
+
+def test_exponent_one_is_pca_whatever_the_iteration_count():
+    """a = 1 makes every term linear in its residual: the weights never move, and every
+    solve is the first one (weighted PCA with unit weights)."""
+    G = _rand(15, 6, 77)
+    first = fa_literal(G, 3, 1.0, 1, 0.0)
+    many = fa_literal(G, 3, 1.0, 9, 0.0, a=1.0)
+    assert np.allclose(many["Y"] @ many["Y"].T, first["Y"] @ first["Y"].T, atol=1e-10)
+    assert np.allclose(many["w"], 1.0) and np.allclose(many["out"], first["out"], atol=1e-10)
 
 
 @pytest.mark.parametrize("seed", [0, 1, 2])
