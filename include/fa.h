@@ -47,6 +47,12 @@ typedef enum {
 
 typedef enum { FA_F32 = 0, FA_BF16 = 1 } fa_dtype; /* storage type of G */
 
+/* Storage order of G.  FA_WORKER_MAJOR: gradient i contiguous (see above).  FA_ROW_MAJOR
+ * ("interleaved", the n x p matrix of Sec. 2.1 stored row by row): element i of coordinate k
+ * at G + (k*ldg + i) * elem_size with p <= ldg <= 16*ceil(p/16); G 16-byte aligned.  All
+ * entry points accept it except fa_aggregate_restream. */
+typedef enum { FA_WORKER_MAJOR = 0, FA_ROW_MAJOR = 1 } fa_layout;
+
 typedef struct {
   int64_t n_max;      /* largest n this context will see (sizes the workspace) */
   int p_max;          /* largest p, 1..FA_P_MAX */
@@ -61,6 +67,7 @@ typedef struct {
                          term of the objective is (1 - v)^(1/a).  Default 2 = the Flag
                          Aggregator's square roots (Eq. 5).  Other values run on the any-p
                          Jacobi kernel (slower p x p part, same passes over G). */
+  int layout;         /* fa_layout of every G this context sees; default FA_WORKER_MAJOR */
 } fa_config;
 
 /* What the last fa_aggregate / fa_irls call on the context found (all fp64). */

@@ -124,7 +124,7 @@ class FlagAggregator:
 
     def __init__(self, n_max: int, p_max: int = FA_P_MAX, dtype: str = "f32",
                  clamp_delta: float = 1e-6, rank_tol: float = 1e-12, pair_tol: float = 1e-12,
-                 exponent_a: float = 2.0):
+                 exponent_a: float = 2.0, layout: str = "worker_major"):
         import torch  # device memory and streams only
         self._torch = torch
         self._lib = load_library()
@@ -138,6 +138,8 @@ class FlagAggregator:
         cfg.rank_tol = rank_tol
         cfg.pair_tol = pair_tol
         cfg.exponent_a = exponent_a
+        cfg.layout = {"worker_major": 0, "row_major": 1}[layout]
+        self.layout = layout
         self.dtype = dtype
         self._ctx = ctypes.c_void_p()
         _check(self._lib.fa_create(ctypes.byref(cfg), ctypes.byref(self._ctx)), "fa_create")
@@ -158,7 +160,11 @@ class FlagAggregator:
         torch = self._torch
         want = torch.float32 if self.dtype == "f32" else torch.bfloat16
         if not G.is_cuda or G.dim() != 2 or G.dtype != want or G.stride(1) != 1:
-            raise TypeError(f"G must be a device tensor [p, n] of {want} with unit inner stride")
+            raise TypeError(f"G must be a device tensor of {want} with unit inner stride")
+        if self.layout == "row_major":       # [n, p]: coordinate k's p values are contiguous
+            n, p = G.shape
+            ldg = G.stride(0) if n > 1 else p
+            return ctypes.c_void_p(G.data_ptr()), int(ldg), int(p), int(n)
         p, n = G.shape
         ldg = G.stride(0) if p > 1 else n
         return ctypes.c_void_p(G.data_ptr()), int(ldg), int(p), int(n)

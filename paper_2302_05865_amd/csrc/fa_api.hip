@@ -48,6 +48,7 @@ extern "C" void fa_default_config(fa_config* cfg) {
   cfg->rank_tol = 1e-12;
   cfg->pair_tol = 1e-12;
   cfg->exponent_a = 2.0;
+  cfg->layout = FA_WORKER_MAJOR;
 }
 
 extern "C" const char* fa_status_string(fa_status s) {
@@ -69,6 +70,7 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   *out_ctx = nullptr;
   if (cfg->n_max < 1 || cfg->p_max < 1 || cfg->p_max > FA_P_MAX) return FA_ERR_ARG;
   if (cfg->dtype != FA_F32 && cfg->dtype != FA_BF16) return FA_ERR_ARG;
+  if (cfg->layout != FA_WORKER_MAJOR && cfg->layout != FA_ROW_MAJOR) return FA_ERR_ARG;
   if (!(cfg->clamp_delta > 0.0) || !(cfg->rank_tol >= 0.0) || !(cfg->pair_tol >= 0.0) ||
       !(cfg->exponent_a >= 1.0) || !(cfg->exponent_a <= 1e6))
     return FA_ERR_ARG;
@@ -140,9 +142,12 @@ extern "C" fa_status fa_set_stream(fa_ctx* c, void* stream) {
 
 static bool check_matrix_args(const fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n) {
   if (!c || !G) return false;
-  if (p < 1 || p > c->cfg.p_max || n < 1 || n > c->cfg.n_max || ldg < n) return false;
-  const int es = elem_size(c->cfg.dtype);
+  if (p < 1 || p > c->cfg.p_max || n < 1 || n > c->cfg.n_max) return false;
   if (((uintptr_t)G & 15u) != 0) return false;
+  if (c->cfg.layout == FA_ROW_MAJOR)   // ldg = row pitch; a tile row must fit the tile width
+    return ldg >= p && ldg <= 16 * ((p + 15) / 16);
+  if (ldg < n) return false;
+  const int es = elem_size(c->cfg.dtype);
   if ((ldg * es) % 16 != 0 && p > 1) return false;
   return true;
 }
@@ -165,7 +170,7 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   c->ev_recorded = 0;
   // S1: norms and Gram matrix, per-workgroup partials;  S2: their fixed-order sum
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
                               &nparts, nullptr, st, prof ? &c->tm[0] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, prof ? &c->tm[1] : nullptr) !=
@@ -177,7 +182,7 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
                      prof ? &c->tm[2] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   // S6: out = G c
-  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks, st,
+  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cd, 1, out, c->combine_max_blocks, st,
                         prof ? &c->tm[3] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (prof) c->ev_recorded = 1;
@@ -193,6 +198,7 @@ extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg
   if (!check_matrix_args(c, G, ldg, p, n) || !out || ((uintptr_t)out & 15u) != 0)
     return FA_ERR_ARG;
   if (!check_solver_args(p, m, lambda, iters, 0.0)) return FA_ERR_ARG;
+  if (c->cfg.layout != FA_WORKER_MAJOR) return FA_ERR_ARG;   // measurement schedule: one layout
   hipStream_t st = c->stream;
   const bool prof = c->profiling != 0;
   c->ev_recorded = 0;
@@ -206,7 +212,7 @@ extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg
   for (int it = 0; it < iters; ++it) {
     const bool last = it == iters - 1;
     // pass 1 over G: Gram matrix of the columns scaled by sqrt(w_i)/|g_i| (plain at first)
-    if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+    if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
                                 &nparts, it == 0 ? nullptr : u_d, st,
                                 (prof && last) ? &c->tm_r[0] : nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
@@ -228,7 +234,7 @@ extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg
                                    c->cfg.pair_tol, c->cfg.exponent_a, c->rs_d, st) != hipSuccess)
       return FA_ERR_DEVICE;
   }
-  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks, st,
+  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cd, 1, out, c->combine_max_blocks, st,
                         nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (prof) c->ev_recorded_r = 1;
@@ -284,7 +290,7 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
                              double* K_host) {
   if (!check_matrix_args(c, G, ldg, p, n) || !K_host) return FA_ERR_ARG;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
                               &nparts, nullptr, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
@@ -298,7 +304,7 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
 extern "C" fa_status fa_gram_async(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n) {
   if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
                               &nparts, nullptr, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
@@ -330,7 +336,7 @@ extern "C" fa_status fa_combine(fa_ctx* c, const void* G, int64_t ldg, int p, in
   if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
   if (hipMemcpy(c->cd, c_host, sizeof(double) * p, hipMemcpyHostToDevice) != hipSuccess)
     return FA_ERR_DEVICE;
-  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks,
+  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cd, 1, out, c->combine_max_blocks,
                         c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   return FA_OK;
@@ -346,7 +352,7 @@ extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int6
   const double* A = reinterpret_cast<const double*>(reinterpret_cast<const char*>(c->info_d) +
                                                     offsetof(fa_info, A));
   for (int a = 0; a < m; ++a)
-    if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, A + a, m, Y + (int64_t)a * ldy,
+    if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, A + a, m, Y + (int64_t)a * ldy,
                           c->combine_max_blocks, c->stream, nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
   return FA_OK;
@@ -360,7 +366,7 @@ extern "C" fa_status fa_enqueue_kernel(fa_ctx* c, int which, const void* G, int6
   hipError_t e = hipSuccess;
   if (which == 0) {
     if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
-    e = fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->gram_max_blocks, c->partials,
+    e = fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
                                 &c->last_nparts, nullptr, c->stream, nullptr);
   } else if (which == 1) {
     if (c->last_nparts < 1) return FA_ERR_ARG;
@@ -374,7 +380,7 @@ extern "C" fa_status fa_enqueue_kernel(fa_ctx* c, int which, const void* G, int6
   } else {
     if (!check_matrix_args(c, G, ldg, p, n) || !out || ((uintptr_t)out & 15u) != 0)
       return FA_ERR_ARG;
-    e = fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cd, 1, out, c->combine_max_blocks,
+    e = fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cd, 1, out, c->combine_max_blocks,
                           c->stream, nullptr);
   }
   return e == hipSuccess ? FA_OK : FA_ERR_DEVICE;

@@ -28,10 +28,11 @@ typedef struct { hipEvent_t start, stop; } fa_ktime;
 
 // K1: partial Grams of G, one per launched workgroup, into `partials` (up to max_blocks *
 // T(T+1)/2 * 256 doubles, T = ceil(p/16)); max_blocks = workgroups (one per compute unit);
-// *nparts receives how many partials were written.  colscale (device, p doubles, may be
+// *nparts receives how many partials were written.  layout: fa_layout (for FA_ROW_MAJOR ldg is
+// the row pitch in elements, p <= ldg <= 16 ceil(p/16)).  colscale (device, p doubles, may be
 // null): column i is scaled by colscale[i], i.e. the result is diag(u) K diag(u).
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
-                                   int max_blocks, double* partials, int* nparts,
+                                   int layout, int max_blocks, double* partials, int* nparts,
                                    const double* colscale, hipStream_t st, const fa_ktime* tm);
 // K2: their fixed-order sum into Kd (p*p doubles, row-major).
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
@@ -81,7 +82,7 @@ hipError_t fa_launch_restream_weights(const fa_info* info_d, const double* Pd, i
                                       double exponent_a, fa_resume* rs, hipStream_t st);
 
 // K4: out = sum_i c[i*cstride] g_i.
-hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype, int layout,
                              const double* c, int cstride, float* out, int max_blocks,
                              hipStream_t st, const fa_ktime* tm);
 

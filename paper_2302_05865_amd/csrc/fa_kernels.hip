@@ -135,7 +135,12 @@ __device__ __forceinline__ void unpack4(const unsigned char* src, double* x) {
 
 // SCALED: column i is multiplied by colscale[i] on its way into the matrix core, so the
 // result is diag(u) G^T G diag(u) (the weighted Gram matrix of a re-weighted PCA).
-template <int T, int CPL, typename E, int WAVES, bool SCALED>
+// ROWS: G is stored row by row ("interleaved": element i of coordinate k at G + (k*ldg + i)
+// * elem_size, ldg <= 16 T).  A tile of R rows is then one contiguous span of memory; it is
+// read with the same 16-byte coalesced loads, and each lane scatters the four (eight)
+// elements of its pieces to their [column][row] places in LDS.  Where the elements of a piece
+// go is the same for every tile, so it is worked out once.
+template <int T, int CPL, typename E, int WAVES, bool SCALED, bool ROWS>
 __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
                                                      const unsigned char* __restrict__ G,
                                                      int64_t ldg, int p, int64_t n,
@@ -186,8 +191,36 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
     if constexpr (SCALED) us[tt] = (tt * 16 + c16 < p) ? colscale[tt * 16 + c16] : 0.0;
   }
 
+  // interleaved storage: (row in tile, column) of the first element of each of this lane's
+  // pieces; the span of a tile is R * ldg elements (<= NCG * 64 pieces)
+  int prow[NCG], pcol[NCG];
+  bool pon[NCG];
+  const int ldr = (int)ldg;
+#pragma unroll
+  for (int cg = 0; cg < NCG; ++cg) {
+    const int e0 = (cg * 64 + lane) * EPL;
+    pon[cg] = ROWS && e0 < R * ldr;
+    prow[cg] = ROWS ? e0 / ldr : 0;
+    pcol[cg] = ROWS ? e0 - prow[cg] * ldr : 0;
+  }
+
   uint4 regs[NCG];
   auto load_tile = [&](int64_t tl) {
+    if constexpr (ROWS) {
+      const unsigned char* base = G + tl * R * ldr * E::SIZE;
+      const int64_t rows_here = n - tl * R < R ? n - tl * R : R;
+      const int lim = (int)rows_here * ldr;          // elements of this tile that exist
+#pragma unroll
+      for (int cg = 0; cg < NCG; ++cg) {
+        regs[cg] = make_uint4(0u, 0u, 0u, 0u);
+        const int e0 = (cg * 64 + lane) * EPL;
+        if (pon[cg]) {
+          if (e0 + EPL <= lim) regs[cg] = load16_stream(base + (int64_t)e0 * E::SIZE);
+          else if (e0 < lim) regs[cg] = load16_guarded<E>(base, e0, lim);
+        }
+      }
+      return;
+    }
     const int64_t row0 = tl * R + lrow;
     if ((tl + 1) * R <= n) {               // uniform: a full tile needs no row guards
 #pragma unroll
@@ -197,6 +230,32 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
 #pragma unroll
       for (int cg = 0; cg < NCG; ++cg) regs[cg] = load16_guarded<E>(colbase[cg], row0, n);
     }
+  };
+  auto store_tile_lds = [&]() {
+    if constexpr (ROWS) {
+#pragma unroll
+      for (int cg = 0; cg < NCG; ++cg) {
+        if (!pon[cg]) continue;
+        int r = prow[cg], c = pcol[cg];
+        const uint32_t wds[4] = {regs[cg].x, regs[cg].y, regs[cg].z, regs[cg].w};
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+          if (c < p) {
+            if constexpr (E::SIZE == 4)
+              *reinterpret_cast<uint32_t*>(lds + c * CS + r * 4) = wds[j];
+            else
+              *reinterpret_cast<uint16_t*>(lds + c * CS + r * 2) =
+                  (uint16_t)(wds[j >> 1] >> (16 * (j & 1)));
+          }
+          if (++c == ldr) { c = 0; ++r; }
+        }
+      }
+      return;
+    }
+#pragma unroll
+    for (int cg = 0; cg < NCG; ++cg)
+      if (colon[cg])
+        *reinterpret_cast<uint4*>(lds + (cg * CPL + lcol) * CS + lrow * E::SIZE) = regs[cg];
   };
   auto operand = [&](const unsigned char* src, int tt, double* x) {
     unpack4<E>(src, x);
@@ -211,10 +270,7 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
   if (tile < ntiles) load_tile(tile);
   for (; tile < ntiles; tile += nwaves) {
     wave_lds_fence();  // the previous tile's LDS reads precede these writes
-#pragma unroll
-    for (int cg = 0; cg < NCG; ++cg)
-      if (colon[cg])
-        *reinterpret_cast<uint4*>(lds + (cg * CPL + lcol) * CS + lrow * E::SIZE) = regs[cg];
+    store_tile_lds();
     wave_lds_fence();
     const int64_t next = tile + nwaves;
     if (next < ntiles) load_tile(next);
@@ -405,6 +461,76 @@ __global__ __launch_bounds__(64 * WAVES) void fa_proj_kernel(
       dst[tp * 256 + e] = tot;
     }
     __syncthreads();
+  }
+}
+
+// K4 for interleaved storage (G row by row, row pitch ldr elements): a workgroup copies the
+// contiguous span of its 256 rows with coalesced 16-byte loads, scattering the elements to
+// LDS as [column][row]; then thread r adds up row r (fp64) and the workgroup writes 256
+// consecutive outputs.
+template <typename E>
+__global__ __launch_bounds__(256) void fa_combine_rows_kernel(const unsigned char* __restrict__ G,
+                                                              int ldr, int p, int64_t n,
+                                                              const double* __restrict__ c,
+                                                              int cstride, float* __restrict__ out,
+                                                              unsigned magic) {
+  constexpr int EPL = E::EPL;
+  constexpr int RB = 256;                  // rows per workgroup pass
+  constexpr int PITCH = RB + 1;            // LDS words per column
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  float* tile = reinterpret_cast<float*>(lds_raw);          // p * PITCH floats
+  __shared__ double cs[FA_P_MAX];
+  if (threadIdx.x < FA_P_MAX)
+    cs[threadIdx.x] = (int)threadIdx.x < p ? c[(int64_t)threadIdx.x * cstride] : 0.0;
+  const int64_t nblk = (n + RB - 1) / RB;
+  for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+    const int64_t row_base = blk * RB;
+    const int rows_here = (int)(n - row_base < RB ? n - row_base : RB);
+    const int lim = rows_here * ldr;                        // elements of this span
+    const unsigned char* base = G + row_base * ldr * E::SIZE;
+    __syncthreads();                                        // the previous pass has been read
+    constexpr int PCH = 4;                                  // pieces in flight per thread
+    for (int eb = (int)threadIdx.x * EPL; eb < lim; eb += 256 * EPL * PCH) {
+      uint4 v[PCH];
+#pragma unroll
+      for (int q = 0; q < PCH; ++q) {
+        const int e0 = eb + q * 256 * EPL;
+        v[q] = make_uint4(0u, 0u, 0u, 0u);
+        if (e0 + EPL <= lim) v[q] = load16_stream(base + (int64_t)e0 * E::SIZE);
+        else if (e0 < lim) v[q] = load16_guarded<E>(base, e0, lim);
+      }
+#pragma unroll
+      for (int q = 0; q < PCH; ++q) {
+        const int e0 = eb + q * 256 * EPL;
+        if (e0 >= lim) continue;
+        const uint32_t wds[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+        // e0 / ldr (exact for e0 < 2^16; the multiplier of ldr = 1 would not fit 32 bits)
+        int r = ldr == 1 ? e0 : (int)__umulhi((unsigned)e0, magic);
+        int col = e0 - r * ldr;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+          if (col < p && e0 + j < lim) {
+            float f;
+            if constexpr (E::SIZE == 4) f = __uint_as_float(wds[j]);
+            else f = bf16_bits_to_f32((wds[j >> 1] >> (16 * (j & 1))) & 0xffffu);
+            tile[col * PITCH + r] = f;
+          }
+          if (++col == ldr) { col = 0; ++r; }
+        }
+      }
+    }
+    __syncthreads();
+    const int r = (int)threadIdx.x;
+    if (r < rows_here) {
+      double a0 = 0.0, a1 = 0.0;
+      int i = 0;
+      for (; i + 1 < p; i += 2) {
+        a0 = fma(cs[i], (double)tile[i * PITCH + r], a0);
+        a1 = fma(cs[i + 1], (double)tile[(i + 1) * PITCH + r], a1);
+      }
+      if (i < p) a0 = fma(cs[i], (double)tile[i * PITCH + r], a0);
+      out[row_base + r] = (float)(a0 + a1);
+    }
   }
 }
 
@@ -672,7 +798,7 @@ size_t fa_irls_lds_bytes(int p, int* big_in_global) {
 
 // ------------------------------------------------------------------------------------------
 // launchers (host).  Shapes are validated by the callers in fa_api.cpp.
-template <int T, int CPL, typename E, int WAVES, bool SCALED>
+template <int T, int CPL, typename E, int WAVES, bool SCALED, bool ROWS>
 static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
                                 double* partials, int* nparts, const double* colscale,
                                 hipStream_t st, const fa_ktime* tm) {
@@ -686,7 +812,7 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
   static bool prepared = false;
   if (!prepared) {
     hipError_t e = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(fa_gram_kernel<T, CPL, E, WAVES, SCALED>),
+        reinterpret_cast<const void*>(fa_gram_kernel<T, CPL, E, WAVES, SCALED, ROWS>),
         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     prepared = true;
@@ -695,33 +821,39 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
   int64_t wgs = (ntiles + WAVES - 1) / WAVES;
   if (wgs > max_blocks) wgs = max_blocks;
   *nparts = (int)wgs;
-  FA_LAUNCH(tm, (fa_gram_kernel<T, CPL, E, WAVES, SCALED>), dim3((unsigned)wgs),
+  FA_LAUNCH(tm, (fa_gram_kernel<T, CPL, E, WAVES, SCALED, ROWS>), dim3((unsigned)wgs),
             dim3(64 * WAVES), lds_bytes, st, (const unsigned char*)G, ldg, p, n, ntiles, partials,
             colscale);
   return hipGetLastError();
 }
 
-template <typename E, bool SCALED>
+template <typename E, bool SCALED, bool ROWS>
 static hipError_t launch_gram_e(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
                                 double* partials, int* nparts, const double* colscale,
                                 hipStream_t st, const fa_ktime* tm) {
   switch ((p + 15) / 16) {
-    case 1: return launch_gram_t<1, FA_GRAM_CPL1, E, FA_GRAM_W1, SCALED>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
-    case 2: return launch_gram_t<2, 4, E, 8, SCALED>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
-    case 3: return launch_gram_t<3, 4, E, 8, SCALED>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
-    case 4: return launch_gram_t<4, 4, E, 8, SCALED>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+    case 1: return launch_gram_t<1, FA_GRAM_CPL1, E, FA_GRAM_W1, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+    case 2: return launch_gram_t<2, 4, E, 8, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+    case 3: return launch_gram_t<3, 4, E, 8, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+    case 4: return launch_gram_t<4, 4, E, 8, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
   }
   return hipErrorInvalidValue;
 }
 
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
-                                   int max_blocks, double* partials, int* nparts,
+                                   int layout, int max_blocks, double* partials, int* nparts,
                                    const double* colscale, hipStream_t st, const fa_ktime* tm) {
+  if (layout == FA_ROW_MAJOR) {
+    if (colscale) return hipErrorInvalidValue;    // the re-streaming schedule is worker-major only
+    if (dtype == FA_F32)
+      return launch_gram_e<ElemF32, false, true>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
+    return launch_gram_e<ElemBF16, false, true>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
+  }
   if (dtype == FA_F32)
-    return colscale ? launch_gram_e<ElemF32, true>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm)
-                    : launch_gram_e<ElemF32, false>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
-  return colscale ? launch_gram_e<ElemBF16, true>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm)
-                  : launch_gram_e<ElemBF16, false>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
+    return colscale ? launch_gram_e<ElemF32, true, false>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm)
+                    : launch_gram_e<ElemF32, false, false>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
+  return colscale ? launch_gram_e<ElemBF16, true, false>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm)
+                  : launch_gram_e<ElemBF16, false, false>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
 }
 
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
@@ -884,9 +1016,36 @@ hipError_t fa_irls_prepare(void) {
                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 
-hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype, int layout,
                              const double* c, int cstride, float* out, int max_blocks,
                              hipStream_t st, const fa_ktime* tm) {
+  if (layout == FA_ROW_MAJOR) {
+    const int ldr = (int)ldg;
+    const size_t lds = (size_t)p * 257 * sizeof(float);
+    // ceil(2^32 / ldr): floor(e * magic / 2^32) = e / ldr for every e < 2^16
+    const unsigned magic = (unsigned)((0x100000000ull + (unsigned)ldr - 1) / (unsigned)ldr);
+    static bool prepared = false;
+    if (!prepared) {
+      hipError_t e = hipFuncSetAttribute(
+          reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemF32>),
+          hipFuncAttributeMaxDynamicSharedMemorySize, FA_P_MAX * 257 * (int)sizeof(float));
+      if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemBF16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                FA_P_MAX * 257 * (int)sizeof(float));
+      if (e != hipSuccess) return e;
+      prepared = true;
+    }
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    if (dtype == FA_F32)
+      FA_LAUNCH(tm, (fa_combine_rows_kernel<ElemF32>), dim3((unsigned)blocks), dim3(256), lds, st,
+                (const unsigned char*)G, ldr, p, n, c, cstride, out, magic);
+    else
+      FA_LAUNCH(tm, (fa_combine_rows_kernel<ElemBF16>), dim3((unsigned)blocks), dim3(256), lds, st,
+                (const unsigned char*)G, ldr, p, n, c, cstride, out, magic);
+    return hipGetLastError();
+  }
   const int epl = dtype == FA_F32 ? 4 : 8;
   const int64_t ngroups = (n + epl - 1) / epl;
   int64_t blocks = (ngroups + 255) / 256;

@@ -48,10 +48,10 @@ def test_struct_layouts_match_the_header(tmp_path):
 #include <stddef.h>
 #include "fa.h"
 int main(void) {
-  printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %d %d\n", sizeof(fa_config), sizeof(fa_info),
+  printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %d %d\n", sizeof(fa_config), sizeof(fa_info),
          offsetof(fa_info, objective), offsetof(fa_info, s), offsetof(fa_info, c),
          offsetof(fa_info, A), offsetof(fa_info, K), offsetof(fa_config, clamp_delta),
-         offsetof(fa_config, exponent_a), FA_P_MAX, FA_ITERS_MAX);
+         offsetof(fa_config, exponent_a), offsetof(fa_config, layout), FA_P_MAX, FA_ITERS_MAX);
   return 0;
 }''')
     exe = tmp_path / "layout"
@@ -60,7 +60,7 @@ int main(void) {
     I, C = defs.FaInfo, defs.FaConfig
     assert vals == [ctypes.sizeof(C), ctypes.sizeof(I), I.objective.offset, I.s.offset,
                     I.c.offset, I.A.offset, I.K.offset, C.clamp_delta.offset,
-                    C.exponent_a.offset, defs.FA_P_MAX, defs.FA_ITERS_MAX]
+                    C.exponent_a.offset, C.layout.offset, defs.FA_P_MAX, defs.FA_ITERS_MAX]
 
 
 def test_default_config_needs_no_gpu():
@@ -69,7 +69,7 @@ def test_default_config_needs_no_gpu():
     lib.fa_default_config(ctypes.byref(cfg))
     assert cfg.p_max == 64 and cfg.dtype == defs.FA_F32
     assert cfg.clamp_delta == 1e-6 and cfg.rank_tol == 1e-12 and cfg.pair_tol == 1e-12
-    assert cfg.exponent_a == 2.0
+    assert cfg.exponent_a == 2.0 and cfg.layout == defs.FA_WORKER_MAJOR
 
 
 def test_argument_errors_are_synchronous_without_a_context():

@@ -457,3 +457,68 @@ def test_general_exponent(name, n, a):
         out2 = agg.fa_aggregate_restream(dev, w.m, w.lam, iters).cpu().numpy().astype(np.float64)
         assert rel_l2(out2, ref["out"]) <= GATE
     agg.close()
+
+
+# --------------------------------------------------- interleaved (row-major) storage of G
+def _rows_device(Gw, pitch=None):
+    """[p, n] host array -> device tensor [n, pitch][:, :p] (coordinate k's values contiguous)."""
+    p, n = Gw.shape
+    pitch = pitch or p
+    if Gw.dtype == np.uint16:
+        t = torch.zeros((n, pitch), dtype=torch.bfloat16, device="cuda")
+        t[:, :p] = torch.from_numpy(np.ascontiguousarray(Gw.T).view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        t = torch.zeros((n, pitch), dtype=torch.float32, device="cuda")
+        t[:, :p] = torch.from_numpy(np.ascontiguousarray(Gw.T)).cuda()
+    return t[:, :p]
+
+
+@pytest.mark.parametrize("p,pitch", [(1, 1), (3, 3), (7, 8), (15, 15), (15, 16), (16, 16), (17, 17),
+                                      (31, 32), (40, 44), (64, 64)])
+@pytest.mark.parametrize("n", [1, 5, 255, 1031, 70_001])
+def test_row_major_gram_and_combine(p, pitch, n):
+    announce("row-major gram/combine", p, pitch, n)
+    agg = FlagAggregator(n_max=1 << 20, p_max=64, layout="row_major")
+    Gw = si.random_dense(p, n, seed=100 + p)
+    dev = _rows_device(Gw, pitch)
+    G = as_f64_matrix(Gw)
+    K = agg.fa_gram(dev)
+    ref = G.T @ G
+    scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref)))
+    assert np.abs(K - ref).max() <= 1e-12 * scale.max()
+    c = np.random.default_rng(p).standard_normal(p)
+    out = agg.fa_combine(dev, c).cpu().numpy().astype(np.float64)
+    want = G @ c
+    assert np.abs(out - want).max() <= 2.0 ** -23 * np.abs(G).max() * np.abs(c).sum() + 1e-30
+    agg.close()
+
+
+@pytest.mark.parametrize("name,n", [("cfg1", 100_000), ("cfg2", 300_007), ("cfg5", 30_001)])
+def test_row_major_aggregate(name, n):
+    announce("row-major aggregate", name)
+    w = si.WORKLOADS[name].with_n(n).with_lam(1.0)
+    Gw, _ = si.make_inputs(w, 0)
+    ref = fa_scaled(Gw, w.m, w.lam, w.iters, 0.0)
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, layout="row_major")
+    dev = _rows_device(Gw)
+    out = agg.fa_aggregate(dev, w.m, w.lam, w.iters, 0.0).cpu().numpy().astype(np.float64)
+    info = agg.fa_get_info()
+    assert info.status == 0
+    assert rel_l2(out, ref["out"]) <= GATE
+    assert projector_difference(info.A, ref["A"], ref["R"]) <= GATE
+    Y = agg.fa_basis(dev, w.m).cpu().numpy().astype(np.float64).T
+    assert np.abs(Y.T @ Y - np.eye(w.m)).max() <= 1e-5
+    with pytest.raises(FaError):
+        agg.fa_aggregate_restream(dev, w.m, w.lam, 2)
+    agg.close()
+
+
+def test_row_major_bf16():
+    announce("row-major bf16")
+    w = si.WORKLOADS["cfg4"].with_n(50_003)
+    Gw, _ = si.make_inputs(w, 0)
+    ref = fa_scaled(Gw, w.m, w.lam, w.iters, 0.0)
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype="bf16", layout="row_major")
+    out = agg.fa_aggregate(_rows_device(Gw), w.m, w.lam, w.iters, 0.0).cpu().numpy()
+    assert rel_l2(out, ref["out"]) <= GATE
+    agg.close()
