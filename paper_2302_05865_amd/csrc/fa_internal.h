@@ -16,7 +16,8 @@
 
 // layout of the p x p solvers' global workspace (doubles)
 #define FA_GWS_GENERIC (2 * FA_P_MAX * (FA_P_MAX + 1))    // any-p Jacobi kernel: D2inv, Vt
-#define FA_GWS_TILES (3 * FA_P_MAX * FA_P_MAX)            // 16 < p <= 64 matrix-core kernel
+// 16 < p <= 64 matrix-core kernel: three matrices as (p_max/16)^2 tiles of 272 doubles
+#define FA_GWS_TILES (3 * (FA_P_MAX / 16) * (FA_P_MAX / 16) * 272)
 #define FA_GWS_MLAST_OFF (FA_GWS_GENERIC + FA_GWS_TILES)  // last weighted-PCA matrix N x N, rank, m
 #define FA_GWS_DOUBLES (FA_GWS_MLAST_OFF + FA_P_MAX * FA_P_MAX + 2)
 

@@ -79,57 +79,70 @@ __device__ __forceinline__ double rsq2(double x) {
 }
 
 // ---- tiles ---------------------------------------------------------------------------------
-// tile (I, J) of a matrix stored as T x T tiles of 256 doubles; entry r of lane l at r*64 + l
-template <int T>
-__device__ __forceinline__ v4d load_tile(const double* base, int I, int J, int lane) {
-  const double* t = base + (I * T + J) * 256 + lane;
-  return v4d{t[0], t[64], t[128], t[192]};
+// A matrix is stored as T x T tiles of 16 x 16.  Lane l = 16 q + c of a wavefront holds rows
+// 4e + q (e = 0..3), column c of a tile, as the matrix instruction delivers them; entry e of
+// lane l sits at e * FA_ES + sw(l) doubles into the tile.  Both the lane-parallel access
+// (fixed e) and the transposed store (lane (q, c), fixed source entry r, goes to entry c / 4,
+// lane 16 (c % 4) + 4 r + q) then touch every LDS bank once per half wavefront: the entry
+// stride 68 spreads the four destination entries over banks, and sw() moves the bit of c
+// that would otherwise be lost into the bit that q leaves constant within a half wavefront.
+constexpr int FA_ES = 68, FA_TILE = 272;
+__device__ __forceinline__ int sw(int l) { return l ^ ((l >> 5) << 1); }
+template <int T, typename P>
+__device__ __forceinline__ v4d load_tile(P base, int I, int J, int lane) {
+  const double* t = base + (I * T + J) * FA_TILE + sw(lane);
+  return v4d{t[0], t[FA_ES], t[2 * FA_ES], t[3 * FA_ES]};
 }
 template <int T>
 __device__ __forceinline__ void store_tile(double* base, int I, int J, int lane, const v4d& v) {
-  double* t = base + (I * T + J) * 256 + lane;
-  t[0] = v[0]; t[64] = v[1]; t[128] = v[2]; t[192] = v[3];
+  double* t = base + (I * T + J) * FA_TILE + sw(lane);
+  t[0] = v[0]; t[FA_ES] = v[1]; t[2 * FA_ES] = v[2]; t[3 * FA_ES] = v[3];
 }
-// the same values written as the transposed tile (J, I): element (4r + q4, c16) of (I, J) is
-// element (c16, 4r + q4) of (J, I), i.e. entry c16/4 of lane (c16 % 4) * 16 + 4r + q4
+// the same values written as the transposed tile (J, I): element (4r + q, c) of (I, J) is
+// element (c, 4r + q) of (J, I), i.e. entry c / 4 of lane 16 (c % 4) + 4r + q
 template <int T>
 __device__ __forceinline__ void store_tile_transposed(double* base, int I, int J, int lane,
                                                       const v4d& v) {
   const int c16 = lane & 15, q4 = lane >> 4;
-  double* t = base + (J * T + I) * 256 + (c16 >> 2) * 64 + (c16 & 3) * 16 + q4;
+  double* t = base + (J * T + I) * FA_TILE + (c16 >> 2) * FA_ES + sw((c16 & 3) * 16 + q4);
 #pragma unroll
   for (int r = 0; r < 4; ++r) t[4 * r] = v[r];
 }
 // offset of element (i, j) in the tiled storage
 template <int T>
 __device__ __forceinline__ int eidx(int i, int j) {
-  return ((i >> 4) * T + (j >> 4)) * 256 + ((i & 15) >> 2) * 64 + (i & 3) * 16 + (j & 15);
+  return ((i >> 4) * T + (j >> 4)) * FA_TILE + ((i & 15) >> 2) * FA_ES +
+         sw((i & 3) * 16 + (j & 15));
 }
 // offset of element (a, j) of a matrix kept in A-operand order: tile (a/16, j/16), entry
 // (j%16)/4 of lane ((j%16)%4) * 16 + a%16   [lane (i, k) supplies element (i, 4s + k)]
 template <int T>
 __device__ __forceinline__ int aidx(int a, int j) {
-  return ((a >> 4) * T + (j >> 4)) * 256 + ((j & 15) >> 2) * 64 + (j & 3) * 16 + (a & 15);
+  return ((a >> 4) * T + (j >> 4)) * FA_TILE + ((j & 15) >> 2) * FA_ES +
+         sw((j & 3) * 16 + (a & 15));
 }
 __device__ __forceinline__ v4d mma4(const v4d& a, const v4d& b, v4d acc) {
 #pragma unroll
   for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s], b[s], acc, 0, 0, 0);
   return acc;
 }
-// the k-th pair (I <= J) of the upper triangle, row by row
+// the k-th pair (I <= J) of the upper triangle: the T diagonal tiles first (the wavefronts
+// that start first hold them, one per SIMD), then the rest row by row
 template <int T>
 __device__ __forceinline__ void upper_pair(int k, int* I, int* J) {
-  int i = 0, rem = k;
-  while (rem >= T - i) { rem -= T - i; ++i; }
-  *I = i; *J = i + rem;
+  if (k < T) { *I = k; *J = k; return; }
+  int i = 0, rem = k - T;
+  while (rem >= T - 1 - i) { rem -= T - 1 - i; ++i; }
+  *I = i; *J = i + 1 + rem;
 }
 
 struct Small {
   double s[64], dinv[64], w[64], wn[64], r1[64], beta[64], rinv[64], gd[64], rho[64];
-  double slot[2][2][NW];   // [parity][trace | frobenius][wavefront]
+  double dgx[2][64], dgy[2][64];   // [step parity]: diagonals of X_k and of X_k^2
   double red[NW];
   int piv[64], used[64];
-  int flag;
+  int dec[4];   // word of purification step g at [g & 3]: g << 4 | trace ok (4) | converged (2) | square (1)
+  int flag;     // a wavefront gave up waiting for a steering word
 };
 
 }  // namespace
@@ -144,7 +157,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
                                                              double* __restrict__ gws,
                                                              double* __restrict__ Ml,
                                                              fa_resume* rs) {
-  constexpr int N = 16 * T, TT = T * T, NTP = T * (T + 1) / 2, MSZ = TT * 256;
+  constexpr int N = 16 * T, TT = T * T, NTP = T * (T + 1) / 2, MSZ = TT * FA_TILE;
   constexpr int EPT = (N * N + NTHREADS - 1) / NTHREADS;   // matrix entries per thread
   extern __shared__ __attribute__((aligned(16))) double lds[];
   double* B0 = lds;
@@ -157,6 +170,13 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
   double* RtG = gws + 2 * MSZ;      // rows of the Cholesky factor of K~, row-major N x N
   // Ml: last weighted-PCA matrix, row-major N x N, then rank, m (for the eigengap diagnostic)
 
+#ifdef FA_K3_TIMING
+  long long tq[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  long long tlast = clock64();
+#define FA_TICK(i) do { const long long tn_ = clock64(); tq[i] += tn_ - tlast; tlast = tn_; } while (0)
+#else
+#define FA_TICK(i) do { } while (0)
+#endif
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c16 = lane & 15, q4 = lane >> 4;
   const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
@@ -175,6 +195,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     sm.w[tid] = si > 0.0 ? 1.0 : 0.0;
     sm.used[tid] = 0;
     sm.rho[tid] = 0.0;
+    if (tid < 4) sm.dec[tid] = 0;   // tag 0 is never used
   }
   __syncthreads();
   bool bad = false, live = false;
@@ -267,8 +288,10 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     __syncthreads();
     return rank;
   };
+  FA_TICK(0);
   const int rank = pivoted_cholesky(B0, B1, rank_tol, N);
   const int mm = m < rank ? m : rank;
+  FA_TICK(1);
 
   // ---- R = R~ D^1/2 in both operand orders; R 1; Cholesky rows kept for the epilogue --------
 #pragma unroll
@@ -320,11 +343,12 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
   int uI = 0, uJ = 0;
   if (wave < NTP) upper_pair<T>(wave, &uI, &uJ);
   const double rs_delta = 1.0 / sqrt(delta);
-  int iters_done = 0, steps = 0;
+  int iters_done = 0, steps = 0, gstep = 0;
   double* cur = B0;   // where the projector of the last solve is
   double* nxt = B1;
   int failed = 0;
 
+  FA_TICK(0);
   for (int it = 0; it < iters; ++it) {
     // ---- C: diagonal from the data weights and the row sums of the pair part ---------------
     {
@@ -374,6 +398,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
       for (int r = 0; r < 4; ++r) Ml[(16 * fI + 4 * r + q4) * N + 16 * fJ + c16] = mt[r];
     }
     cur = B0; nxt = B1;
+    FA_TICK(2);
     if (mm < rank) {
       // ---- X_0 = M / trace(M) (slightly less: any scale with eigenvalues in [0, 1] will do)
       const double sc = __builtin_amdgcn_rcp(hi) * (1.0 - 1e-7);
@@ -383,62 +408,115 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
         for (int r = 0; r < 4; ++r) x[r] *= sc;
         store_tile<T>(B0, fI, fJ, lane, x);
       }
-      __syncthreads();
       // ---- purification ---------------------------------------------------------------------
-      double tX = hi * sc;          // trace(X_k), carried: exact in exact arithmetic
-      bool sq_prev = false, conv = false;
-      for (int k = 0; k < MAX_PURIFY; ++k) {
-        v4d x = {0.0, 0.0, 0.0, 0.0}, y = {0.0, 0.0, 0.0, 0.0};
+      // A wavefront's fp64 vector instructions do not get a turn while older wavefronts of
+      // its SIMD have matrix instructions to issue, and every dependent LDS round trip or
+      // cross-lane sum costs hundreds of cycles, so measuring and deciding stay off the
+      // multiplying wavefronts' path:
+      //  - wavefronts 0..NTP-1 multiply (one tile of X_k^2 each); those with a diagonal tile
+      //    leave the diagonals of X_k and X_k^2 in LDS;
+      //  - during step k wavefront NTP (on the SIMD with the fewest multiplying wavefronts)
+      //    sums the diagonals left in step k-1 (trace(X_{k-1}), trace(X_{k-1}^2) =
+      //    |X_{k-1}|_F^2) and publishes the word of step k: "X_{k-1} was a projector" (then
+      //    X_k, its polished successor, is the result) and "square X_k", from trace(X_k) =
+      //    |X_{k-1}|_F^2 after a squaring and 2 trace(X_{k-1}) - |X_{k-1}|_F^2 otherwise;
+      //  - the multiplying wavefronts pick the word up after their products; everybody else
+      //    reads it at the top of the next step, after the barrier.
+      // Waits: the steering wavefront waits for nobody, so the readers' bounded spin ends; one
+      // that gives up (never seen) raises sm.flag, which all read at the top of the next step.
+      ++gstep;                        // a tag of its own between solves: no stale word matches
+      bool sq_prev = hi * sc > (double)mm, conv = false;
+      int wprev = 0;                  // the word of the previous step
+      bool reread = wave > NTP;       // ... fetched from LDS by those who did not use it then
+      if (tid == 0) sm.flag = 0;
+      __syncthreads();
+      // One step: X_k in cu, X_{k+1} into nx.  Written for fixed buffers (the loop below
+      // alternates two instances) so that every LDS address is loop invariant: a wavefront
+      // that leaves the barrier behind older ones of its SIMD can put its loads in flight at
+      // once, without a vector instruction that would wait for their products.
+      // Returns false when the loop is over.
+      auto step = [&](double* cu, double* nx, int k) __attribute__((always_inline)) -> bool {
+        ++gstep;                      // tags the words: never repeats within a launch
+        const int fl = sm.flag;       // raised before the last barrier, if at all
+        if (k > 0) {
+          // in place since the last barrier: its publisher waits for nobody
+          if (reread) wprev = sm.dec[(gstep - 1) & 3];
+          if (wprev & 2) {            // X_{k-1}, left alone in nx, is the result
+            conv = (wprev & 4) != 0;
+            cur = nx; nxt = cu;
+            return false;
+          }
+        }
         if (wave < NTP) {
-          // own tile (uI, uJ) of X_k^2 = sum_K X(K, uI)^T X(K, uJ)
+          // own tile (uI, uJ) of X_k^2 = sum_K X(K, uI)^T X(K, uJ); the operands of the
+          // next K are on their way from LDS while this K is multiplied
+          v4d y = {0.0, 0.0, 0.0, 0.0};
+          v4d a = load_tile<T>(cu, 0, uI, lane), b = load_tile<T>(cu, 0, uJ, lane);
 #pragma unroll
           for (int K = 0; K < T; ++K) {
-            const v4d b = load_tile<T>(cur, K, uJ, lane);
-            y = mma4(load_tile<T>(cur, K, uI, lane), b, y);
-            if (K == uI) x = b;
+            v4d an = a, bn = b;
+            if (K + 1 < T) {
+              an = load_tile<T>(cu, K + 1, uI, lane);
+              bn = load_tile<T>(cu, K + 1, uJ, lane);
+            } else {
+              an = load_tile<T>(cu, uI, uJ, lane);       // the tile itself, for the update
+            }
+            __builtin_amdgcn_sched_barrier(0);           // keep those loads ahead of the products
+            y = mma4(a, b, y);
+            a = an; b = bn;
           }
-          // trace and squared Frobenius norm of this tile of X_k (off-diagonal tiles stand
-          // for their mirror image too)
-          double td = 0.0, fr = 0.0;
+          const v4d x = a;
+          if (uI == uJ) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            td += (uI == uJ && isdiag[r]) ? x[r] : 0.0;
-            fr = fma(x[r], x[r], fr);
+            for (int r = 0; r < 4; ++r)
+              if (isdiag[r]) {
+                sm.dgx[k & 1][16 * uI + c16] = x[r];
+                sm.dgy[k & 1][16 * uI + c16] = y[r];
+              }
           }
-          if (uI != uJ) fr *= 2.0;
-          td = wave_sum(td);
-          fr = wave_sum(fr);
-          if (lane == 0) { sm.slot[k & 1][0][wave] = td; sm.slot[k & 1][1][wave] = fr; }
-        }
-        if (k > 0) {
-          // what everyone published about X_{k-1} (the barrier of step k-1 lies in between)
-          double trp = 0.0, frp = 0.0;
+          // this step's word
+          int word = 0, tries = 0;
+          do {
+            word = __hip_atomic_load(&sm.dec[gstep & 3], __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_WORKGROUP);
+          } while ((word >> 4) != gstep && ++tries < (1 << 22));
+          word = __builtin_amdgcn_readfirstlane(word);
+          if ((word >> 4) != gstep) { sm.flag = 1; word = 2; reread = true; }
+          wprev = word;
+          if (!(word & 2)) {
+            v4d xn;
+            if (word & 1) {
+              xn = y;
+            } else {
 #pragma unroll
-          for (int q = 0; q < NTP; ++q) {
-            trp += sm.slot[(k - 1) & 1][0][q];
-            frp += sm.slot[(k - 1) & 1][1][q];
+              for (int r = 0; r < 4; ++r) xn[r] = fma(2.0, x[r], -y[r]);
+            }
+            store_tile<T>(nx, uI, uJ, lane, xn);
+            if (uI != uJ) store_tile_transposed<T>(nx, uI, uJ, lane, xn);
           }
-          if (trp - frp < 1e-10) {
-            // X_{k-1} is a projector to working precision, and so is its successor X_k (in
-            // cur); it is the wanted one only if the trace is m
-            conv = fabs(trp - (double)mm) < 0.25;
-            break;
+        } else if (wave == NTP) {
+          int word = gstep << 4;
+          if (k == 0) {
+            word |= sq_prev ? 1 : 0;
+          } else {
+            const double dx = lane < N ? sm.dgx[(k - 1) & 1][lane] : 0.0;
+            const double dy = lane < N ? sm.dgy[(k - 1) & 1][lane] : 0.0;
+            const double trx = wave_sum(dx), fro = wave_sum(dy);
+            if (trx - fro < 1e-10) word |= 2 | (fabs(trx - (double)mm) < 0.25 ? 4 : 0);
+            if ((sq_prev ? fro : fma(2.0, trx, -fro)) > (double)mm) word |= 1;
+            sq_prev = (word & 1) != 0;
           }
-          tX = sq_prev ? frp : fma(2.0, trp, -frp);
+          if (lane == 0) __hip_atomic_store(&sm.dec[gstep & 3], word, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_WORKGROUP);
+          wprev = word;
         }
-        const bool sq = tX > (double)mm;
-        if (wave < NTP) {
-          v4d xn;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) xn[r] = sq ? y[r] : fma(2.0, x[r], -y[r]);
-          store_tile<T>(nxt, uI, uJ, lane, xn);
-          if (uI != uJ) store_tile_transposed<T>(nxt, uI, uJ, lane, xn);
-        }
-        sq_prev = sq;
+        if (fl) return false;         // the same value in every wavefront
         steps = steps + 1;
         __syncthreads();
-        double* t = cur; cur = nxt; nxt = t;
-      }
+        return true;
+      };
+      for (int k = 0; k < MAX_PURIFY; k += 2)
+        if (!step(B0, B1, k) || !step(B1, B0, k + 1)) break;
       if (!conv) { failed = 1; break; }
     } else {
       // m >= rank: Y spans all of span(G)
@@ -451,6 +529,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
       }
       __syncthreads();
     }
+    FA_TICK(3);
     // ---- Z = (I - P) R (nxt): A operand = I - P (symmetric), B operand = R from global -------
     if (wave < TT) {
       v4d acc = {0.0, 0.0, 0.0, 0.0};
@@ -459,8 +538,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
         v4d q = load_tile<T>(cur, K, fI, lane);
 #pragma unroll
         for (int r = 0; r < 4; ++r) q[r] = (K == fI && isdiag[r]) ? 1.0 - q[r] : -q[r];
-        const double* rb = Rb + (K * T + fJ) * 256 + lane;
-        acc = mma4(q, v4d{rb[0], rb[64], rb[128], rb[192]}, acc);
+        acc = mma4(q, load_tile<T>((const double*)Rb, K, fJ, lane), acc);
       }
       store_tile<T>(nxt, fI, fJ, lane, acc);
     }
@@ -522,6 +600,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     const bool stop = it0 + it > 0 && fabs(prev_obj - obj) < tol;
     prev_obj = obj;
     __syncthreads();   // red[] is reused by the next solve
+    FA_TICK(4);
     if (stop) break;
     if (tid < 64) sm.w[tid] = sm.wn[tid];
   }
@@ -639,6 +718,11 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     if (tid < p) rs->w[tid] = sm.w[tid];
     if (tid == 0) { rs->prev_obj = prev_obj; rs->it0 = it0 + iters_done; }
   }
+  FA_TICK(5);
+#ifdef FA_K3_TIMING
+  if (tid == 0)
+    for (int i = 0; i < 9; ++i) info->objective[FA_ITERS_MAX - 1 - i] = (double)tq[i];
+#endif
   if (tid == 0) {
     info->status = 0;
     info->p = p; info->m = m; info->rank = rank;
@@ -655,7 +739,7 @@ static hipError_t launch_t(const double* Kd, int p, int m, double lambda, int it
                            double delta, double rank_tol, double pair_tol, double* cd,
                            fa_info* info_d, double* tiles_ws, double* mlast, fa_resume* rs,
                            hipStream_t st, const fa_ktime* tm) {
-  const size_t lds = (size_t)4 * T * T * 256 * sizeof(double) + sizeof(Small);
+  const size_t lds = (size_t)4 * T * T * FA_TILE * sizeof(double) + sizeof(Small);
   static bool prepared = false;
   if (!prepared) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<T>),
