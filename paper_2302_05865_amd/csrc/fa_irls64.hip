@@ -177,7 +177,9 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
 #else
 #define FA_TICK(i) do { } while (0)
 #endif
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // in a scalar register: everything decided per wavefront is a scalar branch
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c16 = lane & 15, q4 = lane >> 4;
   const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
   const int it0 = rs ? rs->it0 : 0;
@@ -440,7 +442,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
         const int fl = sm.flag;       // raised before the last barrier, if at all
         if (k > 0) {
           // in place since the last barrier: its publisher waits for nobody
-          if (reread) wprev = sm.dec[(gstep - 1) & 3];
+          if (reread) wprev = __builtin_amdgcn_readfirstlane(sm.dec[(gstep - 1) & 3]);
           if (wprev & 2) {            // X_{k-1}, left alone in nx, is the result
             conv = (wprev & 4) != 0;
             cur = nx; nxt = cu;
@@ -474,13 +476,12 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
                 sm.dgy[k & 1][16 * uI + c16] = y[r];
               }
           }
-          // this step's word
-          int word = 0, tries = 0;
-          do {
-            word = __hip_atomic_load(&sm.dec[gstep & 3], __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_WORKGROUP);
-          } while ((word >> 4) != gstep && ++tries < (1 << 22));
-          word = __builtin_amdgcn_readfirstlane(word);
+          // this step's word (there already, as a rule)
+          int word = __builtin_amdgcn_readfirstlane(__hip_atomic_load(
+              &sm.dec[gstep & 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+          for (int tries = 0; (word >> 4) != gstep && tries < (1 << 22); ++tries)
+            word = __builtin_amdgcn_readfirstlane(__hip_atomic_load(
+                &sm.dec[gstep & 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
           if ((word >> 4) != gstep) { sm.flag = 1; word = 2; reread = true; }
           wprev = word;
           if (!(word & 2)) {
@@ -499,9 +500,14 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
           if (k == 0) {
             word |= sq_prev ? 1 : 0;
           } else {
-            const double dx = lane < N ? sm.dgx[(k - 1) & 1][lane] : 0.0;
-            const double dy = lane < N ? sm.dgy[(k - 1) & 1][lane] : 0.0;
-            const double trx = wave_sum(dx), fro = wave_sum(dy);
+            // both sums in one pass: the lower half wavefront adds up one diagonal, the
+            // upper half the other (entries N..63 are never written: masked)
+            const double* dg = lane < 32 ? sm.dgx[(k - 1) & 1] : sm.dgy[(k - 1) & 1];
+            const int l32 = lane & 31;
+            const double d0 = l32 < N ? dg[l32] : 0.0, d1 = l32 + 32 < N ? dg[l32 + 32] : 0.0;
+            const double hs = row_sum(d0 + d1);
+            const double trx = lane_bcast(hs, 0) + lane_bcast(hs, 16);
+            const double fro = lane_bcast(hs, 32) + lane_bcast(hs, 48);
             if (trx - fro < 1e-10) word |= 2 | (fabs(trx - (double)mm) < 0.25 ? 4 : 0);
             if ((sq_prev ? fro : fma(2.0, trx, -fro)) > (double)mm) word |= 1;
             sq_prev = (word & 1) != 0;
@@ -510,7 +516,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
                                             __HIP_MEMORY_SCOPE_WORKGROUP);
           wprev = word;
         }
-        if (fl) return false;         // the same value in every wavefront
+        if (__builtin_amdgcn_readfirstlane(fl)) return false;   // the same in every wavefront
         steps = steps + 1;
         __syncthreads();
         return true;
