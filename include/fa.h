@@ -176,6 +176,21 @@ fa_status fa_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, fl
                    int64_t ldy);
 
 /*
+ * Streamed check of a materialised basis (Sec. 2.1: Y has orthonormal columns, and the
+ * explained variance of worker i is |Y^T g_i|^2 / |g_i|^2).  One pass over Y and G computes, in
+ * fp64 on the device,
+ *   YtY_host (m x m, row-major, host memory)  = Y^T Y   - the identity for a basis,
+ *   YtG_host (m x p, row-major, host memory)  = Y^T G   - row a, column i: y_a . g_i.
+ * Y is device memory as fa_basis writes it (m columns of n floats, column a at Y + a*ldy,
+ * ldy >= n, 16-byte aligned); G, ldg, p, n as for fa_aggregate, in the context's dtype and
+ * layout.  Y need not come from fa_basis.  Synchronises the context's stream.  Uses the
+ * context's workspace: the record of the last solve stays, its p x p scratch does not.
+ * FA_ERR_ARG for bad shapes or pointers, FA_ERR_DEVICE if a launch or copy fails.
+ */
+fa_status fa_check_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n,
+                         const float* Y, int64_t ldy, int m, double* YtY_host, double* YtG_host);
+
+/*
  * Per-kernel timing of fa_aggregate with HIP events on the context's stream.
  * fa_set_profiling(ctx, 1) makes every later fa_aggregate attach a begin and an end event
  * to each of its kernel dispatches (the events carry the kernel's own timestamps; nothing

@@ -234,3 +234,12 @@ def projector_difference(A1: np.ndarray, A2: np.ndarray, R: np.ndarray) -> float
     """
     W1, W2 = R @ A1, R @ A2
     return float(np.linalg.norm(W1 @ W1.T - W2 @ W2.T))
+
+
+def basis_products(G: np.ndarray, Y: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """``(Y^T Y, Y^T G)`` for ``G`` (n x p) and ``Y`` (n x m), written out as the definition
+    (Sec. 2.1: ``Y`` has orthonormal columns, so the first is the identity for a valid basis;
+    the explained variance of worker ``i`` is ``sum_a (Y^T G)[a, i]^2 / ||g_i||^2``)."""
+    G = np.asarray(G, dtype=np.float64)
+    Y = np.asarray(Y, dtype=np.float64)
+    return Y.T @ Y, Y.T @ G

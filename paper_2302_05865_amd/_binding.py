@@ -22,7 +22,8 @@ _lib: Optional[ctypes.CDLL] = None
 # every symbol include/fa.h declares
 EXPORTED_SYMBOLS = (
     "fa_default_config", "fa_create", "fa_destroy", "fa_set_stream", "fa_aggregate",
-    "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_set_profiling",
+    "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_check_basis",
+    "fa_set_profiling",
     "fa_get_timings", "fa_enqueue_kernel", "fa_aggregate_restream", "fa_get_restream_info",
     "fa_status_string", "fa_version",
 )
@@ -73,6 +74,8 @@ def load_library() -> ctypes.CDLL:
     lib.fa_combine.restype = i32
     lib.fa_basis.argtypes = [vp, vp, i64, i32, i64, vp, i64]
     lib.fa_basis.restype = i32
+    lib.fa_check_basis.argtypes = [vp, vp, i64, i32, i64, vp, i64, i32, vp, vp]
+    lib.fa_check_basis.restype = i32
     lib.fa_set_profiling.argtypes = [vp, i32]
     lib.fa_set_profiling.restype = i32
     lib.fa_get_timings.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4)]
@@ -270,6 +273,25 @@ class FlagAggregator:
         _check(self._lib.fa_basis(self._ctx, ptr, ldg, p, n, ctypes.c_void_p(Y.data_ptr()), ldy),
                "fa_basis")
         return Y[:, :n]
+
+    def fa_check_basis(self, G, Y):
+        """(Y^T Y, Y^T G) as float64 arrays of shapes (m, m) and (m, p), computed on the device
+        in one pass; Y is an ``[m, n]`` float32 device tensor whose rows are the columns of the
+        basis, as fa_basis returns it."""
+        ptr, ldg, p, n = self._matrix(G)
+        torch = self._torch
+        if (not Y.is_cuda or Y.dim() != 2 or Y.dtype != torch.float32 or Y.shape[1] != n or
+                Y.stride(1) != 1):
+            raise TypeError("Y must be an [m, n] float32 device tensor with unit inner stride")
+        m = int(Y.shape[0])
+        ldy = int(Y.stride(0)) if m > 1 else n
+        YtY = np.empty((m, m), dtype=np.float64)
+        YtG = np.empty((m, p), dtype=np.float64)
+        self._use_current_stream()
+        _check(self._lib.fa_check_basis(self._ctx, ptr, ldg, p, n, ctypes.c_void_p(Y.data_ptr()),
+                                        ldy, m, YtY.ctypes.data_as(ctypes.c_void_p),
+                                        YtG.ctypes.data_as(ctypes.c_void_p)), "fa_check_basis")
+        return YtY, YtG
 
     def fa_enqueue_kernel(self, which: int, G, m: int, lam: float, iters: int, tol: float,
                           out=None) -> None:

@@ -1,6 +1,8 @@
 // C ABI of the Flag Aggregator library (see include/fa.h): argument checking, workspace
 // ownership, and the order in which the kernels are enqueued.  No arithmetic happens here.
 #include <hip/hip_runtime.h>
+
+#include <vector>
 #include <math.h>
 #include <new>
 #include <stdlib.h>
@@ -355,6 +357,33 @@ extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int6
     if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, A + a, m, Y + (int64_t)a * ldy,
                           c->combine_max_blocks, c->stream, nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_check_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n,
+                                    const float* Y, int64_t ldy, int m, double* YtY_host,
+                                    double* YtG_host) {
+  if (!check_matrix_args(c, G, ldg, p, n) || !Y || ((uintptr_t)Y & 15u) != 0) return FA_ERR_ARG;
+  if (m < 1 || m > p || ldy < n || !YtY_host || !YtG_host) return FA_ERR_ARG;
+  const int TMr = (m + 15) / 16, TC = TMr + (p + 15) / 16;
+  const int T = (c->cfg.p_max + 15) / 16;
+  // the Gram pass's partial buffer holds gram_max_blocks * T^2 tiles
+  const int max_parts = (int)((int64_t)c->gram_max_blocks * T * T / (TMr * TC));
+  const int ncols = 16 * TMr + p;
+  static_assert(FA_GWS_DOUBLES >= FA_P_MAX * (FA_P_MAX + 16 * ((FA_P_MAX + 15) / 16)),
+                "the solvers' workspace doubles as the result buffer of the check");
+  if (fa_launch_cross(Y, ldy, m, G, ldg, p, n, c->cfg.dtype, c->cfg.layout, max_parts,
+                      c->partials, c->gws, c->stream) != hipSuccess)
+    return FA_ERR_DEVICE;
+  std::vector<double> W((size_t)m * ncols);
+  if (hipMemcpyAsync(W.data(), c->gws, W.size() * sizeof(double), hipMemcpyDeviceToHost,
+                     c->stream) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
+  for (int a = 0; a < m; ++a) {
+    for (int b = 0; b < m; ++b) YtY_host[a * m + b] = W[(size_t)a * ncols + b];
+    for (int i = 0; i < p; ++i) YtG_host[a * p + i] = W[(size_t)a * ncols + 16 * TMr + i];
+  }
   return FA_OK;
 }
 

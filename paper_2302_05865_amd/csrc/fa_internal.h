@@ -87,6 +87,10 @@ hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int d
                              const double* c, int cstride, float* out, int max_blocks,
                              hipStream_t st, const fa_ktime* tm);
 
+// Streamed check of a basis: W = Y^T [Y | G] (m rows, 16 ceil(m/16) + p columns, row-major).
+hipError_t fa_launch_cross(const float* Y, int64_t ldy, int m, const void* G, int64_t ldg, int p,
+                           int64_t n, int dtype, int layout, int max_parts, double* partials,
+                           double* Wd, hipStream_t st);
 
 #define FA_LAUNCH(tm, kern, grid, block, lds, st, ...)                                          \
   do {                                                                                           \

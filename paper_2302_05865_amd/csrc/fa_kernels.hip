@@ -736,6 +736,104 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
 }
 
 // ------------------------------------------------------------------------------------------
+// Streamed check of a materialised basis Y (n x m, fp32, column a at Y + a*ldy): one pass
+// computes W = Y^T [Y | G] in fp64 on the matrix cores: Y^T Y (the identity for the
+// orthonormal basis of Sec. 2.1) and Y^T G (row a, column i: the projection of g_i on y_a,
+// whose squares add up to the explained variance of Sec. 2.1 times |g_i|^2).
+// One workgroup (sixteen wavefronts) per (row stripe, 16 x 16 output tile); a wavefront takes
+// 16 rows at a time: lane (c, k) holds rows 4k..4k+3 of column c of either operand (one
+// 16-byte load where the rows are contiguous), and feeds row 4k+s of both to the s-th
+// matrix instruction - the contraction does not care in which order the rows come, as long
+// as both operands agree.  Not a tuned kernel: the operand of a 16 x 16 tile is re-read for
+// every tile that uses it (once or twice at p, m <= 16).
+// G is addressed by strides (elements): g_rs between rows, g_cs between columns, which
+// covers both storage orders.
+template <typename E>
+__device__ __forceinline__ double load_elem(const unsigned char* base, int64_t idx) {
+  if constexpr (E::SIZE == 4) return (double)reinterpret_cast<const float*>(base)[idx];
+  else return (double)bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(base)[idx]);
+}
+// rows row0..row0+3 of one column (zero past n, zero if the column does not exist)
+template <typename E>
+__device__ __forceinline__ void load_rows4(const unsigned char* base, int64_t col_off,
+                                           int64_t rs, int64_t row0, int64_t n, bool on,
+                                           double* x) {
+  x[0] = x[1] = x[2] = x[3] = 0.0;
+  if (!on || row0 >= n) return;
+  if (rs == 1 && row0 + 4 <= n) {
+    const unsigned char* src = base + (col_off + row0) * E::SIZE;
+    if constexpr (E::SIZE == 4) {
+      if (((uintptr_t)src & 15u) == 0) {
+        const float4 f = *reinterpret_cast<const float4*>(src);
+        x[0] = (double)f.x; x[1] = (double)f.y; x[2] = (double)f.z; x[3] = (double)f.w;
+        return;
+      }
+    } else {
+      if (((uintptr_t)src & 7u) == 0) {
+        const uint2 h = *reinterpret_cast<const uint2*>(src);
+        x[0] = (double)bf16_bits_to_f32(h.x & 0xffffu); x[1] = (double)bf16_bits_to_f32(h.x >> 16);
+        x[2] = (double)bf16_bits_to_f32(h.y & 0xffffu); x[3] = (double)bf16_bits_to_f32(h.y >> 16);
+        return;
+      }
+    }
+  }
+  for (int s = 0; s < 4; ++s)
+    if (row0 + s < n) x[s] = load_elem<E>(base, col_off + (row0 + s) * rs);
+}
+
+template <typename E>
+__global__ __launch_bounds__(1024) void fa_cross_kernel(const float* __restrict__ Y, int64_t ldy,
+                                                        int m,
+                                                        const unsigned char* __restrict__ G,
+                                                        int64_t g_rs, int64_t g_cs, int p,
+                                                        int64_t n, int TMr, int TC,
+                                                        double* __restrict__ partials) {
+  __shared__ double red[16 * 256];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c16 = lane & 15, kq = lane >> 4;
+  const int ta = (int)blockIdx.y / TC, tb = (int)blockIdx.y % TC;
+  // left operand: column ca of Y; right operand: column cb of Y (tb < TMr) or of G
+  const int ca = ta * 16 + c16;
+  const bool right_is_y = tb < TMr;
+  const int cb = (right_is_y ? tb : tb - TMr) * 16 + c16;
+  const bool a_on = ca < m, b_on = right_is_y ? cb < m : cb < p;
+  const unsigned char* Yb = reinterpret_cast<const unsigned char*>(Y);
+  const int64_t a_off = (int64_t)ca * ldy;
+  const int64_t b_off = right_is_y ? (int64_t)cb * ldy : (int64_t)cb * g_cs;
+  const int64_t nchunks = (n + 15) / 16;
+  const int64_t wid = (int64_t)blockIdx.x * 16 + wave, nw = (int64_t)gridDim.x * 16;
+  v4f64 acc = {0.0, 0.0, 0.0, 0.0};
+  constexpr int U = 4;                       // chunks in flight per wavefront
+  for (int64_t c0 = wid; c0 < nchunks; c0 += nw * U) {
+    double a[U][4], b[U][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t ch = c0 + (int64_t)u * nw;
+      const int64_t row0 = ch < nchunks ? ch * 16 + 4 * kq : n;
+      load_rows4<ElemF32>(Yb, a_off, 1, row0, n, a_on, a[u]);
+      if (right_is_y) load_rows4<ElemF32>(Yb, b_off, 1, row0, n, b_on, b[u]);
+      else load_rows4<E>(G, b_off, g_rs, row0, n, b_on, b[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u][s], b[u][s], acc, 0, 0, 0);
+  }
+  // the wavefronts add up in wave order; one partial tile per workgroup leaves the kernel
+#pragma unroll
+  for (int r = 0; r < 4; ++r) red[wave * 256 + r * 64 + lane] = acc[r];
+  __syncthreads();
+  double* dst = partials + ((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * 256;
+  for (int e = threadIdx.x; e < 256; e += 1024) {
+    double tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += red[w * 256 + e];
+    dst[e] = tot;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // K3: the p x p solver, one workgroup, matrices in LDS.
 
 __global__ __launch_bounds__(FA_IRLS_THREADS) void fa_irls_kernel(const double* __restrict__ Kg,
@@ -870,6 +968,31 @@ hipError_t fa_launch_proj_reduce(const double* partials, int nparts, int p, int 
   const int T = (p + 15) / 16, TM = (m + 15) / 16;
   FA_LAUNCH(tm, fa_gram_reduce_kernel, dim3(T * TM * 4), dim3(1024), 0, st, partials, nparts, T,
             p, Td, TM, m);
+  return hipGetLastError();
+}
+
+// W = Y^T [Y | G], m x (16 ceil(m/16) + p) row-major into Wd: the partial tiles of at most
+// max_parts row stripes go to `partials` (max_parts * tiles * 256 doubles), then K2 adds them.
+hipError_t fa_launch_cross(const float* Y, int64_t ldy, int m, const void* G, int64_t ldg, int p,
+                           int64_t n, int dtype, int layout, int max_parts, double* partials,
+                           double* Wd, hipStream_t st) {
+  const int TMr = (m + 15) / 16, TC = TMr + (p + 15) / 16;
+  const int64_t g_rs = layout == FA_ROW_MAJOR ? ldg : 1, g_cs = layout == FA_ROW_MAJOR ? 1 : ldg;
+  int64_t stripes = (n + 16 * 16 * 4 - 1) / (16 * 16 * 4);   // at least one pass of 4 chunks each
+  if (stripes > max_parts) stripes = max_parts;
+  if (stripes < 1) stripes = 1;
+  const dim3 grid((unsigned)stripes, (unsigned)(TMr * TC));
+  if (dtype == FA_F32)
+    hipLaunchKernelGGL((fa_cross_kernel<ElemF32>), grid, dim3(1024), 0, st, Y, ldy, m,
+                       (const unsigned char*)G, g_rs, g_cs, p, n, TMr, TC, partials);
+  else
+    hipLaunchKernelGGL((fa_cross_kernel<ElemBF16>), grid, dim3(1024), 0, st, Y, ldy, m,
+                       (const unsigned char*)G, g_rs, g_cs, p, n, TMr, TC, partials);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int ncols = 16 * TMr + p;
+  hipLaunchKernelGGL(fa_gram_reduce_kernel, dim3(TMr * TC * 4), dim3(1024), 0, st,
+                     (const double*)partials, (int)stripes, TMr, m, Wd, TC, ncols);
   return hipGetLastError();
 }
 

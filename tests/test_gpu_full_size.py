@@ -4,6 +4,8 @@ cfg3 (n = 25.6M).  The oracle's R-factor form finishes these in seconds.  cfg4 (
 n = 124M) and cfg5 (n = 50M) run at reduced n in test_gpu_parity.py: generating them
 with the seeded NumPy stream and factoring them in fp64 takes minutes on the host.
 """
+import time
+
 import numpy as np
 import pytest
 
@@ -39,5 +41,14 @@ def test_full_size(name):
     rows = rng.integers(0, w.n, 1000)
     direct = Gw[:, rows].astype(np.float64).T @ ref["c"]
     assert np.allclose(got[rows], direct, rtol=0, atol=1e-4 * np.abs(direct).max())
+    # the basis at full size, checked on the device in one streamed pass: orthonormal columns
+    # (Y is stored in fp32) and the oracle's explained variances
+    Y = agg.fa_basis(dev, w.m)
+    t0 = time.perf_counter()
+    YtY, YtG = agg.fa_check_basis(dev, Y)
+    announce(name, "fa_check_basis seconds", time.perf_counter() - t0)
+    assert np.abs(YtY - np.eye(w.m)).max() <= 1e-5
+    s = np.diag(ref["R"].T @ ref["R"])                     # |g_i|^2
+    assert np.allclose((YtG ** 2).sum(axis=0) / s, ref["v"], atol=1e-5)
     agg.close()
-    del dev, out
+    del dev, out, Y

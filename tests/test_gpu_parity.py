@@ -11,7 +11,8 @@ import pytest
 import torch
 
 import synth_inputs as si
-from oracle import as_f64_matrix, fa_literal, fa_scaled, projector_difference
+from oracle import (as_f64_matrix, basis_products, fa_literal, fa_scaled,
+                    projector_difference)
 from paper_2302_05865_amd import FaError, FlagAggregator
 
 from gpu_util import announce, rel_l2, to_device
@@ -522,3 +523,52 @@ def test_row_major_bf16():
     out = agg.fa_aggregate(_rows_device(Gw), w.m, w.lam, w.iters, 0.0).cpu().numpy()
     assert rel_l2(out, ref["out"]) <= GATE
     agg.close()
+
+
+# ---- streamed check of a materialised basis (Y^T Y, Y^T G on the device) -----------------------
+@pytest.mark.parametrize("name,n,layout", [
+    ("cfg1", 100_000, "worker_major"), ("cfg2", 262_147, "worker_major"),
+    ("cfg2", 4_099, "row_major"), ("cfg3", 65_537, "worker_major"),
+    ("cfg4", 70_001, "worker_major"), ("cfg4", 20_011, "row_major"),
+    ("cfg5", 40_003, "worker_major"), ("cfg2", 13, "worker_major"), ("cfg2", 1, "worker_major")])
+def test_check_basis_matches_the_definition(name, n, layout):
+    announce("fa_check_basis", name, n, layout)
+    w = si.WORKLOADS[name].with_n(n)
+    Gw, _ = si.make_inputs(w, 0)
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, layout=layout)
+    dev = _rows_device(Gw) if layout == "row_major" else to_device(Gw)
+    agg.fa_aggregate(dev, w.m, w.lam, min(w.iters, 4), 0.0)
+    Y = agg.fa_basis(dev, w.m)
+    YtY, YtG = agg.fa_check_basis(dev, Y)
+    # the definition, on exactly the numbers the device holds (Y is stored in fp32)
+    G64 = as_f64_matrix(Gw)
+    Y64 = Y.cpu().numpy().astype(np.float64).T
+    rYY, rYG = basis_products(G64, Y64)
+    scale_g = np.sqrt((G64 ** 2).sum(axis=0)).max()
+    assert np.abs(YtY - rYY).max() <= 1e-11
+    assert np.abs(YtG - rYG).max() <= 1e-11 * max(scale_g, 1.0)
+    # and what it is for: the basis is orthonormal (to the fp32 storage of Y), and the
+    # explained variances of the last solve come back from Y^T G
+    if n > w.p:
+        assert np.abs(YtY - np.eye(w.m)).max() <= 1e-5
+        info = agg.fa_get_info()
+        s = (G64 ** 2).sum(axis=0)
+        assert np.allclose((YtG ** 2).sum(axis=0) / s, info.v, atol=1e-5)
+    agg.close()
+
+
+def test_check_basis_of_any_matrix_and_argument_errors(agg_f32):
+    announce("fa_check_basis free Y")
+    rng = np.random.default_rng(5)
+    n, p, m = 5_003, 15, 3
+    Gw = si.random_dense(p, n, seed=7)
+    dev = to_device(Gw)
+    Yh = rng.standard_normal((m, n)).astype(np.float32)
+    Yd = torch.from_numpy(np.ascontiguousarray(np.pad(Yh, ((0, 0), (0, 1))))).cuda()[:, :n]
+    YtY, YtG = agg_f32.fa_check_basis(dev, Yd)
+    rYY, rYG = basis_products(as_f64_matrix(Gw), Yh.astype(np.float64).T)
+    assert np.abs(YtY - rYY).max() <= 1e-9 and np.abs(YtG - rYG).max() <= 1e-9
+    with pytest.raises(TypeError):
+        agg_f32.fa_check_basis(dev, Yd[:, :-1])
+    with pytest.raises(FaError):
+        agg_f32.fa_check_basis(dev, torch.zeros((p + 1, n), dtype=torch.float32, device="cuda"))

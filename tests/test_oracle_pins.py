@@ -8,7 +8,7 @@ import math
 import numpy as np
 import pytest
 
-from oracle import (as_f64_matrix, decode_bf16, fa_literal, fa_scaled,
+from oracle import (as_f64_matrix, basis_products, decode_bf16, fa_literal, fa_scaled,
                     projector_difference, tsqr_r)
 
 
@@ -412,6 +412,31 @@ def test_projector_difference_matches_dense():
     B2[0] += 0.5
     B2[5] -= 0.5                      # same G2 @ B, different representation
     assert projector_difference(B1, B2, R2) < 1e-12
+
+
+def test_basis_products_by_brute_force_and_on_a_solution():
+    # entry by entry, with plain loops
+    rng = np.random.default_rng(11)
+    G = rng.standard_normal((9, 4))
+    Y = rng.standard_normal((9, 3))
+    YtY, YtG = basis_products(G, Y)
+    for a in range(3):
+        for b in range(3):
+            assert math.isclose(YtY[a, b], sum(Y[k, a] * Y[k, b] for k in range(9)),
+                                rel_tol=1e-12, abs_tol=1e-14)
+        for i in range(4):
+            assert math.isclose(YtG[a, i], sum(Y[k, a] * G[k, i] for k in range(9)),
+                                rel_tol=1e-12, abs_tol=1e-14)
+    # an orthonormal basis gives the identity; a transposed operand would not even have the shape
+    Q = np.linalg.qr(rng.standard_normal((40, 5)))[0]
+    I5, QtG = basis_products(rng.standard_normal((40, 7)), Q)
+    assert I5.shape == (5, 5) and QtG.shape == (5, 7) and np.allclose(I5, np.eye(5), atol=1e-13)
+    # on a solution of the method the column sums of squares of Y^T G are the explained variances
+    G = _rand(60, 6, 3)
+    res = fa_literal(G, 3, 1.0, 5, 0.0)
+    YtY, YtG = basis_products(G, res["Y"])
+    assert np.allclose(YtY, np.eye(3), atol=1e-12)
+    assert np.allclose((YtG ** 2).sum(axis=0) / (G ** 2).sum(axis=0), res["v"], atol=1e-12)
 
 
 def test_bf16_decode_known_patterns():
