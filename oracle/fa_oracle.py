@@ -243,3 +243,73 @@ def basis_products(G: np.ndarray, Y: np.ndarray) -> Tuple[np.ndarray, np.ndarray
     G = np.asarray(G, dtype=np.float64)
     Y = np.asarray(Y, dtype=np.float64)
     return Y.T @ Y, Y.T @ G
+
+
+def fa_literal_grouped(G: np.ndarray, sizes: List[int], m: int, lam: float, iters: int,
+                       tol: float, delta: float = DELTA_DEFAULT,
+                       tau_pair: float = TAU_PAIR_DEFAULT, a: float = 2.0) -> Dict[str, object]:
+    """FA when worker ``i`` sends ``k_i = sizes[i]`` gradients: ``g_i`` is the n x k_i block of
+    consecutive columns of ``G`` (Sec. 2.1, "different number of gradients from each worker";
+    Sec. 2.2, the extension to ``g_i in R^{n x k}``; Appendix D works with such lists).
+
+    The value of worker ``i`` is ``v_i = tr(g_i^T Y Y^T g_i) / tr(g_i^T g_i)``; every other
+    step is ``fa_literal``'s with blocks in place of columns.  Readings (the paper does not
+    spell these out): the pairwise term of Sec. 2.3 needs ``g_i - g_j`` and so exists only
+    between workers with equal ``k``; its distance is the Frobenius one; the factor is
+    ``lam / (P - 1)`` with ``P`` workers; a worker counts once in the output whatever its
+    ``k``: ``d = (1/P) Y Y^T sum_i mean_columns(g_i)``.
+    Returns ``out``, ``Y``, ``v`` and ``w`` (per worker), ``objective``, ``iters_done``.
+    """
+    G = np.asarray(G, dtype=np.float64)
+    n, q = G.shape
+    P = len(sizes)
+    if P < 1 or any(k < 1 for k in sizes) or sum(sizes) != q:
+        raise ValueError("sizes must be positive and add up to the number of columns")
+    if not (1 <= m <= q) or n < m:
+        raise ValueError("need 1 <= m <= number of columns <= ... and n >= m")
+    if iters < 1 or lam < 0 or tol < 0 or not (a >= 1.0):
+        raise ValueError("bad solver arguments")
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(int)
+    blocks = [G[:, off[i]:off[i + 1]] for i in range(P)]
+    s = np.array([np.sum(b * b) for b in blocks])                 # tr(g_i^T g_i)
+    live = s > 0
+    Gn = [b / np.sqrt(s[i]) if live[i] else np.zeros_like(b) for i, b in enumerate(blocks)]
+
+    use_pairs = lam > 0 and P > 1
+    coef = lam / (P - 1) if use_pairs else 0.0
+    Dn: List[np.ndarray] = []
+    if use_pairs:
+        for i in range(P):
+            for j in range(P):
+                if i == j or sizes[i] != sizes[j]:
+                    continue
+                d = blocks[i] - blocks[j]
+                d2 = np.sum(d * d)
+                if d2 > tau_pair * (s[i] + s[j]):
+                    Dn.append(d / np.sqrt(d2))
+
+    w = live.astype(np.float64)
+    wp = np.ones(len(Dn))
+    objective: List[float] = []
+    Y = None
+    v = np.zeros(P)
+    for k in range(iters):
+        cols = [np.sqrt(w[i]) * Gn[i] for i in range(P)]
+        cols += [np.sqrt(coef * wp[t]) * Dn[t] for t in range(len(Dn))]
+        U, _, _ = np.linalg.svd(np.concatenate(cols, axis=1), full_matrices=False)
+        Y = U[:, :m]
+        v = np.array([np.sum((Y.T @ Gn[i]) ** 2) for i in range(P)])
+        u = np.array([np.sum((Y.T @ d) ** 2) for d in Dn])
+        rho = np.maximum(1.0 - v, 0.0)
+        rho_p = np.maximum(1.0 - u, 0.0)
+        obj = float(np.sum((rho ** (1.0 / a))[live]) + coef * np.sum(rho_p ** (1.0 / a)))
+        objective.append(obj)
+        if k > 0 and abs(objective[-2] - obj) < tol:
+            break
+        w = np.where(live, np.maximum(rho, delta) ** (1.0 / a - 1.0), 0.0)
+        wp = np.maximum(rho_p, delta) ** (1.0 / a - 1.0)
+
+    gbar = sum(b.mean(axis=1) for b in blocks)
+    out = Y @ (Y.T @ gbar) / P
+    return {"out": out, "Y": Y, "v": np.where(live, v, 0.0), "w": w, "objective": objective,
+            "iters_done": len(objective), "s": s}

@@ -8,8 +8,8 @@ import math
 import numpy as np
 import pytest
 
-from oracle import (as_f64_matrix, basis_products, decode_bf16, fa_literal, fa_scaled,
-                    projector_difference, tsqr_r)
+from oracle import (as_f64_matrix, basis_products, decode_bf16, fa_literal, fa_literal_grouped,
+                    fa_scaled, projector_difference, tsqr_r)
 
 
 def _rand(n, p, seed, col_scales=True):
@@ -412,6 +412,96 @@ def test_projector_difference_matches_dense():
     B2[0] += 0.5
     B2[5] -= 0.5                      # same G2 @ B, different representation
     assert projector_difference(B1, B2, R2) < 1e-12
+
+
+# ---- workers that send several gradients (blocks of columns) ------------------------------------
+def _grouped_objective(Y, G, sizes, lam):
+    """Eq. 5 with blocks, written out independently: values tr(g^T Y Y^T g) / tr(g^T g),
+    pair terms only between blocks of equal width, factor lam / (P - 1), ordered pairs."""
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    B = [G[:, off[i]:off[i + 1]] for i in range(len(sizes))]
+    tot = 0.0
+    for b in B:
+        tot += math.sqrt(max(1.0 - np.sum((Y.T @ b) ** 2) / np.sum(b * b), 0.0))
+    P = len(B)
+    for i in range(P):
+        for j in range(P):
+            if i != j and sizes[i] == sizes[j]:
+                d = B[i] - B[j]
+                tot += lam / (P - 1) * math.sqrt(max(1.0 - np.sum((Y.T @ d) ** 2) / np.sum(d * d), 0.0))
+    return tot
+
+
+@pytest.mark.parametrize("lam", [0.0, 1.0])
+def test_grouped_with_single_columns_is_the_plain_method(lam):
+    G = _rand(30, 6, 5)
+    a = fa_literal(G, 3, lam, 7, 0.0)
+    b = fa_literal_grouped(G, [1] * 6, 3, lam, 7, 0.0)
+    assert np.allclose(a["out"], b["out"], atol=1e-12)
+    assert np.allclose(a["v"], b["v"], atol=1e-12)
+    assert np.allclose(a["objective"], b["objective"], atol=1e-12)
+
+
+def test_grouped_repeated_gradient_counts_once():
+    """A worker that sends the same gradient k times is the worker that sends it once (no
+    pair terms: they only exist between blocks of equal width)."""
+    G = _rand(40, 5, 8)
+    sizes = [3, 1, 2, 1, 4]
+    Gg = np.concatenate([np.repeat(G[:, i:i + 1], k, axis=1) for i, k in enumerate(sizes)], axis=1)
+    a = fa_literal(G, 2, 0.0, 9, 0.0)
+    b = fa_literal_grouped(Gg, sizes, 2, 0.0, 9, 0.0)
+    assert np.allclose(a["out"], b["out"], atol=1e-11)
+    assert np.allclose(a["v"], b["v"], atol=1e-11)
+    assert np.allclose(a["objective"], b["objective"], atol=1e-11)
+
+
+def test_grouped_value_ignores_a_rotation_within_a_block():
+    rng = np.random.default_rng(2)
+    G = _rand(35, 7, 9)
+    sizes = [3, 2, 2]
+    Q = np.linalg.qr(rng.standard_normal((3, 3)))[0]
+    G2 = G.copy()
+    G2[:, :3] = G[:, :3] @ Q
+    a = fa_literal_grouped(G, sizes, 2, 0.0, 6, 0.0)
+    b = fa_literal_grouped(G2, sizes, 2, 0.0, 6, 0.0)
+    assert np.allclose(a["v"], b["v"], atol=1e-11)
+    assert np.allclose(a["objective"], b["objective"], atol=1e-11)
+    assert np.allclose(a["Y"] @ a["Y"].T, b["Y"] @ b["Y"].T, atol=1e-9)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_grouped_fixed_point_is_stationary(seed):
+    """As for Eq. 5 itself: the fixed point of the block IRLS is a stationary point of the
+    block objective written out above (pins the block normalisation, which pairs exist,
+    and the factor lam / (P - 1))."""
+    rng = np.random.default_rng(seed)
+    n, sizes, m, lam = 20, [3, 3, 4, 3, 3], 2, 1.0    # blocks wider than m: interior point
+    G = rng.standard_normal((n, sum(sizes))) * rng.uniform(0.5, 3, sum(sizes))[None, :]
+    res = fa_literal_grouped(G, sizes, m, lam, 500, 0.0)
+    Y = res["Y"]
+    assert (1 - res["v"]).min() > 1e-3
+    worst = worst_wrong = 0.0
+    h = 1e-5
+    for _ in range(6):
+        D = rng.standard_normal((n, m))
+        D -= Y @ (Y.T @ D)
+        D /= np.linalg.norm(D)
+        dd = (_grouped_objective(_retract(Y, D, h), G, sizes, lam)
+              - _grouped_objective(_retract(Y, D, -h), G, sizes, lam)) / (2 * h)
+        worst = max(worst, abs(dd))
+        dw = (_grouped_objective(_retract(Y, D, h), G, sizes, 3 * lam)
+              - _grouped_objective(_retract(Y, D, -h), G, sizes, 3 * lam)) / (2 * h)
+        worst_wrong = max(worst_wrong, abs(dw))
+    assert worst < 1e-6
+    assert worst_wrong > 1e-3
+
+
+def test_grouped_output_is_the_projected_mean_of_worker_means():
+    G = _rand(25, 6, 4)
+    sizes = [2, 3, 1]
+    res = fa_literal_grouped(G, sizes, 6, 1.0, 3, 0.0)          # m = all columns: Y spans G
+    gbar = (G[:, :2].mean(axis=1) + G[:, 2:5].mean(axis=1) + G[:, 5]) / 3
+    assert np.allclose(res["out"], gbar, atol=1e-10)
 
 
 def test_basis_products_by_brute_force_and_on_a_solution():
