@@ -176,6 +176,23 @@ fa_status fa_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, fl
                    int64_t ldy);
 
 /*
+ * Workers that send several gradients (Sec. 2.1, "different number of gradients from each
+ * worker"; Sec. 2.2, the extension to g_i in R^{n x k}; Appendix D): the q columns of G are
+ * nworkers blocks of consecutive columns, block i of sizes_host[i] >= 1 columns (host memory,
+ * they add up to q).  The value of worker i is tr(g_i^T Y Y^T g_i) / tr(g_i^T g_i); the IRLS
+ * re-weights whole blocks; the pairwise term of Sec. 2.3 exists between blocks of equal width
+ * (Frobenius distance), with the factor lambda / (nworkers - 1); the output counts every worker
+ * once: out = (1/nworkers) Y Y^T sum_i mean_of_columns(g_i).  With every size 1 this is
+ * fa_aggregate.  The other arguments, the layouts and the errors are fa_aggregate's (q takes
+ * the place of p, also in m <= q and q <= p_max); fa_get_info then reports per column (v and w
+ * of a column are its worker's).  Runs on the any-p solver.  Synchronises the stream before
+ * it returns, so sizes_host may be reused at once.
+ */
+fa_status fa_aggregate_grouped(fa_ctx* ctx, const void* G, int64_t ldg, int q, int64_t n,
+                               const int* sizes_host, int nworkers, int m, double lambda,
+                               int iters, double tol, float* out);
+
+/*
  * Streamed check of a materialised basis (Sec. 2.1: Y has orthonormal columns, and the
  * explained variance of worker i is |Y^T g_i|^2 / |g_i|^2).  One pass over Y and G computes, in
  * fp64 on the device,

@@ -22,7 +22,7 @@ _lib: Optional[ctypes.CDLL] = None
 # every symbol include/fa.h declares
 EXPORTED_SYMBOLS = (
     "fa_default_config", "fa_create", "fa_destroy", "fa_set_stream", "fa_aggregate",
-    "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_check_basis",
+    "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_check_basis", "fa_aggregate_grouped",
     "fa_set_profiling",
     "fa_get_timings", "fa_enqueue_kernel", "fa_aggregate_restream", "fa_get_restream_info",
     "fa_status_string", "fa_version",
@@ -76,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     lib.fa_basis.restype = i32
     lib.fa_check_basis.argtypes = [vp, vp, i64, i32, i64, vp, i64, i32, vp, vp]
     lib.fa_check_basis.restype = i32
+    lib.fa_aggregate_grouped.argtypes = [vp, vp, i64, i32, i64, vp, i32, i32, dbl, i32, dbl, vp]
+    lib.fa_aggregate_grouped.restype = i32
     lib.fa_set_profiling.argtypes = [vp, i32]
     lib.fa_set_profiling.restype = i32
     lib.fa_get_timings.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4)]
@@ -187,6 +189,20 @@ class FlagAggregator:
         self._use_current_stream()
         _check(self._lib.fa_aggregate(self._ctx, ptr, ldg, p, n, int(m), float(lam), int(iters),
                                       float(tol), ctypes.c_void_p(out.data_ptr())), "fa_aggregate")
+        return out
+
+    def fa_aggregate_grouped(self, G, sizes, m: int, lam: float, iters: int, tol: float, out=None):
+        """Workers that send several gradients: ``sizes[i]`` consecutive columns of G each."""
+        ptr, ldg, q, n = self._matrix(G)
+        torch = self._torch
+        if out is None:
+            out = torch.empty(n, dtype=torch.float32, device=G.device)
+        sz = (ctypes.c_int * len(sizes))(*[int(k) for k in sizes])
+        self._use_current_stream()
+        _check(self._lib.fa_aggregate_grouped(self._ctx, ptr, ldg, q, n, sz, len(sizes), int(m),
+                                              float(lam), int(iters), float(tol),
+                                              ctypes.c_void_p(out.data_ptr())),
+               "fa_aggregate_grouped")
         return out
 
     def fa_aggregate_restream(self, G, m: int, lam: float, iters: int, out=None):

@@ -30,6 +30,7 @@ struct fa_ctx {
                       // 2 = any-p Jacobi kernel (testing)
   fa_resume* rs_d;    // IRLS state of the re-streaming schedule
   double* Pd;         // streamed projections, FA_P_MAX^2
+  int* sizes_d;       // FA_P_MAX: block widths of fa_aggregate_grouped
   fa_ktime tm[4];     // per-kernel begin/end events (profiling)
   fa_ktime tm_r[2];   // re-streaming schedule: weighted Gram pass and projection pass of the
                       // last iteration
@@ -102,6 +103,7 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   ok = ok && hipMalloc((void**)&c->info_d, sizeof(fa_info)) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->rs_d, sizeof(fa_resume)) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->Pd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->sizes_d, sizeof(int) * FA_P_MAX) == hipSuccess;
   if (!ok) { fa_destroy(c); return FA_ERR_ALLOC; }
   if (hipMemset(c->info_d, 0, sizeof(fa_info)) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
   for (int i = 0; i < 4; ++i)
@@ -125,6 +127,7 @@ extern "C" void fa_destroy(fa_ctx* c) {
   if (c->info_d) (void)hipFree(c->info_d);
   if (c->rs_d) (void)hipFree(c->rs_d);
   if (c->Pd) (void)hipFree(c->Pd);
+  if (c->sizes_d) (void)hipFree(c->sizes_d);
   for (int i = 0; i < 4; ++i) {
     if (c->tm[i].start) (void)hipEventDestroy(c->tm[i].start);
     if (c->tm[i].stop) (void)hipEventDestroy(c->tm[i].stop);
@@ -357,6 +360,46 @@ extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int6
     if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, A + a, m, Y + (int64_t)a * ldy,
                           c->combine_max_blocks, c->stream, nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_aggregate_grouped(fa_ctx* c, const void* G, int64_t ldg, int q, int64_t n,
+                                          const int* sizes_host, int nworkers, int m,
+                                          double lambda, int iters, double tol, float* out) {
+  if (!check_matrix_args(c, G, ldg, q, n) || !out || ((uintptr_t)out & 15u) != 0)
+    return FA_ERR_ARG;
+  if (!check_solver_args(q, m, lambda, iters, tol)) return FA_ERR_ARG;
+  if (!sizes_host || nworkers < 1 || nworkers > q) return FA_ERR_ARG;
+  int tot = 0;
+  for (int i = 0; i < nworkers; ++i) {
+    if (sizes_host[i] < 1 || sizes_host[i] > q) return FA_ERR_ARG;
+    tot += sizes_host[i];
+  }
+  if (tot != q) return FA_ERR_ARG;
+  hipStream_t st = c->stream;
+  c->ev_recorded = 0;
+  if (hipMemcpyAsync(c->sizes_d, sizes_host, sizeof(int) * nworkers, hipMemcpyHostToDevice, st) !=
+      hipSuccess)
+    return FA_ERR_DEVICE;
+  int nparts = 0;
+  if (fa_launch_gram_partials(G, ldg, q, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks,
+                              c->partials, &nparts, nullptr, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_gram_reduce(c->partials, nparts, q, c->Kd, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_irls_grouped(c->Kd, q, nworkers, c->sizes_d, m, lambda, iters, tol,
+                             c->cfg.clamp_delta, c->cfg.rank_tol, c->cfg.pair_tol,
+                             c->cfg.exponent_a, c->cd, c->info_d, c->gws, st) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_combine(G, ldg, q, n, c->cfg.dtype, c->cfg.layout, c->cd, 1, out,
+                        c->combine_max_blocks, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  // the host array may be reused as soon as this returns
+  if (hipStreamSynchronize(st) != hipSuccess) return FA_ERR_DEVICE;
+  c->last_nparts = nparts;
+  c->has_solution = 1;
+  c->last_p = q;
+  c->last_m = m;
   return FA_OK;
 }
 

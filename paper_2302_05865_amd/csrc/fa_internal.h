@@ -50,6 +50,10 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
                           double* cd,
                           fa_info* info_d, double* gws, int solver, fa_resume* rs,
                           hipStream_t st, const fa_ktime* tm);
+hipError_t fa_launch_irls_grouped(const double* Kd, int q, int nworkers, const int* sizes_d, int m,
+                                  double lambda, int iters, double tol, double delta,
+                                  double rank_tol, double pair_tol, double exponent_a, double* cd,
+                                  fa_info* info_d, double* gws, hipStream_t st);
 hipError_t fa_irls_prepare(void);
 // K3 for p <= 16 (latency-tuned single-workgroup solver, static LDS).
 // mlast: 258 doubles; the fast path leaves the last weighted-PCA matrix there (16 x 16, then

@@ -869,6 +869,9 @@ __global__ __launch_bounds__(FA_IRLS_THREADS) void fa_irls_kernel(const double* 
   sm.lam0 = q; q += FA_P_MAX;
   sm.mu = q; q += FA_P_MAX;
   sm.beta = q; q += FA_P_MAX;
+  sm.ginv = q; q += FA_P_MAX;
+  sm.ctop = q; q += FA_P_MAX;
+  sm.cbot = q; q += FA_P_MAX;
   sm.rot_c = q; q += FA_P_MAX / 2;
   sm.rot_s = q; q += FA_P_MAX / 2;
   sm.red = q; q += FA_IRLS_THREADS;
@@ -877,14 +880,16 @@ __global__ __launch_bounds__(FA_IRLS_THREADS) void fa_irls_kernel(const double* 
   sm.rot_q = qi; qi += FA_P_MAX / 2;
   sm.pos = qi; qi += FA_P_MAX;
   sm.order = qi; qi += FA_P_MAX;
+  sm.gfirst = qi; qi += FA_P_MAX;
+  sm.gcnt = qi; qi += FA_P_MAX;
   sm.flag = qi; qi += 8;
   fa_irls_solve(Kg, ar, sm, cg, info, rs);
 }
 
 size_t fa_irls_lds_bytes(int p, int* big_in_global) {
   const size_t msz = (size_t)p * (p | 1) * sizeof(double);
-  const size_t small = (8 * FA_P_MAX + FA_P_MAX + FA_IRLS_THREADS) * sizeof(double) +
-                       (3 * FA_P_MAX + 8) * sizeof(int);
+  const size_t small = (11 * FA_P_MAX + FA_P_MAX + FA_IRLS_THREADS) * sizeof(double) +
+                       (5 * FA_P_MAX + 8) * sizeof(int);
   size_t need = 6 * msz + small;
   *big_in_global = 0;
   if (need > 60 * 1024) {   // keep the common sizes under the default dynamic-LDS limit
@@ -1082,10 +1087,29 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
   ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
   ar.expo = 1.0 / exponent_a;
+  ar.nworkers = 0; ar.sizes = nullptr;
   int big = 0;
   const size_t lds = fa_irls_lds_bytes(p, &big);
   FA_LAUNCH(tm, fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d, gws,
             big, rs, retry_only);
+  return hipGetLastError();
+}
+
+// The same for workers that send several gradients: q columns in nworkers blocks of
+// sizes_d[i] consecutive columns (device memory).  Always the any-p kernel.
+hipError_t fa_launch_irls_grouped(const double* Kd, int q, int nworkers, const int* sizes_d, int m,
+                                  double lambda, int iters, double tol, double delta,
+                                  double rank_tol, double pair_tol, double exponent_a, double* cd,
+                                  fa_info* info_d, double* gws, hipStream_t st) {
+  fa_irls_args ar;
+  ar.p = q; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
+  ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
+  ar.expo = 1.0 / exponent_a;
+  ar.nworkers = nworkers; ar.sizes = sizes_d;
+  int big = 0;
+  const size_t lds = fa_irls_lds_bytes(q, &big);
+  hipLaunchKernelGGL(fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d,
+                     gws, big, (fa_resume*)nullptr, 0);
   return hipGetLastError();
 }
 

@@ -20,12 +20,12 @@
 // one solve per call through the resume state, as the re-streaming schedule drives it.
 static int emulate(const double* K, int p, int m, double lambda, int iters, double tol,
                    double delta, double rank_tol, double pair_tol, double* c, fa_info* info,
-                   int stepwise, double a) {
+                   int stepwise, double a, int nworkers = 0, const int* sizes = 0) {
   if (p < 1 || p > FA_P_MAX || m < 1 || m > p || iters < 1 || iters > FA_ITERS_MAX) return 1;
   const int ld = p | 1;
   const size_t msz = (size_t)p * ld;
-  double* buf = (double*)calloc(6 * msz + 16 * FA_P_MAX + 8, sizeof(double));
-  int* ibuf = (int*)calloc(8 * FA_P_MAX + 16, sizeof(int));
+  double* buf = (double*)calloc(6 * msz + 20 * FA_P_MAX + 8, sizeof(double));
+  int* ibuf = (int*)calloc(10 * FA_P_MAX + 16, sizeof(int));
   if (!buf || !ibuf) return 2;
   fa_irls_mem sm;
   sm.ld = ld;
@@ -35,13 +35,16 @@ static int emulate(const double* K, int p, int m, double lambda, int iters, doub
   sm.s = q; q += FA_P_MAX; sm.dinv = q; q += FA_P_MAX; sm.w = q; q += FA_P_MAX;
   sm.rho = q; q += FA_P_MAX; sm.v = q; q += FA_P_MAX; sm.lam0 = q; q += FA_P_MAX;
   sm.mu = q; q += FA_P_MAX; sm.beta = q; q += FA_P_MAX;
+  sm.ginv = q; q += FA_P_MAX; sm.ctop = q; q += FA_P_MAX; sm.cbot = q; q += FA_P_MAX;
   sm.rot_c = q; q += FA_P_MAX; sm.rot_s = q; q += FA_P_MAX; sm.red = q; q += 8;
   int* qi = ibuf;
   sm.rot_p = qi; qi += FA_P_MAX; sm.rot_q = qi; qi += FA_P_MAX; sm.pos = qi; qi += FA_P_MAX;
-  sm.order = qi; qi += FA_P_MAX; sm.flag = qi; qi += 8;
+  sm.order = qi; qi += FA_P_MAX; sm.gfirst = qi; qi += FA_P_MAX; sm.gcnt = qi; qi += FA_P_MAX;
+  sm.flag = qi; qi += 8;
   fa_irls_args ar;
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol; ar.delta = delta;
   ar.rank_tol = rank_tol; ar.pair_tol = pair_tol; ar.expo = 1.0 / a;
+  ar.nworkers = nworkers; ar.sizes = sizes;
   memset(info, 0, sizeof(*info));
   if (!stepwise) {
     fa_irls_solve(K, ar, sm, c, info, (fa_resume*)0);
@@ -76,4 +79,16 @@ extern "C" int fa_irls_emulate_exponent(const double* K, int p, int m, double la
                                         double tol, double delta, double rank_tol,
                                         double pair_tol, double a, double* c, fa_info* info) {
   return emulate(K, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, c, info, 0, a);
+}
+
+// workers that send several gradients: p columns in nworkers blocks of sizes[i] columns
+extern "C" int fa_irls_emulate_grouped(const double* K, int p, const int* sizes, int nworkers,
+                                       int m, double lambda, int iters, double tol, double delta,
+                                       double rank_tol, double pair_tol, double* c,
+                                       fa_info* info) {
+  int tot = 0;
+  for (int i = 0; i < nworkers; ++i) { if (sizes[i] < 1) return 1; tot += sizes[i]; }
+  if (nworkers < 1 || tot != p) return 1;
+  return emulate(K, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, c, info, 0, 2.0,
+                 nworkers, sizes);
 }

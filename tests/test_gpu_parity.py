@@ -11,7 +11,7 @@ import pytest
 import torch
 
 import synth_inputs as si
-from oracle import (as_f64_matrix, basis_products, fa_literal, fa_scaled,
+from oracle import (as_f64_matrix, basis_products, fa_literal, fa_literal_grouped, fa_scaled,
                     projector_difference)
 from paper_2302_05865_amd import FaError, FlagAggregator
 
@@ -572,3 +572,61 @@ def test_check_basis_of_any_matrix_and_argument_errors(agg_f32):
         agg_f32.fa_check_basis(dev, Yd[:, :-1])
     with pytest.raises(FaError):
         agg_f32.fa_check_basis(dev, torch.zeros((p + 1, n), dtype=torch.float32, device="cuda"))
+
+
+# ---- workers that send several gradients (blocks of columns) -----------------------------------
+@pytest.mark.parametrize("sizes,m,lam,n,dtype", [
+    ([2, 3, 1, 2, 2, 1, 4], 8, 1.0, 30_011, "f32"), ([4] * 8, 9, 1.0, 20_000, "f32"),
+    ([1] * 15, 8, 1.0, 25_003, "f32"), ([3, 2, 3, 2, 3], 4, 0.0, 12_345, "f32"),
+    ([8, 8, 8, 8, 8, 8, 8, 4], 20, 0.5, 9_001, "f32"), ([5, 5, 6], 3, 1.0, 16_384, "bf16"),
+    ([7], 2, 1.0, 1_000, "f32")])
+def test_grouped_workers_match_the_block_oracle(sizes, m, lam, n, dtype):
+    announce("grouped", sizes, m, lam, n, dtype)
+    q = sum(sizes)
+    Gw = si.random_dense(q, n, seed=q + m)
+    Gw[0] += 1.5 * Gw[q - 1]
+    if dtype == "bf16":
+        Gw = (Gw.view(np.uint32) >> 16).astype(np.uint16)      # truncated to bf16 bits
+    iters = 6
+    ref = fa_literal_grouped(as_f64_matrix(Gw), sizes, m, lam, iters, 0.0)
+    agg = FlagAggregator(n_max=n, p_max=q, dtype=dtype)
+    out = agg.fa_aggregate_grouped(to_device(Gw), sizes, m, lam, iters, 0.0).cpu().numpy()
+    info = agg.fa_get_info()
+    assert info.status == 0 and info.iters_done == iters
+    assert rel_l2(out.astype(np.float64), ref["out"]) <= GATE
+    first = np.concatenate([[0], np.cumsum(sizes)[:-1]])
+    assert np.allclose(info.v[first], ref["v"], atol=1e-6)
+    assert np.allclose(info.objective, ref["objective"], atol=1e-6)
+    agg.close()
+
+
+def test_grouped_with_single_columns_is_fa_aggregate_bit_for_bit(agg_f32):
+    announce("grouped = plain at k = 1")
+    w = si.WORKLOADS["cfg2"].with_n(100_003)
+    Gw, _ = si.make_inputs(w, 2)
+    dev = to_device(Gw)
+    import os
+    plain = FlagAggregator(n_max=w.n, p_max=w.p)
+    a = agg_f32.fa_aggregate_grouped(dev, [1] * w.p, w.m, w.lam, 5, 0.0).clone()
+    # the plain entry on the same any-p solver
+    os.environ["FA_IRLS_SOLVER"] = "2"
+    try:
+        gen = FlagAggregator(n_max=w.n, p_max=w.p)
+        b = gen.fa_aggregate(dev, w.m, w.lam, 5, 0.0)
+        assert torch.equal(a, b)
+        gen.close()
+    finally:
+        del os.environ["FA_IRLS_SOLVER"]
+    c = plain.fa_aggregate(dev, w.m, w.lam, 5, 0.0)
+    assert rel_l2(a.cpu().numpy().astype(np.float64), c.cpu().numpy().astype(np.float64)) <= 1e-6
+    plain.close()
+
+
+def test_grouped_argument_errors(agg_f32):
+    announce("grouped argument errors")
+    dev = to_device(si.random_dense(6, 100, seed=1))
+    for sizes in ([2, 2, 1], [2, 2, 3], [6, 0], [], [2, -1, 5]):
+        with pytest.raises(FaError):
+            agg_f32.fa_aggregate_grouped(dev, sizes, 2, 1.0, 3, 0.0)
+    with pytest.raises(FaError):
+        agg_f32.fa_aggregate_grouped(dev, [3, 3], 7, 1.0, 3, 0.0)

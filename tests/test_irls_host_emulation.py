@@ -13,7 +13,8 @@ import numpy as np
 import pytest
 
 import synth_inputs as si
-from oracle import as_f64_matrix, fa_literal, fa_scaled, projector_difference
+from oracle import (as_f64_matrix, fa_literal, fa_literal_grouped, fa_scaled,
+                    projector_difference)
 from paper_2302_05865_amd._ctypes_defs import FaInfo
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -28,12 +29,20 @@ def emul(tmp_path_factory):
     lib = ctypes.CDLL(str(out))
 
     def run(K, m, lam, iters, tol, delta=1e-6, rank_tol=1e-12, pair_tol=1e-12, stepwise=False,
-            a=None):
+            a=None, sizes=None):
         K = np.ascontiguousarray(K, dtype=np.float64)
         p = K.shape[0]
         info = FaInfo()
         c = np.zeros(p)
         d = ctypes.c_double
+        if sizes is not None:
+            sz = (ctypes.c_int * len(sizes))(*sizes)
+            rc = lib.fa_irls_emulate_grouped(
+                K.ctypes.data_as(ctypes.c_void_p), p, sz, len(sizes), m, d(lam), iters, d(tol),
+                d(delta), d(rank_tol), d(pair_tol), c.ctypes.data_as(ctypes.c_void_p),
+                ctypes.byref(info))
+            assert rc == 0
+            return c, info
         if a is not None:
             rc = lib.fa_irls_emulate_exponent(
                 K.ctypes.data_as(ctypes.c_void_p), p, m, d(lam), iters, d(tol), d(delta),
@@ -143,3 +152,35 @@ def test_general_exponent_in_the_solver_text(emul, a):
     c, info = emul(G.T @ G, w.m, w.lam, 12, 0.0, a=a)
     assert np.linalg.norm(G @ c - ref["out"]) <= 1e-8 * np.linalg.norm(ref["out"])
     assert np.allclose(np.array(info.objective[:12]), ref["objective"], atol=1e-6)
+
+
+@pytest.mark.parametrize("sizes,m,lam", [([2, 3, 1, 2, 2, 1], 3, 1.0), ([4, 4, 4], 5, 1.0),
+                                         ([1, 1, 1, 1, 1], 2, 1.0), ([3, 2, 3, 2, 3], 4, 0.0),
+                                         ([7], 2, 1.0)])
+def test_workers_with_several_gradients_in_the_solver_text(emul, sizes, m, lam):
+    """Sec. 2.1 / Sec. 2.2 extension: blocks of columns as workers, value
+    tr(g^T Y Y^T g) / tr(g^T g); the solver text against the block oracle."""
+    rng = np.random.default_rng(sum(sizes))
+    q, n = sum(sizes), 200
+    G = rng.standard_normal((n, q)) * rng.uniform(0.3, 3.0, q)[None, :]
+    G[:, 0] += 2.0 * G[:, -1]
+    ref = fa_literal_grouped(G, sizes, m, lam, 9, 0.0)
+    c, info = emul(G.T @ G, m, lam, 9, 0.0, sizes=sizes)
+    assert info.status == 0 and info.iters_done == 9
+    assert np.linalg.norm(G @ c - ref["out"]) <= 1e-8 * np.linalg.norm(ref["out"])
+    assert np.allclose(np.array(info.objective[:9]), ref["objective"], atol=1e-8)
+    first = np.concatenate([[0], np.cumsum(sizes)[:-1]])
+    assert np.allclose(np.array(info.v[:q])[first], ref["v"], atol=1e-8)
+    # every column of a block reports its worker's value
+    assert np.allclose(np.repeat(np.array(info.v[:q])[first], sizes), np.array(info.v[:q]))
+
+
+def test_a_zero_block_is_a_dropped_worker_in_the_solver_text(emul):
+    rng = np.random.default_rng(3)
+    sizes = [2, 2, 3]
+    G = rng.standard_normal((60, 7))
+    G[:, 2:4] = 0.0
+    ref = fa_literal_grouped(G, sizes, 2, 1.0, 6, 0.0)
+    c, info = emul(G.T @ G, 2, 1.0, 6, 0.0, sizes=sizes)
+    assert np.linalg.norm(G @ c - ref["out"]) <= 1e-8 * np.linalg.norm(ref["out"])
+    assert np.allclose(np.array(info.objective[:6]), ref["objective"], atol=1e-8)
