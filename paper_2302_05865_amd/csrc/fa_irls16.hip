@@ -588,40 +588,46 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
       double tXp = 2.0, tX = hi * sc;      // trace(X_{k-1}) (dummy for k = 0), trace(X_k)
       double pend = tX * (1.0 / 16.0);     // stage-1 partial of |X_{k-1}|_F^2: stage 2 gives tX
       bool sqp = true;                     // with the above, step 0 computes trace(X_0) = tX
-      bool conv = false, near = false;
+      bool conv = false;
       int k_end = MAX_PURIFY;
-      for (int k = 0; k < MAX_PURIFY; ++k) {
-        if (near) {
-          double td = 0.0;
+      // Two loops: the steps run in an inner loop of their own until the iterate is nearly
+      // idempotent, the exact test sits outside it.  (With the test inside one loop, never
+      // taken until the end, every step was a quarter slower: 700 against 534 cycles.)
+      for (int k = 0; k < MAX_PURIFY;) {
+        bool near = false;
+        do {
+          const v4d y = mm16(x, x);
+          const double tYp = fro2_stage2(pend);              // |X_{k-1}|_F^2
+          pend = fro2_stage1(x);
+          tX = sqp ? tYp : fma(2.0, tXp, -tYp);              // trace(X_k)
+          near = (tXp - tYp < 1e-8);
+          const bool sq = tX > (double)mm;
+          if (sq) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) td += isdiag[r] ? x[r] : 0.0;
-          tX = wave_sum(td);
-          if (tX - fro2_stage2(fro2_stage1(x)) < 1e-12) {
-            // idempotent; it is the wanted projector only if its trace is m (the maps are
-            // monotone, so the eigenvalue order is kept whatever the steering did)
-            conv = fabs(tX - (double)mm) < 0.25;
-            k_end = k;
-            break;
+            for (int r = 0; r < 4; ++r) x[r] = y[r];
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) x[r] = fma(2.0, x[r], -y[r]);
           }
-          // not yet: go on from the exact trace
-          tXp = 2.0; sqp = true; pend = tX * (1.0 / 16.0);
-        }
-        const v4d y = mm16(x, x);
-        const double tYp = fro2_stage2(pend);              // |X_{k-1}|_F^2
-        pend = fro2_stage1(x);
-        tX = sqp ? tYp : fma(2.0, tXp, -tYp);              // trace(X_k)
-        near = (tXp - tYp < 1e-8);
-        const bool sq = tX > (double)mm;
-        if (sq) {
+          tXp = tX;
+          sqp = sq;
+          steps = steps + 1;
+          ++k;
+        } while (!near && k < MAX_PURIFY);
+        if (!near) break;
+        double td = 0.0;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) x[r] = y[r];
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) x[r] = fma(2.0, x[r], -y[r]);
+        for (int r = 0; r < 4; ++r) td += isdiag[r] ? x[r] : 0.0;
+        tX = wave_sum(td);
+        if (tX - fro2_stage2(fro2_stage1(x)) < 1e-12) {
+          // idempotent; it is the wanted projector only if its trace is m (the maps are
+          // monotone, so the eigenvalue order is kept whatever the steering did)
+          conv = fabs(tX - (double)mm) < 0.25;
+          k_end = k;
+          break;
         }
-        tXp = tX;
-        sqp = sq;
-        steps = steps + 1;
+        // not yet: go on from the exact trace
+        tXp = 2.0; sqp = true; pend = tX * (1.0 / 16.0);
       }
       if (!conv) return -(1000 + it * 1000 + k_end);
     } else {
