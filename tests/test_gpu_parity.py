@@ -630,3 +630,28 @@ def test_grouped_argument_errors(agg_f32):
             agg_f32.fa_aggregate_grouped(dev, sizes, 2, 1.0, 3, 0.0)
     with pytest.raises(FaError):
         agg_f32.fa_aggregate_grouped(dev, [3, 3], 7, 1.0, 3, 0.0)
+
+
+# ---- seeded sweep over shapes: every p x p path, many (p, m, lambda) ----------------------------
+@pytest.mark.parametrize("seed", range(36))
+def test_random_shapes_all_solvers(agg_f32, seed):
+    rng = np.random.default_rng(1000 + seed)
+    p = int(rng.integers(2, 65))
+    m = int(rng.integers(1, p + 1))
+    lam = float(rng.choice([0.0, 0.3, 1.0, 4.0]))
+    iters = int(rng.integers(1, 9))
+    n = int(rng.integers(p + 1, 6000))
+    announce("random shape", seed, p, m, lam, iters, n)
+    mu = rng.standard_normal(n)
+    Gw = (mu[None, :] * rng.uniform(0.2, 2.0, p)[:, None] +
+          rng.uniform(0.1, 1.5) * rng.standard_normal((p, n))).astype(np.float32)
+    nbyz = int(rng.integers(0, max(1, p // 4) + 1))
+    for b in rng.choice(p, size=nbyz, replace=False):
+        Gw[b] = (-4.0 * mu if rng.random() < 0.5 else 30.0 * rng.standard_normal(n)).astype(np.float32)
+    ref = fa_scaled(Gw, m, lam, iters, 0.0)
+    out = agg_f32.fa_aggregate(to_device(Gw), m, lam, iters, 0.0).cpu().numpy().astype(np.float64)
+    info = agg_f32.fa_get_info()
+    assert info.status == 0 and info.iters_done == iters
+    assert rel_l2(out, ref["out"]) <= GATE
+    assert projector_difference(info.A, ref["A"], ref["R"]) <= GATE
+    assert np.allclose(info.objective, ref["objective"], atol=2e-5)
