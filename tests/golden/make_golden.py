@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__)
 sys.path.insert(0, ROOT)
 
 import synth_inputs as si                      # noqa: E402
-from oracle import fa_literal, as_f64_matrix   # noqa: E402
+from oracle import fa_literal, fa_literal_grouped, as_f64_matrix   # noqa: E402
 
 CASES = [
     # (name, p, n, m, lambda, iters, seed)
@@ -30,6 +30,12 @@ CASES = [
     ("p33", 33, 120, 17, 1.0, 6, 5),
 ]
 
+GROUPED_CASES = [
+    # (name, block widths, n, m, lambda, iters, seed): workers that send several gradients
+    ("grouped_mixed", [2, 3, 1, 2, 2], 60, 4, 1.0, 6, 6),
+    ("grouped_equal", [3, 3, 3, 3], 50, 5, 1.0, 6, 7),
+]
+
 
 def build():
     rec = {}
@@ -37,6 +43,14 @@ def build():
         Gw = si.random_dense(p, n, seed=seed)
         res = fa_literal(as_f64_matrix(Gw), m, lam, iters, 0.0)
         rec[name] = {"p": p, "n": n, "m": m, "lambda": lam, "iters": iters, "seed": seed,
+                     "out": [float(x) for x in res["out"]],
+                     "v": [float(x) for x in res["v"]],
+                     "objective": [float(x) for x in res["objective"]]}
+    for name, sizes, n, m, lam, iters, seed in GROUPED_CASES:
+        Gw = si.random_dense(sum(sizes), n, seed=seed)
+        res = fa_literal_grouped(as_f64_matrix(Gw), sizes, m, lam, iters, 0.0)
+        rec[name] = {"sizes": sizes, "p": sum(sizes), "n": n, "m": m, "lambda": lam,
+                     "iters": iters, "seed": seed,
                      "out": [float(x) for x in res["out"]],
                      "v": [float(x) for x in res["v"]],
                      "objective": [float(x) for x in res["objective"]]}
