@@ -193,6 +193,22 @@ fa_status fa_aggregate_grouped(fa_ctx* ctx, const void* G, int64_t ldg, int q, i
                                int iters, double tol, float* out);
 
 /*
+ * Multi-Krum on the same two passes (the distance-based aggregator the paper compares with:
+ * Sec. 3 "Baselines", Sec. 2.3 on aggregators built on pairwise distances; the rule is the
+ * published one of Blanchard et al., 2017, which the paper cites).  The Gram pass gives
+ * D_ij^2 = K_ii + K_jj - 2 K_ij; worker i is scored by the sum of its p - f - 2 smallest squared
+ * distances to the other workers (f = Byzantine workers provided for, p - f - 2 >= 1); the q
+ * workers with the smallest scores (ties: smaller index; 1 <= q <= p) are averaged by the
+ * aggregate pass: out = (1/q) sum of the selected g_i.  scores_host (p doubles) and
+ * selected_host (p ints, 0/1) are host memory and may be NULL; if either is given the call
+ * synchronises the stream, otherwise it is asynchronous like fa_aggregate.  G, ldg, p, n, out
+ * and the errors as for fa_aggregate.  No basis belongs to this result: fa_basis and
+ * fa_get_info refer to the last fa_aggregate.
+ */
+fa_status fa_multikrum(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, int f, int q,
+                       float* out, double* scores_host, int* selected_host);
+
+/*
  * Streamed check of a materialised basis (Sec. 2.1: Y has orthonormal columns, and the
  * explained variance of worker i is |Y^T g_i|^2 / |g_i|^2).  One pass over Y and G computes, in
  * fp64 on the device,

@@ -313,3 +313,30 @@ def fa_literal_grouped(G: np.ndarray, sizes: List[int], m: int, lam: float, iter
     out = Y @ (Y.T @ gbar) / P
     return {"out": out, "Y": Y, "v": np.where(live, v, 0.0), "w": w, "objective": objective,
             "iters_done": len(objective), "s": s}
+
+
+def multi_krum(G: np.ndarray, f: int, q: int) -> Dict[str, object]:
+    """Multi-Krum, the distance-based aggregator the paper compares with most (Sec. 3
+    "Baselines"; Sec. 2.3 on aggregators "that benefit from pairwise distances"; Appendix E):
+    the paper only cites it, so this restates the published rule (Blanchard et al., 2017) on the
+    columns of ``G`` (n x p).  Worker ``i`` is scored by the sum of its squared distances to its
+    ``p - f - 2`` nearest other workers (``f`` = number of Byzantine workers provided for); the
+    ``q`` workers with the smallest scores are averaged.  Ties (equal scores, equal distances)
+    go to the smaller index.  Returns ``out`` (n), ``scores`` (p), ``selected`` (p, 0/1)."""
+    G = np.asarray(G, dtype=np.float64)
+    n, p = G.shape
+    k = p - f - 2
+    if f < 0 or k < 1 or not (1 <= q <= p):
+        raise ValueError("need f >= 0, p - f - 2 >= 1 and 1 <= q <= p")
+    scores = np.zeros(p)
+    for i in range(p):
+        d = sorted(float(np.sum((G[:, i] - G[:, j]) ** 2)) for j in range(p) if j != i)
+        acc = 0.0
+        for x in d[:k]:                      # ascending order, the order the library adds in
+            acc += x
+        scores[i] = acc
+    order = sorted(range(p), key=lambda i: (scores[i], i))
+    selected = np.zeros(p, dtype=np.int32)
+    selected[order[:q]] = 1
+    out = G[:, selected == 1].sum(axis=1) / q
+    return {"out": out, "scores": scores, "selected": selected}

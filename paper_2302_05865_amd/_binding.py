@@ -22,7 +22,7 @@ _lib: Optional[ctypes.CDLL] = None
 # every symbol include/fa.h declares
 EXPORTED_SYMBOLS = (
     "fa_default_config", "fa_create", "fa_destroy", "fa_set_stream", "fa_aggregate",
-    "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_check_basis", "fa_aggregate_grouped",
+    "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_check_basis", "fa_aggregate_grouped", "fa_multikrum",
     "fa_set_profiling",
     "fa_get_timings", "fa_enqueue_kernel", "fa_aggregate_restream", "fa_get_restream_info",
     "fa_status_string", "fa_version",
@@ -78,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.fa_check_basis.restype = i32
     lib.fa_aggregate_grouped.argtypes = [vp, vp, i64, i32, i64, vp, i32, i32, dbl, i32, dbl, vp]
     lib.fa_aggregate_grouped.restype = i32
+    lib.fa_multikrum.argtypes = [vp, vp, i64, i32, i64, i32, i32, vp, vp, vp]
+    lib.fa_multikrum.restype = i32
     lib.fa_set_profiling.argtypes = [vp, i32]
     lib.fa_set_profiling.restype = i32
     lib.fa_get_timings.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4)]
@@ -204,6 +206,21 @@ class FlagAggregator:
                                               ctypes.c_void_p(out.data_ptr())),
                "fa_aggregate_grouped")
         return out
+
+    def fa_multikrum(self, G, f: int, q: int, out=None):
+        """Multi-Krum: (out, scores, selected) with scores float64[p] and selected int32[p]."""
+        ptr, ldg, p, n = self._matrix(G)
+        torch = self._torch
+        if out is None:
+            out = torch.empty(n, dtype=torch.float32, device=G.device)
+        scores = np.zeros(p, dtype=np.float64)
+        selected = np.zeros(p, dtype=np.int32)
+        self._use_current_stream()
+        _check(self._lib.fa_multikrum(self._ctx, ptr, ldg, p, n, int(f), int(q),
+                                      ctypes.c_void_p(out.data_ptr()),
+                                      scores.ctypes.data_as(ctypes.c_void_p),
+                                      selected.ctypes.data_as(ctypes.c_void_p)), "fa_multikrum")
+        return out, scores, selected
 
     def fa_aggregate_restream(self, G, m: int, lam: float, iters: int, out=None):
         ptr, ldg, p, n = self._matrix(G)

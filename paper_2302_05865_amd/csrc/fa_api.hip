@@ -403,6 +403,39 @@ extern "C" fa_status fa_aggregate_grouped(fa_ctx* c, const void* G, int64_t ldg,
   return FA_OK;
 }
 
+extern "C" fa_status fa_multikrum(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n, int f,
+                                  int q, float* out, double* scores_host, int* selected_host) {
+  if (!check_matrix_args(c, G, ldg, p, n) || !out || ((uintptr_t)out & 15u) != 0)
+    return FA_ERR_ARG;
+  if (f < 0 || p - f - 2 < 1 || q < 1 || q > p) return FA_ERR_ARG;
+  hipStream_t st = c->stream;
+  c->ev_recorded = 0;
+  c->has_solution = 0;                       // no basis belongs to this result
+  int nparts = 0;
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks,
+                              c->partials, &nparts, nullptr, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  // scores in the solvers' workspace, the selection in the block-width buffer
+  if (fa_launch_krum(c->Kd, p, f, q, c->cd, c->gws, c->sizes_d, st) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cd, 1, out,
+                        c->combine_max_blocks, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  c->last_nparts = nparts;
+  if (scores_host || selected_host) {
+    if (scores_host && hipMemcpyAsync(scores_host, c->gws, sizeof(double) * p,
+                                      hipMemcpyDeviceToHost, st) != hipSuccess)
+      return FA_ERR_DEVICE;
+    if (selected_host && hipMemcpyAsync(selected_host, c->sizes_d, sizeof(int) * p,
+                                        hipMemcpyDeviceToHost, st) != hipSuccess)
+      return FA_ERR_DEVICE;
+    if (hipStreamSynchronize(st) != hipSuccess) return FA_ERR_DEVICE;
+  }
+  return FA_OK;
+}
+
 extern "C" fa_status fa_check_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n,
                                     const float* Y, int64_t ldy, int m, double* YtY_host,
                                     double* YtG_host) {

@@ -746,6 +746,53 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
 }
 
 // ------------------------------------------------------------------------------------------
+// Multi-Krum from the Gram matrix (the distance-based aggregator the paper compares with,
+// Sec. 3 "Baselines", Sec. 2.3; rule of Blanchard et al., 2017): D_ij^2 = K_ii + K_jj - 2 K_ij,
+// worker i is scored by the sum of its k = p - f - 2 smallest distances to the others (added
+// in ascending order), the q smallest scores are selected (ties: smaller index), and the
+// coefficients of out = G c are 1/q on the selected workers.  One thread per worker; p <= 64.
+__global__ __launch_bounds__(64) void fa_krum_kernel(const double* __restrict__ K, int p, int k,
+                                                     int q, double* __restrict__ c,
+                                                     double* __restrict__ scores,
+                                                     int* __restrict__ selected) {
+  __shared__ double sc[FA_P_MAX];
+  __shared__ double dist[FA_P_MAX][FA_P_MAX + 1];
+  const int i = threadIdx.x;
+  double s = 0.0;
+  if (i < p) {
+    double* d = dist[i];
+    const double kii = K[i * p + i];
+    int cnt = 0;
+    for (int j = 0; j < p; ++j) {
+      if (j == i) continue;
+      double x = kii + K[j * p + j] - 2.0 * K[i * p + j];
+      x = x > 0.0 ? x : 0.0;
+      int pos = cnt++;                       // insertion sort, ascending
+      while (pos > 0 && d[pos - 1] > x) { d[pos] = d[pos - 1]; --pos; }
+      d[pos] = x;
+    }
+    for (int t = 0; t < k; ++t) s += d[t];
+    sc[i] = s;
+    scores[i] = s;
+  }
+  __syncthreads();
+  if (i < p) {
+    int rank = 0;
+    for (int j = 0; j < p; ++j) rank += (sc[j] < s || (sc[j] == s && j < i)) ? 1 : 0;
+    const int sel = rank < q ? 1 : 0;
+    selected[i] = sel;
+    c[i] = sel ? 1.0 / (double)q : 0.0;
+  }
+}
+
+hipError_t fa_launch_krum(const double* Kd, int p, int f, int q, double* cd, double* scores_d,
+                          int* selected_d, hipStream_t st) {
+  hipLaunchKernelGGL(fa_krum_kernel, dim3(1), dim3(64), 0, st, Kd, p, p - f - 2, q, cd, scores_d,
+                     selected_d);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
 // Streamed check of a materialised basis Y (n x m, fp32, column a at Y + a*ldy): one pass
 // computes W = Y^T [Y | G] in fp64 on the matrix cores: Y^T Y (the identity for the
 // orthonormal basis of Sec. 2.1) and Y^T G (row a, column i: the projection of g_i on y_a,

@@ -12,7 +12,7 @@ import torch
 
 import synth_inputs as si
 from oracle import (as_f64_matrix, basis_products, fa_literal, fa_literal_grouped, fa_scaled,
-                    projector_difference)
+                    multi_krum, projector_difference)
 from paper_2302_05865_amd import FaError, FlagAggregator
 
 from gpu_util import announce, rel_l2, to_device
@@ -655,3 +655,36 @@ def test_random_shapes_all_solvers(agg_f32, seed):
     assert rel_l2(out, ref["out"]) <= GATE
     assert projector_difference(info.A, ref["A"], ref["R"]) <= GATE
     assert np.allclose(info.objective, ref["objective"], atol=2e-5)
+
+
+# ---- Multi-Krum from the same Gram pass -----------------------------------------------------------
+@pytest.mark.parametrize("name,n,f,q,layout", [
+    ("cfg1", 50_000, 1, 6, "worker_major"), ("cfg2", 100_003, 3, 12, "worker_major"),
+    ("cfg2", 100_003, 3, 1, "worker_major"), ("cfg2", 4_099, 3, 12, "row_major"),
+    ("cfg3", 65_537, 3, 12, "worker_major"), ("cfg4", 30_001, 6, 26, "worker_major"),
+    ("cfg5", 20_011, 12, 52, "worker_major"), ("cfg5", 20_011, 0, 64, "worker_major")])
+def test_multi_krum_matches_the_published_rule(name, n, f, q, layout):
+    announce("multi-krum", name, n, f, q, layout)
+    w = si.WORKLOADS[name].with_n(n)
+    Gw, _ = si.make_inputs(w, 0)
+    ref = multi_krum(as_f64_matrix(Gw), f, q)
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, layout=layout)
+    dev = _rows_device(Gw) if layout == "row_major" else to_device(Gw)
+    out, scores, selected = agg.fa_multikrum(dev, f, q)
+    # integer decisions: the same set (the workloads have no near-ties apart from exact
+    # duplicates, which tie exactly on both sides and go to the smaller index)
+    assert np.array_equal(selected, ref["selected"])
+    assert np.allclose(scores, ref["scores"], rtol=1e-10, atol=1e-10 * ref["scores"].max())
+    assert rel_l2(out.cpu().numpy().astype(np.float64), ref["out"]) <= 1e-6
+    agg.close()
+
+
+def test_multi_krum_argument_errors_and_no_basis(agg_f32):
+    announce("multi-krum argument errors")
+    dev = to_device(si.random_dense(6, 100, seed=1))
+    for f, q in ((4, 2), (-1, 2), (1, 0), (1, 7)):
+        with pytest.raises(FaError):
+            agg_f32.fa_multikrum(dev, f, q)
+    agg_f32.fa_multikrum(dev, 1, 5)
+    with pytest.raises(FaError):
+        agg_f32.fa_basis(dev, 2)              # no basis belongs to a Multi-Krum result

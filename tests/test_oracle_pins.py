@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 from oracle import (as_f64_matrix, basis_products, decode_bf16, fa_literal, fa_literal_grouped,
-                    fa_scaled, projector_difference, tsqr_r)
+                    fa_scaled, multi_krum, projector_difference, tsqr_r)
 
 
 def _rand(n, p, seed, col_scales=True):
@@ -502,6 +502,42 @@ def test_grouped_output_is_the_projected_mean_of_worker_means():
     res = fa_literal_grouped(G, sizes, 6, 1.0, 3, 0.0)          # m = all columns: Y spans G
     gbar = (G[:, :2].mean(axis=1) + G[:, 2:5].mean(axis=1) + G[:, 5]) / 3
     assert np.allclose(res["out"], gbar, atol=1e-10)
+
+
+# ---- Multi-Krum (the comparison aggregator that shares the Gram matrix) -------------------------
+def test_multi_krum_worked_example_on_a_line():
+    """Five workers on a line at 0, 1, 2, 3 and 10 (one coordinate), f = 1: each is scored by its
+    p - f - 2 = 2 nearest.  Squared distances by hand: worker 0: {1, 4}; 1: {1, 1}; 2: {1, 1};
+    3: {1, 4}; 4 (the outlier): {49, 64}."""
+    G = np.array([[0.0, 1.0, 2.0, 3.0, 10.0]])
+    res = multi_krum(G, 1, 2)
+    assert np.array_equal(res["scores"], [5.0, 2.0, 2.0, 5.0, 113.0])
+    assert np.array_equal(res["selected"], [0, 1, 1, 0, 0])          # the two best; ties by index
+    assert np.allclose(res["out"], [1.5])
+    res = multi_krum(G, 1, 4)                                         # p - f of them: all but the outlier
+    assert np.array_equal(res["selected"], [1, 1, 1, 1, 0]) and np.allclose(res["out"], [1.5])
+    res = multi_krum(G, 1, 3)                                         # tie 0 / 3 goes to the smaller index
+    assert np.array_equal(res["selected"], [1, 1, 1, 0, 0])
+
+
+def test_multi_krum_properties():
+    rng = np.random.default_rng(6)
+    G = rng.standard_normal((30, 9))
+    G[:, 7] = 50.0 * rng.standard_normal(30)          # two far outliers
+    G[:, 2] = -20.0 * G[:, 0]
+    res = multi_krum(G, 2, 7)
+    assert res["selected"][7] == 0 and res["selected"][2] == 0 and res["selected"].sum() == 7
+    keep = [i for i in range(9) if i not in (2, 7)]
+    assert np.allclose(res["out"], G[:, keep].mean(axis=1))
+    # selecting everybody is the mean; a permutation of the workers permutes the scores
+    assert np.allclose(multi_krum(G, 0, 9)["out"], G.mean(axis=1))
+    perm = rng.permutation(9)
+    assert np.allclose(multi_krum(G[:, perm], 2, 7)["scores"], res["scores"][perm])
+    # a rotation of the coordinates changes no distance
+    Q = np.linalg.qr(rng.standard_normal((30, 30)))[0]
+    assert np.allclose(multi_krum(Q @ G, 2, 7)["scores"], res["scores"], rtol=1e-10)
+    with pytest.raises(ValueError):
+        multi_krum(G, 7, 2)
 
 
 def test_basis_products_by_brute_force_and_on_a_solution():
