@@ -593,25 +593,41 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
       // Two loops: the steps run in an inner loop of their own until the iterate is nearly
       // idempotent, the exact test sits outside it.  (With the test inside one loop, never
       // taken until the end, every step was a quarter slower: 700 against 534 cycles.)
+      // One step X_k (xi) -> X_{k+1} (xo); returns "X_{k-1} was nearly idempotent".  The loop
+      // runs two of them per pass, from x into a second set of registers and back, which
+      // spares the copies of a rotated loop and gives the scheduler two steps to interleave
+      // (522 against 593 cycles per step on a stand-alone copy of the loop).
+      auto one_step = [&](const v4d& xi, v4d& xo) __attribute__((always_inline)) -> bool {
+        const v4d y = mm16(xi, xi);
+        const double tYp = fro2_stage2(pend);              // |X_{k-1}|_F^2
+        pend = fro2_stage1(xi);
+        tX = sqp ? tYp : fma(2.0, tXp, -tYp);              // trace(X_k)
+        const bool nr = (tXp - tYp < 1e-8);
+        const bool sq = tX > (double)mm;
+        if (sq) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) xo[r] = y[r];
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) xo[r] = fma(2.0, xi[r], -y[r]);
+        }
+        tXp = tX;
+        sqp = sq;
+        steps = steps + 1;
+        return nr;
+      };
       for (int k = 0; k < MAX_PURIFY;) {
         bool near = false;
         do {
-          const v4d y = mm16(x, x);
-          const double tYp = fro2_stage2(pend);              // |X_{k-1}|_F^2
-          pend = fro2_stage1(x);
-          tX = sqp ? tYp : fma(2.0, tXp, -tYp);              // trace(X_k)
-          near = (tXp - tYp < 1e-8);
-          const bool sq = tX > (double)mm;
-          if (sq) {
+          v4d x2;
+          near = one_step(x, x2);
+          ++k;
+          if (near || k >= MAX_PURIFY) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) x[r] = y[r];
-          } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) x[r] = fma(2.0, x[r], -y[r]);
+            for (int r = 0; r < 4; ++r) x[r] = x2[r];
+            break;
           }
-          tXp = tX;
-          sqp = sq;
-          steps = steps + 1;
+          near = one_step(x2, x);
           ++k;
         } while (!near && k < MAX_PURIFY);
         if (!near) break;
