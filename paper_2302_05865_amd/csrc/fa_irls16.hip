@@ -265,7 +265,7 @@ struct Fmem {
   double Ps[16 * LDF];   // projector
   double Um[16 * LDF];   // orthonormal basis of range(P) (r x mm), as rows: Um[k][a]
   double Am[16 * LDF];   // A (p x m)
-  __attribute__((aligned(16))) double Zs[16 * LDZ];   // (I-P) R by columns
+  __attribute__((aligned(16))) double Zs[16 * LDZ];   // [0..15]: diag(Z^T Z), Z = (I-P) R
   double s[16], dinv[16], r1[16], beta[16], rinv[16];
   int piv[16];
 };
@@ -655,36 +655,32 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     const long long tc = clock64();
     tk_pur += tc - tb;
 #endif
-    // Z = (I - P) R, by columns into LDS
+    // Z = (I - P) R
     v4d qm;
 #pragma unroll
     for (int r = 0; r < 4; ++r) qm[r] = isdiag[r] ? 1.0 - x[r] : -x[r];
     const v4d z = mm16(qm, rb);
+    // Q = Z^T Z straight from the accumulator registers (for A = tile^T the register layout
+    // of Z is both operands): |z_j|^2 = q_jj is the residual of worker j, and the pair
+    // residuals come from |z_i - z_j|^2 = q_ii + q_jj - 2 q_ij, entry (i, j) of Q sitting in
+    // the lane that owns pair (i, j).  (The cancellation is of the same kind as in D_ij^2
+    // itself; pairs closer than pair_tol never get here.)
+    const v4d qz = mm16(z, z);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) fm.Zs[c16 * LDZ + 4 * r + q4] = z[r];
+    for (int r = 0; r < 4; ++r)
+      if (isdiag[r]) fm.Zs[c16] = qz[r];                 // diag(Q), one entry per diagonal lane
     wave_fence();
-    double zj[16];
-    double nr4[4] = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int a = 0; a < 16; ++a) {
-      zj[a] = fm.Zs[c16 * LDZ + a];
-      nr4[a & 3] = fma(zj[a], zj[a], nr4[a & 3]);
-    }
-    rhoj = ((nr4[0] + nr4[1]) + (nr4[2] + nr4[3])) * dj * dj;      // 1 - v_j
+    const double qjj = fm.Zs[c16];
+    rhoj = qjj * dj * dj;                                // 1 - v_j
     // sqrt(rho) = rho * rsqrt(rho) and max(rho, delta)^(-1/2) = min(rsqrt(rho), delta^(-1/2)):
     // one reciprocal square root per residual, no division
     rsj = rsq_nr<2>(rhoj > 1e-300 ? rhoj : 1e-300);
     double part = (q4 == 0 && livej) ? rhoj * rsj : 0.0;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int i = 4 * r + q4;
-      double ac2[2] = {0.0, 0.0};
-#pragma unroll
-      for (int a = 0; a < 16; ++a) {
-        const double df = fm.Zs[i * LDZ + a] - zj[a];
-        ac2[a & 1] = fma(df, df, ac2[a & 1]);
-      }
-      const double rho = (ac2[0] + ac2[1]) * d2inv[r];
+      const double qii = fm.Zs[4 * r + q4];
+      const double dz2 = fma(-2.0, qz[r], qii + qjj);
+      const double rho = (dz2 > 0.0 ? dz2 : 0.0) * d2inv[r];
       const bool lp = d2inv[r] > 0.0;
       const double rs = rsq_nr<2>(rho > 1e-300 ? rho : 1e-300);
       part += lp ? coef * (rho * rs) : 0.0;            // ordered pair (i, j)
