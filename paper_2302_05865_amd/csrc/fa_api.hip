@@ -451,7 +451,12 @@ extern "C" fa_status fa_check_basis(fa_ctx* c, const void* G, int64_t ldg, int p
   if (fa_launch_cross(Y, ldy, m, G, ldg, p, n, c->cfg.dtype, c->cfg.layout, max_parts,
                       c->partials, c->gws, c->stream) != hipSuccess)
     return FA_ERR_DEVICE;
-  std::vector<double> W((size_t)m * ncols);
+  std::vector<double> W;
+  try {
+    W.resize((size_t)m * ncols);
+  } catch (...) {
+    return FA_ERR_ALLOC;    // no exception crosses the C boundary
+  }
   if (hipMemcpyAsync(W.data(), c->gws, W.size() * sizeof(double), hipMemcpyDeviceToHost,
                      c->stream) != hipSuccess)
     return FA_ERR_DEVICE;
