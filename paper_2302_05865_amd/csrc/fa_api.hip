@@ -356,6 +356,12 @@ extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int6
   // column a of Y = G * A[:, a]; A is row-major p x m inside the device-side record
   const double* A = reinterpret_cast<const double*>(reinterpret_cast<const char*>(c->info_d) +
                                                     offsetof(fa_info, A));
+  if (c->cfg.layout == FA_WORKER_MAJOR) {   // G read once per eight columns of Y
+    if (fa_launch_combine_multi(G, ldg, p, n, c->cfg.dtype, A, m, Y, ldy, c->combine_max_blocks,
+                                c->stream) != hipSuccess)
+      return FA_ERR_DEVICE;
+    return FA_OK;
+  }
   for (int a = 0; a < m; ++a)
     if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, A + a, m, Y + (int64_t)a * ldy,
                           c->combine_max_blocks, c->stream, nullptr) != hipSuccess)

@@ -746,6 +746,81 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
 }
 
 // ------------------------------------------------------------------------------------------
+// Y = G A for MB columns of A at once (the basis of Sec. 2.1 materialised: column a of Y is
+// sum_i A[i][a] g_i): the aggregate pass with MB coefficient vectors, so G is read once per MB
+// columns of Y instead of once per column.  A is row-major p x lda in device memory; column a
+// of Y at Y + a*ldy.  Same thread-to-data map and loads as fa_combine_kernel.
+template <typename E, int MB>
+__global__ __launch_bounds__(256) void fa_combine_multi_kernel(
+    const unsigned char* __restrict__ G, int64_t ldg, int p, int64_t n,
+    const double* __restrict__ A, int lda, int ncols, float* __restrict__ Y, int64_t ldy) {
+  constexpr int EPL = E::EPL;
+  constexpr int NL = 4;                     // columns of G in flight per thread
+  __shared__ double cs[(FA_P_MAX + NL) * MB];
+  for (int t = threadIdx.x; t < (FA_P_MAX + NL) * MB; t += 256) {
+    const int i = t / MB, a = t - i * MB;
+    cs[t] = (i < p && a < ncols) ? A[(int64_t)i * lda + a] : 0.0;
+  }
+  __syncthreads();
+  const int64_t ngroups = (n + EPL - 1) / EPL;
+  for (int64_t gbase = (int64_t)blockIdx.x * 256; gbase < ngroups;
+       gbase += (int64_t)gridDim.x * 256) {
+    const int64_t gidx = gbase + threadIdx.x;
+    const int64_t row0 = gidx * EPL;
+    const bool block_full = (gbase + 256) * EPL <= n;   // uniform: no row guards needed
+    if (!block_full && gidx >= ngroups) continue;
+    double acc[MB][EPL];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[a][e] = 0.0;
+    const unsigned char* src = G + row0 * E::SIZE;
+    for (int c0 = 0; c0 < p; c0 += NL) {
+      uint4 v[NL];
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        const int col = c0 + u < p ? c0 + u : p - 1;    // past p: coefficient zero
+        if (block_full) v[u] = load16_stream(src + (int64_t)col * ldg * E::SIZE);
+        else v[u] = load16_guarded<E>(G + (int64_t)col * ldg * E::SIZE, row0, n);
+      }
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        double x[EPL];
+        if constexpr (E::SIZE == 4) {
+          x[0] = (double)__uint_as_float(v[u].x); x[1] = (double)__uint_as_float(v[u].y);
+          x[2] = (double)__uint_as_float(v[u].z); x[3] = (double)__uint_as_float(v[u].w);
+        } else {
+          x[0] = (double)bf16_bits_to_f32(v[u].x & 0xffffu); x[1] = (double)bf16_bits_to_f32(v[u].x >> 16);
+          x[2] = (double)bf16_bits_to_f32(v[u].y & 0xffffu); x[3] = (double)bf16_bits_to_f32(v[u].y >> 16);
+          x[4] = (double)bf16_bits_to_f32(v[u].z & 0xffffu); x[5] = (double)bf16_bits_to_f32(v[u].z >> 16);
+          x[6] = (double)bf16_bits_to_f32(v[u].w & 0xffffu); x[7] = (double)bf16_bits_to_f32(v[u].w >> 16);
+        }
+#pragma unroll
+        for (int a = 0; a < MB; ++a) {
+          const double cc = cs[(c0 + u) * MB + a];
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[a][e] = fma(cc, x[e], acc[a][e]);
+        }
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < MB; ++a) {
+      if (a >= ncols) break;
+      float* dst = Y + (int64_t)a * ldy + row0;
+      if (row0 + EPL <= n) {
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4)
+          store16_through(dst + e, make_float4((float)acc[a][e], (float)acc[a][e + 1],
+                                               (float)acc[a][e + 2], (float)acc[a][e + 3]));
+      } else {
+        for (int e = 0; e < EPL; ++e)
+          if (row0 + e < n) dst[e] = (float)acc[a][e];
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // Multi-Krum from the Gram matrix (the distance-based aggregator the paper compares with,
 // Sec. 3 "Baselines", Sec. 2.3; rule of Blanchard et al., 2017): D_ij^2 = K_ii + K_jj - 2 K_ij,
 // worker i is scored by the sum of its k = p - f - 2 smallest distances to the others (added
@@ -783,6 +858,35 @@ __global__ __launch_bounds__(64) void fa_krum_kernel(const double* __restrict__ 
     selected[i] = sel;
     c[i] = sel ? 1.0 / (double)q : 0.0;
   }
+}
+
+// Y (+ a*ldy, a < m) = G A, A row-major p x m in device memory; worker-major G only.
+hipError_t fa_launch_combine_multi(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                                   const double* A, int m, float* Y, int64_t ldy, int max_blocks,
+                                   hipStream_t st) {
+  constexpr int MB = 8;
+  const int epl = dtype == FA_F32 ? 4 : 8;
+  const int64_t ngroups = (n + epl - 1) / epl;
+  int64_t blocks = (ngroups + 255) / 256;
+  if (blocks > max_blocks) blocks = max_blocks;
+  for (int a0 = 0; a0 < m; a0 += MB) {
+    const int nc = m - a0 < MB ? m - a0 : MB;
+    if (dtype == FA_F32)
+      hipLaunchKernelGGL((fa_combine_multi_kernel<ElemF32, MB>), dim3((unsigned)blocks), dim3(256),
+                         0, st, (const unsigned char*)G, ldg, p, n, A + a0, m, nc,
+                         Y + (int64_t)a0 * ldy, ldy);
+    else
+      hipLaunchKernelGGL((fa_combine_multi_kernel<ElemBF16, 4>), dim3((unsigned)blocks), dim3(256),
+                         0, st, (const unsigned char*)G, ldg, p, n, A + a0, m, nc < 4 ? nc : 4,
+                         Y + (int64_t)a0 * ldy, ldy);
+    if (dtype != FA_F32 && nc > 4)
+      hipLaunchKernelGGL((fa_combine_multi_kernel<ElemBF16, 4>), dim3((unsigned)blocks), dim3(256),
+                         0, st, (const unsigned char*)G, ldg, p, n, A + a0 + 4, m, nc - 4,
+                         Y + (int64_t)(a0 + 4) * ldy, ldy);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t fa_launch_krum(const double* Kd, int p, int f, int q, double* cd, double* scores_d,
