@@ -40,6 +40,9 @@ typedef double v4f64 __attribute__((ext_vector_type(4)));
 #ifndef FA_GRAM_W4
 #define FA_GRAM_W4 8
 #endif
+#ifndef FA_GRAM_CPL4
+#define FA_GRAM_CPL4 4
+#endif
 
 // ------------------------------------------------------------------------------------------
 // storage element types: 16 bytes per lane per load
@@ -1099,7 +1102,7 @@ static hipError_t launch_gram_e(const void* G, int64_t ldg, int p, int64_t n, in
     case 1: return launch_gram_t<1, FA_GRAM_CPL1, E, FA_GRAM_W1, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
     case 2: return launch_gram_t<2, FA_GRAM_CPL2, E, FA_GRAM_W2, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
     case 3: return launch_gram_t<3, 4, E, 8, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
-    case 4: return launch_gram_t<4, 4, E, FA_GRAM_W4, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+    case 4: return launch_gram_t<4, FA_GRAM_CPL4, E, FA_GRAM_W4, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
   }
   return hipErrorInvalidValue;
 }
