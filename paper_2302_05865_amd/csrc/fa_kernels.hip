@@ -40,6 +40,9 @@ typedef double v4f64 __attribute__((ext_vector_type(4)));
 #ifndef FA_GRAM_W4
 #define FA_GRAM_W4 8
 #endif
+// 48 < p <= 64 (measured at p = 64, n = 50M: 4 columns per load x 8 waves 4.4 ms; 8 columns per
+// load, i.e. tiles of 32 rows, x 12 waves 4.7 ms, x 16 waves 8.5 ms - the accumulators of ten
+// tile pairs do not fit 128 registers; the matrix pipe is 77 % busy at the default)
 #ifndef FA_GRAM_CPL4
 #define FA_GRAM_CPL4 4
 #endif
