@@ -53,6 +53,15 @@ typedef enum { FA_F32 = 0, FA_BF16 = 1 } fa_dtype; /* storage type of G */
  * entry points accept it except fa_aggregate_restream. */
 typedef enum { FA_WORKER_MAJOR = 0, FA_ROW_MAJOR = 1 } fa_layout;
 
+/* Which kernel solves the p x p weighted-PCA problems of the IRLS (Alg. 1, step "IRLS").  All
+ * compute the same iteration; they differ in how the m leading eigenvectors are found.
+ * FA_SOLVER_AUTO: projector by matrix-core purification, no eigen-decomposition; a solve it
+ *   cannot finish (eigenvalues m and m+1 tied) is redone by a Jacobi solver.
+ * FA_SOLVER_JACOBI16: the p <= 16 Jacobi eigensolver (p > 16: as FA_SOLVER_AUTO).
+ * FA_SOLVER_JACOBI: the any-p Jacobi eigensolver (always used for exponent_a != 2 and for
+ *   fa_aggregate_grouped). */
+typedef enum { FA_SOLVER_AUTO = 0, FA_SOLVER_JACOBI16 = 1, FA_SOLVER_JACOBI = 2 } fa_solver;
+
 typedef struct {
   int64_t n_max;      /* largest n this context will see (sizes the workspace) */
   int p_max;          /* largest p, 1..FA_P_MAX */
@@ -68,6 +77,12 @@ typedef struct {
                          Aggregator's square roots (Eq. 5).  Other values run on the any-p
                          Jacobi kernel (slower p x p part, same passes over G). */
   int layout;         /* fa_layout of every G this context sees; default FA_WORKER_MAJOR */
+  int solver;         /* fa_solver: which p x p solver runs the IRLS; default FA_SOLVER_AUTO */
+  int wide_spin_budget; /* 16 < p <= 64 matrix-core solver: how many times a wavefront may poll
+                         for a purification step's steering word before it gives up and the
+                         Jacobi solver redoes the solve.  Default 1 << 22 (never reached in
+                         practice); 0 = give up without polling, which makes every such solve
+                         take the stand-by route (for testing it).  >= 0. */
 } fa_config;
 
 /* What the last fa_aggregate / fa_irls call on the context found (all fp64). */
@@ -89,13 +104,14 @@ typedef struct {
 } fa_info;
 
 /* Fill *cfg with the defaults (n_max = 0, p_max = FA_P_MAX, FA_F32, NULL stream,
- * delta 1e-6, rank_tol 1e-12, pair_tol 1e-12, exponent_a 2). */
+ * delta 1e-6, rank_tol 1e-12, pair_tol 1e-12, exponent_a 2, worker-major, FA_SOLVER_AUTO,
+ * wide_spin_budget 1 << 22). */
 void fa_default_config(fa_config* cfg);
 
 /* Allocate a context on the current HIP device: the per-block Gram partials
  * (sized from n_max, p_max) and the small p x p workspace.  Returns FA_ERR_ARG for
- * n_max < 1, p_max outside 1..FA_P_MAX, an unknown dtype, or tolerances / exponent out of
- * range. */
+ * n_max < 1, p_max outside 1..FA_P_MAX, an unknown dtype, layout or solver, a negative
+ * wide_spin_budget, or tolerances / exponent out of range. */
 fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx);
 
 /* Free everything the context owns (synchronises its stream first).  NULL is ignored. */
@@ -164,7 +180,12 @@ fa_status fa_get_info(fa_ctx* ctx, fa_info* host_out);
  * fa_combine: out = sum_i c[i] g_i with c (p doubles) given in host memory.  Streams G
  *   once.  Asynchronous.
  * fa_basis: Y = G A for the A of the last solve (Sec. 2.1's basis, materialised once):
- *   Y is device memory, m columns of n floats, column a at Y + a*ldy, ldy >= n.
+ *   Y is device memory, m columns of n floats, column a at Y + a*ldy, ldy >= n.  m is the
+ *   number of columns Y has room for and must equal the m of the last fa_aggregate /
+ *   fa_aggregate_restream / fa_aggregate_grouped / fa_irls on the context, p its p
+ *   (FA_ERR_ARG otherwise, nothing is written).  Asynchronous; the device-side status of that
+ *   solve is not consulted: after a solve that fa_get_info reports as failed (non-finite or
+ *   all-zero input) A is zero and so is Y.
  */
 fa_status fa_gram(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, double* K_host);
 fa_status fa_gram_async(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n);
@@ -172,12 +193,12 @@ fa_status fa_irls(fa_ctx* ctx, const double* K_host, int p, int m, double lambda
                   double tol);
 fa_status fa_combine(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n,
                      const double* c_host, float* out);
-fa_status fa_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, float* Y,
+fa_status fa_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, int m, float* Y,
                    int64_t ldy);
 
 /*
- * Workers that send several gradients (Sec. 2.1, "different number of gradients from each
- * worker"; Sec. 2.2, the extension to g_i in R^{n x k}; Appendix D): the q columns of G are
+ * Workers that send several gradients (Sec. 2.1; Sec. 2.2, the extension to g_i in
+ * R^{n x k}; Appendix D): the q columns of G are
  * nworkers blocks of consecutive columns, block i of sizes_host[i] >= 1 columns (host memory,
  * they add up to q).  The value of worker i is tr(g_i^T Y Y^T g_i) / tr(g_i^T g_i); the IRLS
  * re-weights whole blocks; the pairwise term of Sec. 2.3 exists between blocks of equal width
@@ -229,7 +250,9 @@ fa_status fa_check_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t
  * to each of its kernel dispatches (the events carry the kernel's own timestamps; nothing
  * extra is enqueued between the kernels); fa_get_timings synchronises and returns the last
  * call's kernel durations in milliseconds: ms[0] Gram pass, ms[1] partial reduction,
- * ms[2] p x p IRLS, ms[3] aggregate pass.
+ * ms[2] p x p IRLS, ms[3] aggregate pass.  ms[2] covers the first p x p kernel only: when the
+ * matrix-core solver of 16 < p <= 64 gives a solve up, the Jacobi kernel that redoes it (a
+ * separate launch, which otherwise returns at once) is not in it.
  */
 fa_status fa_set_profiling(fa_ctx* ctx, int enabled);
 fa_status fa_get_timings(fa_ctx* ctx, float ms[4]);

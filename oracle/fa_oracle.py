@@ -249,8 +249,8 @@ def fa_literal_grouped(G: np.ndarray, sizes: List[int], m: int, lam: float, iter
                        tol: float, delta: float = DELTA_DEFAULT,
                        tau_pair: float = TAU_PAIR_DEFAULT, a: float = 2.0) -> Dict[str, object]:
     """FA when worker ``i`` sends ``k_i = sizes[i]`` gradients: ``g_i`` is the n x k_i block of
-    consecutive columns of ``G`` (Sec. 2.1, "different number of gradients from each worker";
-    Sec. 2.2, the extension to ``g_i in R^{n x k}``; Appendix D works with such lists).
+    consecutive columns of ``G`` (Sec. 2.1; Sec. 2.2, the extension to ``g_i in R^{n x k}``;
+    Appendix D works with such lists).
 
     The value of worker ``i`` is ``v_i = tr(g_i^T Y Y^T g_i) / tr(g_i^T g_i)``; every other
     step is ``fa_literal``'s with blocks in place of columns.  Readings (the paper does not

@@ -72,7 +72,7 @@ def load_library() -> ctypes.CDLL:
     lib.fa_irls.restype = i32
     lib.fa_combine.argtypes = [vp, vp, i64, i32, i64, vp, vp]
     lib.fa_combine.restype = i32
-    lib.fa_basis.argtypes = [vp, vp, i64, i32, i64, vp, i64]
+    lib.fa_basis.argtypes = [vp, vp, i64, i32, i64, i32, vp, i64]
     lib.fa_basis.restype = i32
     lib.fa_check_basis.argtypes = [vp, vp, i64, i32, i64, vp, i64, i32, vp, vp]
     lib.fa_check_basis.restype = i32
@@ -131,7 +131,8 @@ class FlagAggregator:
 
     def __init__(self, n_max: int, p_max: int = FA_P_MAX, dtype: str = "f32",
                  clamp_delta: float = 1e-6, rank_tol: float = 1e-12, pair_tol: float = 1e-12,
-                 exponent_a: float = 2.0, layout: str = "worker_major"):
+                 exponent_a: float = 2.0, layout: str = "worker_major", solver: str = "auto",
+                 wide_spin_budget: Optional[int] = None):
         import torch  # device memory and streams only
         self._torch = torch
         self._lib = load_library()
@@ -146,6 +147,9 @@ class FlagAggregator:
         cfg.pair_tol = pair_tol
         cfg.exponent_a = exponent_a
         cfg.layout = {"worker_major": 0, "row_major": 1}[layout]
+        cfg.solver = {"auto": 0, "jacobi16": 1, "jacobi": 2}[solver]
+        if wide_spin_budget is not None:
+            cfg.wide_spin_budget = int(wide_spin_budget)
         self.layout = layout
         self.dtype = dtype
         self._ctx = ctypes.c_void_p()
@@ -297,14 +301,15 @@ class FlagAggregator:
         return out
 
     def fa_basis(self, G, m: int):
-        """Y (as a ``[m, n]`` float32 tensor: row a is column a of Y) for the last solve."""
+        """Y (as a ``[m, n]`` float32 tensor: row a is column a of Y) for the last solve, whose
+        ``m`` this must be (the library refuses any other: FA_ERR_ARG)."""
         ptr, ldg, p, n = self._matrix(G)
         torch = self._torch
         ldy = (n + 3) // 4 * 4
         Y = torch.empty((m, ldy), dtype=torch.float32, device=G.device)
         self._use_current_stream()
-        _check(self._lib.fa_basis(self._ctx, ptr, ldg, p, n, ctypes.c_void_p(Y.data_ptr()), ldy),
-               "fa_basis")
+        _check(self._lib.fa_basis(self._ctx, ptr, ldg, p, n, int(m),
+                                  ctypes.c_void_p(Y.data_ptr()), ldy), "fa_basis")
         return Y[:, :n]
 
     def fa_check_basis(self, G, Y):

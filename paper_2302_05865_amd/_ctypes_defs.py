@@ -7,13 +7,15 @@ FA_ITERS_MAX = 256
 FA_OK, FA_ERR_ARG, FA_ERR_ALLOC, FA_ERR_DEVICE, FA_ERR_NONFINITE, FA_ERR_ZERO_INPUT = range(6)
 FA_F32, FA_BF16 = 0, 1
 FA_WORKER_MAJOR, FA_ROW_MAJOR = 0, 1
+FA_SOLVER_AUTO, FA_SOLVER_JACOBI16, FA_SOLVER_JACOBI = 0, 1, 2
 
 
 class FaConfig(ctypes.Structure):
     _fields_ = [("n_max", ctypes.c_int64), ("p_max", ctypes.c_int), ("dtype", ctypes.c_int),
                 ("stream", ctypes.c_void_p), ("clamp_delta", ctypes.c_double),
                 ("rank_tol", ctypes.c_double), ("pair_tol", ctypes.c_double),
-                ("exponent_a", ctypes.c_double), ("layout", ctypes.c_int)]
+                ("exponent_a", ctypes.c_double), ("layout", ctypes.c_int),
+                ("solver", ctypes.c_int), ("wide_spin_budget", ctypes.c_int)]
 
 
 class FaInfo(ctypes.Structure):

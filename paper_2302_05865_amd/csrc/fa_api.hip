@@ -26,8 +26,6 @@ struct fa_ctx {
   int has_solution;   // info_d holds an A from a completed fa_aggregate / fa_irls
   int last_p, last_m;
   int profiling;
-  int solver;         // FA_IRLS_SOLVER in the environment: 0 default, 1 = p<=16 Jacobi path,
-                      // 2 = any-p Jacobi kernel (testing)
   fa_resume* rs_d;    // IRLS state of the re-streaming schedule
   double* Pd;         // streamed projections, FA_P_MAX^2
   int* sizes_d;       // FA_P_MAX: block widths of fa_aggregate_grouped
@@ -52,6 +50,8 @@ extern "C" void fa_default_config(fa_config* cfg) {
   cfg->pair_tol = 1e-12;
   cfg->exponent_a = 2.0;
   cfg->layout = FA_WORKER_MAJOR;
+  cfg->solver = FA_SOLVER_AUTO;
+  cfg->wide_spin_budget = 1 << 22;
 }
 
 extern "C" const char* fa_status_string(fa_status s) {
@@ -74,6 +74,8 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   if (cfg->n_max < 1 || cfg->p_max < 1 || cfg->p_max > FA_P_MAX) return FA_ERR_ARG;
   if (cfg->dtype != FA_F32 && cfg->dtype != FA_BF16) return FA_ERR_ARG;
   if (cfg->layout != FA_WORKER_MAJOR && cfg->layout != FA_ROW_MAJOR) return FA_ERR_ARG;
+  if (cfg->solver < FA_SOLVER_AUTO || cfg->solver > FA_SOLVER_JACOBI) return FA_ERR_ARG;
+  if (cfg->wide_spin_budget < 0) return FA_ERR_ARG;
   if (!(cfg->clamp_delta > 0.0) || !(cfg->rank_tol >= 0.0) || !(cfg->pair_tol >= 0.0) ||
       !(cfg->exponent_a >= 1.0) || !(cfg->exponent_a <= 1e6))
     return FA_ERR_ARG;
@@ -82,10 +84,6 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   memset(c, 0, sizeof(*c));
   c->cfg = *cfg;
   c->stream = (hipStream_t)cfg->stream;
-  {
-    const char* e = getenv("FA_IRLS_SOLVER");
-    c->solver = (e && e[0] >= '0' && e[0] <= '2') ? e[0] - '0' : 0;
-  }
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return FA_ERR_DEVICE; }
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, c->device) != hipSuccess) { delete c; return FA_ERR_DEVICE; }
@@ -112,7 +110,11 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   for (int i = 0; i < 2; ++i)
     if (hipEventCreate(&c->tm_r[i].start) != hipSuccess ||
         hipEventCreate(&c->tm_r[i].stop) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
-  if (fa_irls_prepare() != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
+  // per-function launch attributes (large dynamic LDS) on this context's device
+  if (fa_kernels_prepare() != hipSuccess || fa_irls64_prepare() != hipSuccess) {
+    fa_destroy(c);
+    return FA_ERR_DEVICE;
+  }
   *out_ctx = c;
   return FA_OK;
 }
@@ -145,16 +147,21 @@ extern "C" fa_status fa_set_stream(fa_ctx* c, void* stream) {
   return FA_OK;
 }
 
-static bool check_matrix_args(const fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n) {
-  if (!c || !G) return false;
-  if (p < 1 || p > c->cfg.p_max || n < 1 || n > c->cfg.n_max) return false;
+static bool check_matrix_shape(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                               int layout) {
+  if (!G || p < 1 || n < 1) return false;
   if (((uintptr_t)G & 15u) != 0) return false;
-  if (c->cfg.layout == FA_ROW_MAJOR)   // ldg = row pitch; a tile row must fit the tile width
+  if (layout == FA_ROW_MAJOR)   // ldg = row pitch; a tile row must fit the tile width
     return ldg >= p && ldg <= 16 * ((p + 15) / 16);
   if (ldg < n) return false;
-  const int es = elem_size(c->cfg.dtype);
-  if ((ldg * es) % 16 != 0 && p > 1) return false;
+  if ((ldg * elem_size(dtype)) % 16 != 0 && p > 1) return false;
   return true;
+}
+
+static bool check_matrix_args(const fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n) {
+  if (!c) return false;
+  if (p > c->cfg.p_max || n > c->cfg.n_max) return false;
+  return check_matrix_shape(G, ldg, p, n, c->cfg.dtype, c->cfg.layout);
 }
 
 static bool check_solver_args(int p, int m, double lambda, int iters, double tol) {
@@ -183,7 +190,7 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
     return FA_ERR_DEVICE;
   // S3-S5: p x p IRLS and coefficients
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->solver, nullptr, st,
+                     c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->cfg.solver, c->cfg.wide_spin_budget, nullptr, st,
                      prof ? &c->tm[2] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   // S6: out = G c
@@ -225,7 +232,7 @@ extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg
       return FA_ERR_DEVICE;
     // one weighted PCA with the current weights
     if (fa_launch_irls(c->Kd, p, m, lambda, 1, 0.0, c->cfg.clamp_delta, c->cfg.rank_tol,
-                       c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->solver, c->rs_d, st,
+                       c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->cfg.solver, c->cfg.wide_spin_budget, c->rs_d, st,
                        nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
     // pass 2 over G: projections on the new basis, then the next weights from them
@@ -325,7 +332,7 @@ extern "C" fa_status fa_irls(fa_ctx* c, const double* K_host, int p, int m, doub
   if (hipMemcpy(c->Kd, K_host, sizeof(double) * p * p, hipMemcpyHostToDevice) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                     c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->solver, nullptr, c->stream,
+                     c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->cfg.solver, c->cfg.wide_spin_budget, nullptr, c->stream,
                      nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   c->has_solution = 1;
@@ -347,11 +354,11 @@ extern "C" fa_status fa_combine(fa_ctx* c, const void* G, int64_t ldg, int p, in
   return FA_OK;
 }
 
-extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n, float* Y,
-                              int64_t ldy) {
+extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n, int m,
+                              float* Y, int64_t ldy) {
   if (!check_matrix_args(c, G, ldg, p, n) || !Y || ((uintptr_t)Y & 15u) != 0) return FA_ERR_ARG;
-  if (!c->has_solution || c->last_p != p) return FA_ERR_ARG;
-  const int m = c->last_m;
+  // Y has room for m columns: it must be the m the coefficients in the context were made for
+  if (!c->has_solution || c->last_p != p || c->last_m != m) return FA_ERR_ARG;
   if (ldy < n || ((ldy * 4) % 16 != 0 && m > 1)) return FA_ERR_ARG;
   // column a of Y = G * A[:, a]; A is row-major p x m inside the device-side record
   const double* A = reinterpret_cast<const double*>(reinterpret_cast<const char*>(c->info_d) +
@@ -490,7 +497,7 @@ extern "C" fa_status fa_enqueue_kernel(fa_ctx* c, int which, const void* G, int6
   } else if (which == 2) {
     if (!check_solver_args(p, m, lambda, iters, tol)) return FA_ERR_ARG;
     e = fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
-                       c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->solver, nullptr, c->stream,
+                       c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->cfg.solver, c->cfg.wide_spin_budget, nullptr, c->stream,
                        nullptr);
     c->has_solution = 1; c->last_p = p; c->last_m = m;
   } else {

@@ -43,18 +43,22 @@ hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, doub
 // workspace of FA_GWS_DOUBLES doubles.  solver: 0 = default (matrix-core purification, with
 // the Jacobi solvers as fallback), 1 = p <= 16 Jacobi path, 2 = any-p Jacobi kernel.
 // exponent_a other than 2 always runs on the any-p kernel.
+// spin_budget: see fa_config.wide_spin_budget.
 // rs (device, may be null): continue the IRLS from the weights left there by an earlier
 // launch and leave the next ones (see fa_resume.h).
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double exponent_a,
                           double* cd,
-                          fa_info* info_d, double* gws, int solver, fa_resume* rs,
-                          hipStream_t st, const fa_ktime* tm);
+                          fa_info* info_d, double* gws, int solver, int spin_budget,
+                          fa_resume* rs, hipStream_t st, const fa_ktime* tm);
 hipError_t fa_launch_irls_grouped(const double* Kd, int q, int nworkers, const int* sizes_d, int m,
                                   double lambda, int iters, double tol, double delta,
                                   double rank_tol, double pair_tol, double exponent_a, double* cd,
                                   fa_info* info_d, double* gws, hipStream_t st);
-hipError_t fa_irls_prepare(void);
+// Launch attributes (dynamic LDS above the default limit) of every kernel that needs them, on
+// the current device; called by fa_create.
+hipError_t fa_kernels_prepare(void);
+hipError_t fa_irls64_prepare(void);
 // K3 for p <= 16 (latency-tuned single-workgroup solver, static LDS).
 // mlast: 258 doubles; the fast path leaves the last weighted-PCA matrix there (16 x 16, then
 // rank and m) for fa_launch_gap.  use_purification = 0 forces the Jacobi path.
@@ -67,8 +71,8 @@ hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int i
 // info_d->status = FA_ST_RETRY, in which case the any-p kernel must run next.
 hipError_t fa_launch_irls64(const double* Kd, int p, int m, double lambda, int iters, double tol,
                             double delta, double rank_tol, double pair_tol, double* cd,
-                            fa_info* info_d, double* tiles_ws, double* mlast, fa_resume* rs,
-                            hipStream_t st, const fa_ktime* tm);
+                            fa_info* info_d, double* tiles_ws, double* mlast, int spin_budget,
+                            fa_resume* rs, hipStream_t st, const fa_ktime* tm);
 // eigengap (mu_m - mu_{m+1}) / mu_1 of the N x N matrix left in mlast (then rank, m), into
 // info_d->eigengap.
 hipError_t fa_launch_gap(const double* mlast, int N, fa_info* info_d, hipStream_t st);

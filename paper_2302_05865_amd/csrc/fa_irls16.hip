@@ -52,9 +52,6 @@ struct Smem {
   double red[4];
   int pos[NP], order[NP];
   int done[2], sweeps, status, rank;
-#ifdef FA_K3_TIMING
-  long long t_master, t_tail, t_jacobi;   // shader-clock cycles (diagnostic build)
-#endif
 };
 
 // 1/sqrt(x) from the hardware estimate plus NR Newton steps.
@@ -173,13 +170,7 @@ __device__ __forceinline__ void jacobi16(Smem& sm, double* XA, double* XB, int n
   for (; sweep < MAX_SWEEPS; ++sweep) {
     const int buf = sweep & 1;
     if (wave == 0) {
-#ifdef FA_K3_TIMING
-      const long long t0 = clock64();
-#endif
       const bool fin = master_sweep(sm.M, sm.log[buf], lane);
-#ifdef FA_K3_TIMING
-      if (lane == 0) sm.t_master += clock64() - t0;
-#endif
       if (lane == 0) {
         sm.done[buf] = (fin || sweep + 1 == MAX_SWEEPS) ? 1 : 0;
         sm.sweeps += 1;
@@ -192,9 +183,6 @@ __device__ __forceinline__ void jacobi16(Smem& sm, double* XA, double* XB, int n
     if (sm.done[buf]) break;
   }
   // the last sweep's log; meanwhile the master ranks the eigenvalues
-#ifdef FA_K3_TIMING
-  const long long t1 = clock64();
-#endif
   const int buf = sweep & 1;
   if (wave == 1 && XA) replay_sweep(XA, sm.log[buf], lane);
   if (wave == 2 && XB) replay_sweep(XB, sm.log[buf], lane);
@@ -216,9 +204,6 @@ __device__ __forceinline__ void jacobi16(Smem& sm, double* XA, double* XB, int n
     }
   }
   __syncthreads();
-#ifdef FA_K3_TIMING
-  if (threadIdx.x == 0) sm.t_tail += clock64() - t1;
-#endif
 }
 
 // Deterministic sum over the workgroup (fixed butterfly inside each wave, waves in order).
@@ -399,10 +384,6 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
   const int it0 = rs ? rs->it0 : 0;                    // solves done by earlier launches
   const bool scaled = rs && rs->scaled;
-#ifdef FA_K3_TIMING
-  const long long tk0 = clock64();
-  long long tk_pur = 0, tk_res = 0, tk_mm = 0, tk_setup = 0;
-#endif
 
   // ---- Gram, norms, status ---------------------------------------------------------------
   bool bad = false;
@@ -456,13 +437,7 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   wave_fence();
 
   // ---- R from the pivoted Cholesky factorisation of K~; rank; right inverse --------------
-#ifdef FA_K3_TIMING
-  const long long ts1 = clock64();
-#endif
   const int rank = pivoted_cholesky(fm.Kt, fm.Rt, fm.piv, fm.rinv, rank_tol, 16, lane);
-#ifdef FA_K3_TIMING
-  const long long ts2 = clock64();
-#endif
   // Xi = inverse of the (upper triangular, in pivot order) block U = R~[:, piv]; lane c16
   // solves U x = e_c16 by back substitution, column-oriented: once x_k is known it is taken
   // out of all earlier equations at once (independent multiply-adds, no dependent chain)
@@ -487,9 +462,6 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
       if (lane < 16) fm.Xi[k * LDF + c16] = (c16 < rank) ? bcol[k] : 0.0;
     wave_fence();
   }
-#ifdef FA_K3_TIMING
-  const long long ts3 = clock64();
-#endif
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int i = 4 * r + q4;
@@ -517,9 +489,6 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   }
   wave_fence();
 
-#ifdef FA_K3_TIMING
-  tk_setup = clock64() - tk0;
-#endif
   // ---- IRLS ------------------------------------------------------------------------------
   const int mm = m < rank ? m : rank;
   bool isdiag[4];
@@ -546,9 +515,6 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   v4d x = {0.0, 0.0, 0.0, 0.0}, mk = {0.0, 0.0, 0.0, 0.0};
   int iters_done = 0, steps = 0;
   for (int it = 0; it < iters; ++it) {
-#ifdef FA_K3_TIMING
-    const long long ta = clock64();
-#endif
     // C = diag(w/s) + Laplacian of the pair part;  M = R C R^T via W = C R^T, M = R W
     v4d c;
 #pragma unroll
@@ -558,10 +524,6 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     }
     const v4d wmat = mm16(c, ra);
     mk = mm16(ra, wmat);
-#ifdef FA_K3_TIMING
-    const long long tb = clock64();
-    tk_mm += tb - ta;
-#endif
     if (mm < rank) {
       // scale into [0, 1]: M is PSD, so 0 <= eigenvalues <= trace(M)
       double tr = 0.0;
@@ -651,10 +613,6 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
 #pragma unroll
       for (int r = 0; r < 4; ++r) x[r] = (isdiag[r] && c16 < rank) ? 1.0 : 0.0;
     }
-#ifdef FA_K3_TIMING
-    const long long tc = clock64();
-    tk_pur += tc - tb;
-#endif
     // Z = (I - P) R
     v4d qm;
 #pragma unroll
@@ -688,9 +646,6 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     }
     wave_fence();
     const double obj = wave_sum(part);
-#ifdef FA_K3_TIMING
-    tk_res += clock64() - tc;
-#endif
     if (lane == 0 && it0 + it < FA_ITERS_MAX) info->objective[it0 + it] = obj;
     iters_done = it + 1;
     const bool stop = it0 + it > 0 && fabs(prev_obj - obj) < tol;
@@ -708,13 +663,7 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   }
   wave_fence();
   // P = U U^T with orthonormal U: the rows produced by the pivoted Cholesky of a projector
-#ifdef FA_K3_TIMING
-  const long long te1 = clock64();
-#endif
   const int nb = pivoted_cholesky(fm.Ps, fm.Um, fm.piv, fm.rinv, 1e-6, mm, lane);
-#ifdef FA_K3_TIMING
-  const long long te2 = clock64();
-#endif
   if (nb != mm) return -2;
   v4d ba, ub;   // B as A operand: B[c16][4s+q4];  U_m as B operand: U[a = 4s+q4][k = c16]
 #pragma unroll
@@ -756,17 +705,6 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     info->eigengap = nan("");        // filled in on demand by fa_get_info (needs eigenvalues)
     mlast[256] = (double)rank;
     mlast[257] = (double)m;
-#ifdef FA_K3_TIMING
-    info->objective[FA_ITERS_MAX - 1] = (double)(clock64() - tk0);
-    info->objective[FA_ITERS_MAX - 2] = (double)tk_pur;
-    info->objective[FA_ITERS_MAX - 3] = (double)tk_res;
-    info->objective[FA_ITERS_MAX - 4] = (double)tk_mm;
-    info->objective[FA_ITERS_MAX - 5] = (double)tk_setup;
-    info->objective[FA_ITERS_MAX - 6] = (double)(ts1 - tk0);      // before the first Cholesky
-    info->objective[FA_ITERS_MAX - 7] = (double)(ts2 - ts1);      // Cholesky of the Gram
-    info->objective[FA_ITERS_MAX - 8] = (double)(ts3 - ts2);      // triangular inverse
-    info->objective[FA_ITERS_MAX - 9] = (double)(te2 - te1);      // Cholesky of the projector
-#endif
   }
   // weights for the solve that would come next (only once nothing above can fail any more:
   // the Jacobi path restarts from the state as this launch found it)
@@ -802,9 +740,6 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
       if (tid == 0) fast_done = ok;
     }
     __syncthreads();
-#ifdef FA_K3_TIMING
-    if (tid == 0 && fast_done <= 0) info->objective[250] = (double)fast_done;
-#endif
     if (fast_done > 0) return;
   }
   const int ri = tid >> 4, ci = tid & 15;       // this thread's entry of a 16 x 16 matrix
@@ -812,10 +747,6 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
 
   // ---- setup: norms, status, normalised Gram, pairwise distances ------------------------
   if (tid == 0) { sm.sweeps = 0; sm.status = 0; sm.rank = 0; }
-#ifdef FA_K3_TIMING
-  const long long t_start = clock64();
-  if (tid == 0) { sm.t_master = 0; sm.t_tail = 0; sm.t_jacobi = 0; }
-#endif
   const int it0 = rs ? rs->it0 : 0;
   const bool scaled = rs && rs->scaled;
   if (tid < NP) {
@@ -1024,11 +955,6 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
     double gap = __builtin_inf();
     if (m < r) gap = (sm.mu[sm.order[m - 1]] - sm.mu[sm.order[m]]) / sm.mu[sm.order[0]];
     info->eigengap = gap;
-#ifdef FA_K3_TIMING
-    info->objective[FA_ITERS_MAX - 1] = (double)(clock64() - t_start);
-    info->objective[FA_ITERS_MAX - 2] = (double)sm.t_master;
-    info->objective[FA_ITERS_MAX - 3] = (double)sm.t_tail;
-#endif
   }
 }
 

@@ -142,7 +142,7 @@ struct Small {
   double red[NW];
   int piv[64], used[64];
   int dec[4];   // word of purification step g at [g & 3]: g << 4 | trace ok (4) | converged (2) | square (1)
-  int flag;     // a wavefront gave up waiting for a steering word
+  int flag[2];  // [step parity] a wavefront gave up waiting for that step's steering word
 };
 
 }  // namespace
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
                                                              fa_info* __restrict__ info,
                                                              double* __restrict__ gws,
                                                              double* __restrict__ Ml,
-                                                             fa_resume* rs) {
+                                                             int spin_budget, fa_resume* rs) {
   constexpr int N = 16 * T, TT = T * T, NTP = T * (T + 1) / 2, MSZ = TT * FA_TILE;
   constexpr int EPT = (N * N + NTHREADS - 1) / NTHREADS;   // matrix entries per thread
   extern __shared__ __attribute__((aligned(16))) double lds[];
@@ -170,13 +170,6 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
   double* RtG = gws + 2 * MSZ;      // rows of the Cholesky factor of K~, row-major N x N
   // Ml: last weighted-PCA matrix, row-major N x N, then rank, m (for the eigengap diagnostic)
 
-#ifdef FA_K3_TIMING
-  long long tq[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-  long long tlast = clock64();
-#define FA_TICK(i) do { const long long tn_ = clock64(); tq[i] += tn_ - tlast; tlast = tn_; } while (0)
-#else
-#define FA_TICK(i) do { } while (0)
-#endif
   const int tid = threadIdx.x, lane = tid & 63;
   // in a scalar register: everything decided per wavefront is a scalar branch
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -290,10 +283,8 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     __syncthreads();
     return rank;
   };
-  FA_TICK(0);
   const int rank = pivoted_cholesky(B0, B1, rank_tol, N);
   const int mm = m < rank ? m : rank;
-  FA_TICK(1);
 
   // ---- R = R~ D^1/2 in both operand orders; R 1; Cholesky rows kept for the epilogue --------
 #pragma unroll
@@ -350,7 +341,6 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
   double* nxt = B1;
   int failed = 0;
 
-  FA_TICK(0);
   for (int it = 0; it < iters; ++it) {
     // ---- C: diagonal from the data weights and the row sums of the pair part ---------------
     {
@@ -400,7 +390,6 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
       for (int r = 0; r < 4; ++r) Ml[(16 * fI + 4 * r + q4) * N + 16 * fJ + c16] = mt[r];
     }
     cur = B0; nxt = B1;
-    FA_TICK(2);
     if (mm < rank) {
       // ---- X_0 = M / trace(M) (slightly less: any scale with eigenvalues in [0, 1] will do)
       const double sc = __builtin_amdgcn_rcp(hi) * (1.0 - 1e-7);
@@ -424,13 +413,17 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
       //    |X_{k-1}|_F^2 after a squaring and 2 trace(X_{k-1}) - |X_{k-1}|_F^2 otherwise;
       //  - the multiplying wavefronts pick the word up after their products; everybody else
       //    reads it at the top of the next step, after the barrier.
-      // Waits: the steering wavefront waits for nobody, so the readers' bounded spin ends; one
-      // that gives up (never seen) raises sm.flag, which all read at the top of the next step.
+      // Waits: the steering wavefront waits for nobody, so the readers' bounded spin ends.  One
+      // that runs out of its budget of polls raises the step's flag, skips its store and goes
+      // on to the step's barrier like everybody else; all read that flag right after the
+      // barrier, at the top of the next step, and leave the loop together with the solve marked
+      // as failed (the last step of the loop cannot raise it unseen: MAX_PURIFY is even and a
+      // failed solve is what running out of steps means anyway).
       ++gstep;                        // a tag of its own between solves: no stale word matches
       bool sq_prev = hi * sc > (double)mm, conv = false;
       int wprev = 0;                  // the word of the previous step
       bool reread = wave > NTP;       // ... fetched from LDS by those who did not use it then
-      if (tid == 0) sm.flag = 0;
+      if (tid == 0) { sm.flag[0] = 0; sm.flag[1] = 0; }
       __syncthreads();
       // One step: X_k in cu, X_{k+1} into nx.  Written for fixed buffers (the loop below
       // alternates two instances) so that every LDS address is loop invariant: a wavefront
@@ -439,7 +432,12 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
       // Returns false when the loop is over.
       auto step = [&](double* cu, double* nx, int k) __attribute__((always_inline)) -> bool {
         ++gstep;                      // tags the words: never repeats within a launch
-        const int fl = sm.flag;       // raised before the last barrier, if at all
+        // the previous step's flag: raised before the last barrier, if at all, and written by
+        // nobody in this step (which has the other one), so every wavefront reads the same
+        if (k > 0 && __builtin_amdgcn_readfirstlane(sm.flag[(k - 1) & 1])) {
+          conv = false;
+          return false;
+        }
         if (k > 0) {
           // in place since the last barrier: its publisher waits for nobody
           if (reread) wprev = __builtin_amdgcn_readfirstlane(sm.dec[(gstep - 1) & 3]);
@@ -477,14 +475,14 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
               }
           }
           // this step's word (there already, as a rule)
-          int word = __builtin_amdgcn_readfirstlane(__hip_atomic_load(
-              &sm.dec[gstep & 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-          for (int tries = 0; (word >> 4) != gstep && tries < (1 << 22); ++tries)
+          int word = 0;               // tag 0 is never used
+          for (int tries = 0; (word >> 4) != gstep && tries < spin_budget; ++tries)
             word = __builtin_amdgcn_readfirstlane(__hip_atomic_load(
                 &sm.dec[gstep & 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-          if ((word >> 4) != gstep) { sm.flag = 1; word = 2; reread = true; }
+          const bool gave_up = (word >> 4) != gstep;
+          if (gave_up) { sm.flag[k & 1] = 1; reread = true; }
           wprev = word;
-          if (!(word & 2)) {
+          if (!gave_up && !(word & 2)) {
             v4d xn;
             if (word & 1) {
               xn = y;
@@ -516,7 +514,6 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
                                             __HIP_MEMORY_SCOPE_WORKGROUP);
           wprev = word;
         }
-        if (__builtin_amdgcn_readfirstlane(fl)) return false;   // the same in every wavefront
         steps = steps + 1;
         __syncthreads();
         return true;
@@ -535,7 +532,6 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
       }
       __syncthreads();
     }
-    FA_TICK(3);
     // ---- Z = (I - P) R (nxt): A operand = I - P (symmetric), B operand = R from global -------
     if (wave < TT) {
       v4d acc = {0.0, 0.0, 0.0, 0.0};
@@ -606,7 +602,6 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     const bool stop = it0 + it > 0 && fabs(prev_obj - obj) < tol;
     prev_obj = obj;
     __syncthreads();   // red[] is reused by the next solve
-    FA_TICK(4);
     if (stop) break;
     if (tid < 64) sm.w[tid] = sm.wn[tid];
   }
@@ -724,11 +719,6 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     if (tid < p) rs->w[tid] = sm.w[tid];
     if (tid == 0) { rs->prev_obj = prev_obj; rs->it0 = it0 + iters_done; }
   }
-  FA_TICK(5);
-#ifdef FA_K3_TIMING
-  if (tid == 0)
-    for (int i = 0; i < 9; ++i) info->objective[FA_ITERS_MAX - 1 - i] = (double)tq[i];
-#endif
   if (tid == 0) {
     info->status = 0;
     info->p = p; info->m = m; info->rank = rank;
@@ -741,32 +731,41 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
 }
 
 template <int T>
+static constexpr size_t lds_bytes() {
+  return (size_t)4 * T * T * FA_TILE * sizeof(double) + sizeof(Small);
+}
+
+template <int T>
 static hipError_t launch_t(const double* Kd, int p, int m, double lambda, int iters, double tol,
                            double delta, double rank_tol, double pair_tol, double* cd,
-                           fa_info* info_d, double* tiles_ws, double* mlast, fa_resume* rs,
-                           hipStream_t st, const fa_ktime* tm) {
-  const size_t lds = (size_t)4 * T * T * FA_TILE * sizeof(double) + sizeof(Small);
-  static bool prepared = false;
-  if (!prepared) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<T>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds);   // (the kernel also has a little static LDS)
-    if (e != hipSuccess) return e;
-    prepared = true;
-  }
-  FA_LAUNCH(tm, fa_irls64_kernel<T>, dim3(1), dim3(NTHREADS), lds, st, Kd, p, m, iters, lambda,
-            tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, rs);
+                           fa_info* info_d, double* tiles_ws, double* mlast, int spin_budget,
+                           fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
+  FA_LAUNCH(tm, fa_irls64_kernel<T>, dim3(1), dim3(NTHREADS), lds_bytes<T>(), st, Kd, p, m, iters,
+            lambda, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs);
   return hipGetLastError();
+}
+
+hipError_t fa_irls64_prepare(void) {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<2>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)lds_bytes<2>());
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<3>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<3>());
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<4>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<4>());
+  return e;
 }
 
 hipError_t fa_launch_irls64(const double* Kd, int p, int m, double lambda, int iters, double tol,
                             double delta, double rank_tol, double pair_tol, double* cd,
-                            fa_info* info_d, double* tiles_ws, double* mlast, fa_resume* rs,
-                            hipStream_t st, const fa_ktime* tm) {
+                            fa_info* info_d, double* tiles_ws, double* mlast, int spin_budget,
+                            fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
   switch ((p + 15) / 16) {
-    case 2: return launch_t<2>(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, rs, st, tm);
-    case 3: return launch_t<3>(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, rs, st, tm);
-    case 4: return launch_t<4>(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, rs, st, tm);
+    case 2: return launch_t<2>(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+    case 3: return launch_t<3>(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+    case 4: return launch_t<4>(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
   }
   return hipErrorInvalidValue;
 }

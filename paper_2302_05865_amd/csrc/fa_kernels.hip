@@ -1067,7 +1067,7 @@ size_t fa_irls_lds_bytes(int p, int* big_in_global) {
 }
 
 // ------------------------------------------------------------------------------------------
-// launchers (host).  Shapes are validated by the callers in fa_api.cpp.
+// launchers (host).  Shapes are validated by the callers in fa_api.hip.
 template <int T, int CPL, typename E, int WAVES, bool SCALED, bool ROWS>
 static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
                                 double* partials, int* nparts, const double* colscale,
@@ -1079,14 +1079,6 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
   static_assert(WAVES * tile_bytes <= 160 * 1024, "LDS tiles of one workgroup must fit a CU");
   // more than half of the CU's 160 KiB, so that no second workgroup fits beside this one
   const size_t lds_bytes = WAVES * tile_bytes > 84 * 1024 ? WAVES * tile_bytes : 84 * 1024;
-  static bool prepared = false;
-  if (!prepared) {
-    hipError_t e = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(fa_gram_kernel<T, CPL, E, WAVES, SCALED, ROWS>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    prepared = true;
-  }
   const int64_t ntiles = (n + R - 1) / R;
   int64_t wgs = (ntiles + WAVES - 1) / WAVES;
   if (wgs > max_blocks) wgs = max_blocks;
@@ -1097,17 +1089,35 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
   return hipGetLastError();
 }
 
+// the tiling of each width class: T -> (columns per load, wavefronts per CU)
+#define FA_GRAM_TILINGS(X) \
+  X(1, FA_GRAM_CPL1, FA_GRAM_W1) X(2, FA_GRAM_CPL2, FA_GRAM_W2) X(3, 4, 8) X(4, FA_GRAM_CPL4, FA_GRAM_W4)
+
 template <typename E, bool SCALED, bool ROWS>
 static hipError_t launch_gram_e(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
                                 double* partials, int* nparts, const double* colscale,
                                 hipStream_t st, const fa_ktime* tm) {
   switch ((p + 15) / 16) {
-    case 1: return launch_gram_t<1, FA_GRAM_CPL1, E, FA_GRAM_W1, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
-    case 2: return launch_gram_t<2, FA_GRAM_CPL2, E, FA_GRAM_W2, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
-    case 3: return launch_gram_t<3, 4, E, 8, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
-    case 4: return launch_gram_t<4, FA_GRAM_CPL4, E, FA_GRAM_W4, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm);
+#define FA_X(t, cpl, w)                                                                        \
+    case t: return launch_gram_t<t, cpl, E, w, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, \
+                                                             nparts, colscale, st, tm);
+    FA_GRAM_TILINGS(FA_X)
+#undef FA_X
   }
   return hipErrorInvalidValue;
+}
+
+template <typename E, bool SCALED, bool ROWS>
+static hipError_t prepare_gram_e() {
+  hipError_t e = hipSuccess;
+#define FA_X(t, cpl, w)                                                                          \
+  if (e == hipSuccess)                                                                           \
+    e = hipFuncSetAttribute(                                                                     \
+        reinterpret_cast<const void*>(fa_gram_kernel<t, cpl, E, w, SCALED, ROWS>),               \
+        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  FA_GRAM_TILINGS(FA_X)
+#undef FA_X
+  return e;
 }
 
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
@@ -1180,14 +1190,6 @@ static hipError_t launch_proj_t(const void* G, int64_t ldg, int p, int m, int64_
                                                                         : WAVES * 2048u);
   static_assert(need <= 160 * 1024, "LDS of one workgroup must fit a CU");
   const size_t lds_bytes = need > 84 * 1024 ? need : 84 * 1024;   // one workgroup per CU
-  static bool prepared = false;
-  if (!prepared) {
-    hipError_t e =
-        hipFuncSetAttribute(reinterpret_cast<const void*>(fa_proj_kernel<T, TM, CPL, E, WAVES>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    prepared = true;
-  }
   const int64_t ntiles = (n + R - 1) / R;
   int64_t wgs = (ntiles + WAVES - 1) / WAVES;
   if (wgs > max_blocks) wgs = max_blocks;
@@ -1196,6 +1198,12 @@ static hipError_t launch_proj_t(const void* G, int64_t ldg, int p, int m, int64_
             lds_bytes, st, (const unsigned char*)G, ldg, p, m, n, ntiles, Acoef, partials);
   return hipGetLastError();
 }
+
+// (T, TM) -> (columns per load, wavefronts per CU); the larger tilings run four wavefronts per
+// CU: they need more than 256 registers a lane
+#define FA_PROJ_TILINGS(X)                                                        \
+  X(1, 1, 4, 12) X(2, 1, 4, 8) X(2, 2, 4, 8) X(3, 1, 4, 8) X(3, 2, 4, 8) X(3, 3, 4, 4) \
+  X(4, 1, 8, 8) X(4, 2, 8, 4) X(4, 3, 8, 4) X(4, 4, 8, 4)
 
 template <typename E>
 static hipError_t launch_proj_e(const void* G, int64_t ldg, int p, int m, int64_t n,
@@ -1206,13 +1214,21 @@ static hipError_t launch_proj_e(const void* G, int64_t ldg, int p, int m, int64_
   if (T == t && TM == tmm)                                                                      \
     return launch_proj_t<t, tmm, cpl, E, w>(G, ldg, p, m, n, max_blocks, Acoef, partials, nparts, \
                                             st, tm);
-  FA_PROJ_CASE(1, 1, 4, 12)
-  FA_PROJ_CASE(2, 1, 4, 8) FA_PROJ_CASE(2, 2, 4, 8)
-  // the larger tilings run four wavefronts per CU: they need more than 256 registers a lane
-  FA_PROJ_CASE(3, 1, 4, 8) FA_PROJ_CASE(3, 2, 4, 8) FA_PROJ_CASE(3, 3, 4, 4)
-  FA_PROJ_CASE(4, 1, 8, 8) FA_PROJ_CASE(4, 2, 8, 4) FA_PROJ_CASE(4, 3, 8, 4) FA_PROJ_CASE(4, 4, 8, 4)
+  FA_PROJ_TILINGS(FA_PROJ_CASE)
 #undef FA_PROJ_CASE
   return hipErrorInvalidValue;
+}
+
+template <typename E>
+static hipError_t prepare_proj_e() {
+  hipError_t e = hipSuccess;
+#define FA_PROJ_CASE(t, tmm, cpl, w)                                                            \
+  if (e == hipSuccess)                                                                          \
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_proj_kernel<t, tmm, cpl, E, w>),   \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  FA_PROJ_TILINGS(FA_PROJ_CASE)
+#undef FA_PROJ_CASE
+  return e;
 }
 
 hipError_t fa_launch_proj_partials(const void* G, int64_t ldg, int p, int m, int64_t n, int dtype,
@@ -1235,8 +1251,8 @@ hipError_t fa_launch_restream_weights(const fa_info* info_d, const double* Pd, i
 hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int iters, double tol,
                           double delta, double rank_tol, double pair_tol, double exponent_a,
                           double* cd,
-                          fa_info* info_d, double* gws, int solver, fa_resume* rs,
-                          hipStream_t st, const fa_ktime* tm) {
+                          fa_info* info_d, double* gws, int solver, int spin_budget,
+                          fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
   if (exponent_a != 2.0) solver = 2;   // only the any-p kernel knows other exponents
   if (p <= 16 && solver != 2)
     return fa_launch_irls16(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d,
@@ -1244,8 +1260,8 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
   int retry_only = 0;
   if (p > 16 && solver == 0) {
     hipError_t e = fa_launch_irls64(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd,
-                                    info_d, gws + FA_GWS_GENERIC, gws + FA_GWS_MLAST_OFF, rs, st,
-                                    tm);
+                                    info_d, gws + FA_GWS_GENERIC, gws + FA_GWS_MLAST_OFF,
+                                    spin_budget, rs, st, tm);
     if (e != hipSuccess) return e;
     retry_only = 1;   // the Jacobi kernel below runs only if the one above gave up
     tm = nullptr;
@@ -1324,10 +1340,28 @@ hipError_t fa_launch_gap(const double* mlast, int N, fa_info* info_d, hipStream_
   return hipGetLastError();
 }
 
-hipError_t fa_irls_prepare(void) {
-  // allow the single-workgroup solver its large dynamic LDS (p = 64 needs ~140 KiB)
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls_kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+hipError_t fa_kernels_prepare(void) {
+  // the single-workgroup Jacobi solver's large dynamic LDS (p = 64 needs ~140 KiB)
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  // the streaming kernels that claim a whole compute unit's LDS
+  if (e == hipSuccess) e = prepare_gram_e<ElemF32, false, false>();
+  if (e == hipSuccess) e = prepare_gram_e<ElemF32, true, false>();
+  if (e == hipSuccess) e = prepare_gram_e<ElemF32, false, true>();
+  if (e == hipSuccess) e = prepare_gram_e<ElemBF16, false, false>();
+  if (e == hipSuccess) e = prepare_gram_e<ElemBF16, true, false>();
+  if (e == hipSuccess) e = prepare_gram_e<ElemBF16, false, true>();
+  if (e == hipSuccess) e = prepare_proj_e<ElemF32>();
+  if (e == hipSuccess) e = prepare_proj_e<ElemBF16>();
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemF32>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            FA_P_MAX * 257 * (int)sizeof(float));
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemBF16>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            FA_P_MAX * 257 * (int)sizeof(float));
+  return e;
 }
 
 hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int dtype, int layout,
@@ -1338,18 +1372,6 @@ hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int d
     const size_t lds = (size_t)p * 257 * sizeof(float);
     // ceil(2^32 / ldr): floor(e * magic / 2^32) = e / ldr for every e < 2^16
     const unsigned magic = (unsigned)((0x100000000ull + (unsigned)ldr - 1) / (unsigned)ldr);
-    static bool prepared = false;
-    if (!prepared) {
-      hipError_t e = hipFuncSetAttribute(
-          reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemF32>),
-          hipFuncAttributeMaxDynamicSharedMemorySize, FA_P_MAX * 257 * (int)sizeof(float));
-      if (e == hipSuccess)
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemBF16>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                FA_P_MAX * 257 * (int)sizeof(float));
-      if (e != hipSuccess) return e;
-      prepared = true;
-    }
     int64_t blocks = (n + 255) / 256;
     if (blocks > 256 * 8) blocks = 256 * 8;
     if (dtype == FA_F32)

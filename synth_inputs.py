@@ -187,6 +187,81 @@ def make_inputs(w: Workload, seed: int) -> Tuple[np.ndarray, dict]:
     return out, meta
 
 
+# ---------------------------------------------------------------------------------------------
+# The two widest configurations at their full size: 4.6e9 and 3.3e9 normal deviates.  One
+# sequential stream takes minutes there, so the same recipes are drawn chunk by chunk from
+# independent seeded streams, one per (vector, chunk of rows), on several threads.  The numbers
+# differ from make_inputs' (another stream layout), the distributions, scales and structure do
+# not; the result depends on (workload, seed, chunk_rows) only, not on the thread count.
+CHUNK_ROWS = 1 << 22
+
+_VEC_MU, _VEC_MU2, _VEC_U0, _VEC_COL0 = 0, 1, 2, 16   # stream ids of the vectors of a recipe
+
+
+def _chunk_normal(seed: int, vec: int, chunk: int, rows: int) -> np.ndarray:
+    ss = np.random.SeedSequence([int(seed), int(vec), int(chunk), 0x5EED])
+    return np.random.Generator(np.random.PCG64(ss)).standard_normal(rows)
+
+
+def make_inputs_chunked(w: Workload, seed: int, threads: int = 16,
+                        chunk_rows: int = CHUNK_ROWS) -> Tuple[np.ndarray, dict]:
+    """``(Gw, meta)`` like ``make_inputs`` for the recipes of the two widest configurations
+    (``lowrank_noise``, ``two_cluster``), drawn in parallel (see above)."""
+    from concurrent.futures import ThreadPoolExecutor
+    if w.recipe not in ("lowrank_noise", "two_cluster"):
+        raise ValueError(f"no chunked generator for recipe {w.recipe!r}")
+    p, n, f = w.p, w.n, w.f
+    small = np.random.Generator(np.random.PCG64(np.random.SeedSequence([int(seed), 0xB12])))
+    byz = np.sort(small.choice(p, f, replace=False))
+    z = small.standard_normal((p, 4))            # lowrank_noise: coordinates in span(U)
+    in_first = small.random(p) < 0.7             # two_cluster: which centre a worker follows
+    chunks = [(c, a, min(n, a + chunk_rows)) for c, a in enumerate(range(0, n, chunk_rows))]
+    out = np.empty((p, n), dtype=np.float32 if w.dtype == "f32" else np.uint16)
+
+    def mu_square_sum(ch):
+        c, a, b = ch
+        x = _chunk_normal(seed, _VEC_MU, c, b - a)
+        return float(np.dot(x, x))
+
+    def fill(ch):
+        c, a, b = ch
+        rows = b - a
+        mu = _chunk_normal(seed, _VEC_MU, c, rows)
+        if w.recipe == "lowrank_noise":
+            U = [_chunk_normal(seed, _VEC_U0 + k, c, rows) for k in range(4)]
+        else:
+            mu2 = _chunk_normal(seed, _VEC_MU2, c, rows)
+        nb = 0
+        for i in range(p):
+            if w.recipe == "lowrank_noise":
+                if i in byz:
+                    col = 10.0 * sigma * _chunk_normal(seed, _VEC_COL0 + i, c, rows)
+                else:
+                    col = mu + sigma * _chunk_normal(seed, _VEC_COL0 + i, c, rows)
+                    for k in range(4):
+                        col += z[i, k] * U[k]
+            else:
+                if i in byz:
+                    if nb % 2 == 0:
+                        col = -4.0 * mu
+                    else:
+                        col = 10.0 * sigma * _chunk_normal(seed, _VEC_COL0 + i, c, rows)
+                    nb += 1
+                else:
+                    col = (mu if in_first[i] else mu2) + sigma * _chunk_normal(
+                        seed, _VEC_COL0 + i, c, rows)
+            out[i, a:b] = _store(col, w.dtype)
+        return rows
+
+    with ThreadPoolExecutor(max_workers=max(1, int(threads))) as pool:
+        # sigma = 0.5 rms(mu), added up chunk by chunk in chunk order
+        sigma = 0.5 * float(np.sqrt(sum(pool.map(mu_square_sum, chunks)) / n))
+        done = sum(pool.map(fill, chunks))
+    assert done == n
+    return out, {"seed": seed, "recipe": w.recipe, "byzantine": [int(b) for b in byz],
+                 "generator": "chunked"}
+
+
 def random_dense(p: int, n: int, seed: int, scale: float = 1.0) -> np.ndarray:
     """Plain i.i.d. N(0, scale^2) worker-major fp32 matrix (unit tests of single kernels)."""
     rng = np.random.Generator(np.random.PCG64(seed))

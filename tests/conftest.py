@@ -22,6 +22,11 @@ def _gpu_present() -> bool:
 
 def pytest_collection_modifyitems(config, items):
     if _gpu_present():
+        # the GPU cases name themselves (configuration, seed, shape) as they start, straight to
+        # the terminal: a run that dies in a kernel still says which case it was in
+        sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+        import gpu_util
+        gpu_util.set_reporter(config.pluginmanager.get_plugin("terminalreporter"))
         return
     skip = pytest.mark.skip(reason="no GPU in this container")
     for item in items:

@@ -25,5 +25,20 @@ def rel_l2(a: np.ndarray, b: np.ndarray) -> float:
     return float(np.linalg.norm(a - b)) / (nb if nb > 0 else 1.0)
 
 
+_reporter = None
+
+
+def set_reporter(reporter) -> None:
+    """conftest hands over pytest's terminal reporter, so that progress lines reach the
+    terminal while a long case is still running (captured output only shows up at its end)."""
+    global _reporter
+    _reporter = reporter
+
+
 def announce(*args) -> None:
-    print("[gpu-case]", *args, flush=True)
+    line = "[gpu-case] " + " ".join(str(a) for a in args)
+    if _reporter is not None:
+        _reporter.ensure_newline()
+        _reporter.write_line(line, flush=True)
+    else:
+        print(line, flush=True)

@@ -1,8 +1,10 @@
-"""Parity at the full size of the configuration the bench times (cfg2: p = 15,
-n = 11.2M, fp32, m = 8, lambda = 1, 20 solves), in the bench's launch configuration, and
-cfg3 (n = 25.6M).  The oracle's R-factor form finishes these in seconds.  cfg4 (bf16,
-n = 124M) and cfg5 (n = 50M) run at reduced n in test_gpu_parity.py: generating them
-with the seeded NumPy stream and factoring them in fp64 takes minutes on the host.
+"""Parity at the stated size of every configuration beyond the smallest, in the launch
+configuration the bench times: cfg2 (p = 15, n = 11.2M, fp32; the metric), cfg3 (n = 25.6M),
+cfg4 (p = 32, n = 124M, bf16: 7.9 GB) and cfg5 (p = 64, n = 50M, fp32: 12.8 GB).  The two
+widest are drawn by the chunked parallel generator (the sequential stream takes minutes for
+4e9 deviates); the oracle's R-factor form is chunked and finishes all of them in under a
+minute each.  G of cfg4/cfg5 is larger than 4 GiB, so these are also the cases in which byte
+offsets pass 2^32 and every wavefront makes hundreds of passes.
 """
 import time
 
@@ -10,7 +12,7 @@ import numpy as np
 import pytest
 
 import synth_inputs as si
-from oracle import fa_scaled, projector_difference
+from oracle import decode_bf16, fa_scaled, projector_difference
 from paper_2302_05865_amd import FlagAggregator
 
 from gpu_util import announce, rel_l2, to_device
@@ -18,15 +20,23 @@ from gpu_util import announce, rel_l2, to_device
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["cfg2", "cfg3"])
-def test_full_size(name):
+def _inputs(name):
     w = si.WORKLOADS[name]
+    if name in ("cfg4", "cfg5"):
+        return w, si.make_inputs_chunked(w, 0, threads=16)[0]
+    return w, si.make_inputs(w, 0)[0]
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
+def test_full_size(name):
+    t0 = time.perf_counter()
     announce("full size", name, "generating")
-    Gw, _ = si.make_inputs(w, 0)
-    announce("full size", name, "oracle")
+    w, Gw = _inputs(name)
+    announce("full size", name, f"generated in {time.perf_counter() - t0:.1f} s; oracle")
+    t0 = time.perf_counter()
     ref = fa_scaled(Gw, w.m, w.lam, w.iters, 0.0)
-    announce("full size", name, "gpu")
-    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype="f32")
+    announce("full size", name, f"oracle took {time.perf_counter() - t0:.1f} s; gpu")
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype)
     dev = to_device(Gw)
     out = agg.fa_aggregate(dev, w.m, w.lam, w.iters, 0.0)
     info = agg.fa_get_info()
@@ -36,11 +46,27 @@ def test_full_size(name):
     announce(name, "rel_l2", e_out, "proj", e_proj, "gap", info.eigengap, "sweeps", info.sweeps)
     assert info.status == 0 and info.iters_done == w.iters
     assert e_out <= 1e-4 and e_proj <= 1e-4
-    # sampled outputs recomputed one by one from the definition out[k] = sum_i c_i G[k, i]
+    # the Gram matrix entry by entry against the oracle's R^T R.  Both sides add up n products
+    # per entry in fp64 (relative rounding ~1e-16 sqrt(n) in the worst order); 1e-11 of
+    # sqrt(K_ii K_jj) leaves a decade over that at n = 1.24e8.
+    d = np.sqrt(np.diag(ref["K"]))
+    e_K = np.abs(info.K - ref["K"]) / np.outer(d, d)
+    announce(name, "max Gram error / sqrt(K_ii K_jj)", e_K.max())
+    assert e_K.max() <= 1e-11
+    assert np.allclose(info.v, ref["v"], atol=1e-6)
+    # sampled outputs recomputed one by one from the definition out[k] = sum_i c_i G[k, i]:
+    # random rows, and rows of the last 1 % of n (in the last gradients of cfg4/cfg5 those sit
+    # past the 4 GiB offset), with the very last ones
     rng = np.random.default_rng(0)
-    rows = rng.integers(0, w.n, 1000)
-    direct = Gw[:, rows].astype(np.float64).T @ ref["c"]
+    rows = np.concatenate([rng.integers(0, w.n, 1000),
+                           rng.integers(w.n - w.n // 100, w.n, 1000),
+                           np.arange(w.n - 70, w.n)])
+    sample = Gw[:, rows]
+    if sample.dtype == np.uint16:
+        sample = decode_bf16(sample)
+    direct = sample.astype(np.float64).T @ ref["c"]
     assert np.allclose(got[rows], direct, rtol=0, atol=1e-4 * np.abs(direct).max())
+    del got, out
     # the basis at full size, checked on the device in one streamed pass: orthonormal columns
     # (Y is stored in fp32) and the oracle's explained variances
     Y = agg.fa_basis(dev, w.m)
@@ -48,7 +74,7 @@ def test_full_size(name):
     YtY, YtG = agg.fa_check_basis(dev, Y)
     announce(name, "fa_check_basis seconds", time.perf_counter() - t0)
     assert np.abs(YtY - np.eye(w.m)).max() <= 1e-5
-    s = np.diag(ref["R"].T @ ref["R"])                     # |g_i|^2
+    s = np.diag(ref["K"])                                   # |g_i|^2
     assert np.allclose((YtG ** 2).sum(axis=0) / s, ref["v"], atol=1e-5)
     agg.close()
-    del dev, out, Y
+    del dev, Y

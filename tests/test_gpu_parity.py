@@ -246,6 +246,10 @@ def test_basis_is_orthonormal_and_matches_oracle_subspace(agg_f32):
     Yo = as_f64_matrix(Gw) @ ref["A"]
     cos = np.linalg.svd(Yo.T @ Y, compute_uv=False)
     assert np.all(np.abs(cos - 1) <= 1e-5)
+    # a buffer sized for another m than the last solve's is refused, nothing is written
+    for wrong_m in (w.m - 1, w.m + 1):
+        with pytest.raises(FaError):
+            agg_f32.fa_basis(dev, wrong_m)
 
 
 def test_argument_errors(agg_f32):
@@ -274,14 +278,12 @@ def test_argument_errors(agg_f32):
 
 
 # ------------------------------------------------------------- solver paths of the p x p part
-@pytest.mark.parametrize("solver", ["1", "2"])
-def test_alternative_pxp_solvers_agree_with_the_oracle(monkeypatch, solver):
+@pytest.mark.parametrize("solver", ["jacobi16", "jacobi"])
+def test_alternative_pxp_solvers_agree_with_the_oracle(solver):
     """p <= 16 has three p x p solvers (purification by default, the wave-level Jacobi
-    path, the generic Jacobi kernel); the environment variable read at fa_create picks one."""
+    path, the generic Jacobi kernel); fa_config.solver picks one."""
     announce("solver", solver)
-    monkeypatch.setenv("FA_IRLS_SOLVER", solver)
-    agg = FlagAggregator(n_max=1 << 20, p_max=16, dtype="f32")
-    monkeypatch.delenv("FA_IRLS_SOLVER")
+    agg = FlagAggregator(n_max=1 << 20, p_max=16, dtype="f32", solver=solver)
     _check_aggregate(agg, si.WORKLOADS["cfg2"].with_n(300_007), 5)
     _check_aggregate(agg, si.WORKLOADS["cfg1"].with_n(40_001), 5)
     agg.close()
@@ -414,13 +416,31 @@ def test_wide_problem_with_tied_eigenvalues_uses_the_standby_solver(agg_f32):
     assert rel_l2(out, G @ info.c) <= 1e-6
 
 
-def test_wide_problem_on_the_jacobi_kernel(monkeypatch):
+def test_wide_problem_on_the_jacobi_kernel():
     announce("wide, Jacobi kernel")
-    monkeypatch.setenv("FA_IRLS_SOLVER", "2")
-    agg = FlagAggregator(n_max=1 << 20, p_max=64, dtype="f32")
-    monkeypatch.delenv("FA_IRLS_SOLVER")
+    agg = FlagAggregator(n_max=1 << 20, p_max=64, dtype="f32", solver="jacobi")
     _check_aggregate(agg, si.WORKLOADS["cfg5"].with_n(30_001).with_lam(1.0), 3)
     agg.close()
+
+
+@pytest.mark.parametrize("name,n", [("cfg4", 60_001), ("cfg5", 30_001)])
+def test_wide_solver_gives_up_and_the_jacobi_kernel_redoes_the_solve(name, n):
+    """A spin budget of zero makes the first wait for a steering word of the matrix-core solver
+    (16 < p <= 64) give up; every wavefront then leaves the purification at the same barrier,
+    the kernel hands over, and the Jacobi kernel enqueued behind it must return the oracle's
+    answer.  Every kernel exits normally."""
+    announce("wide solver gives up", name)
+    w = si.WORKLOADS[name].with_n(n)
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, wide_spin_budget=0)
+    info = _check_aggregate(agg, w, 1)
+    ref = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, solver="jacobi")
+    info_j = _check_aggregate(ref, w, 1)
+    # Jacobi sweeps, not purification steps: the stand-by did the work, with the very
+    # arithmetic of a context that asks for the Jacobi kernel outright
+    assert info.sweeps == info_j.sweeps
+    assert np.array_equal(info.c, info_j.c)
+    agg.close()
+    ref.close()
 
 
 def test_wide_problem_nonfinite_and_tol(agg_f32):
@@ -605,18 +625,13 @@ def test_grouped_with_single_columns_is_fa_aggregate_bit_for_bit(agg_f32):
     w = si.WORKLOADS["cfg2"].with_n(100_003)
     Gw, _ = si.make_inputs(w, 2)
     dev = to_device(Gw)
-    import os
     plain = FlagAggregator(n_max=w.n, p_max=w.p)
     a = agg_f32.fa_aggregate_grouped(dev, [1] * w.p, w.m, w.lam, 5, 0.0).clone()
     # the plain entry on the same any-p solver
-    os.environ["FA_IRLS_SOLVER"] = "2"
-    try:
-        gen = FlagAggregator(n_max=w.n, p_max=w.p)
-        b = gen.fa_aggregate(dev, w.m, w.lam, 5, 0.0)
-        assert torch.equal(a, b)
-        gen.close()
-    finally:
-        del os.environ["FA_IRLS_SOLVER"]
+    gen = FlagAggregator(n_max=w.n, p_max=w.p, solver="jacobi")
+    b = gen.fa_aggregate(dev, w.m, w.lam, 5, 0.0)
+    assert torch.equal(a, b)
+    gen.close()
     c = plain.fa_aggregate(dev, w.m, w.lam, 5, 0.0)
     assert rel_l2(a.cpu().numpy().astype(np.float64), c.cpu().numpy().astype(np.float64)) <= 1e-6
     plain.close()

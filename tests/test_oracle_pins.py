@@ -208,23 +208,51 @@ def test_converged_point_is_stationary_for_eq5(seed):
     assert worst_wrong_factor > 1e-3      # the check has power
 
 
-@pytest.mark.parametrize("a", [1.5, 3.0, 6.0])
-@pytest.mark.parametrize("seed", [1, 2])
-def test_general_exponent_fixed_point_is_stationary(seed, a):
-    """Sec. 2.2, Step 2: with the Taylor constant a every term is (1 - v)^(1/a).  The IRLS
-    fixed point must be stationary for that objective (written out independently), and not
-    for the a = 2 objective: pins the weight exponent 1/a - 1."""
+def eq5_floored(Y, G, lam, a, delta):
+    """Eq. 5 with exponent 1/a (Sec. 2.2, Step 2) and every term continued linearly below the
+    floor: phi(rho) = rho^(1/a) for rho >= delta, and its tangent at delta below.  This is the
+    function whose slope is the floored IRLS weight max(rho, delta)^(1/a - 1) / a, so a fixed
+    point of the floored IRLS must be a stationary point of it, vertex or not (Appendix D
+    perturbs the root for the same purpose)."""
+    def phi(rho):
+        rho = max(rho, 0.0)
+        if rho >= delta:
+            return rho ** (1.0 / a)
+        return delta ** (1.0 / a) + (rho - delta) * delta ** (1.0 / a - 1.0) / a
+    n, p = G.shape
+    total = 0.0
+    for i in range(p):
+        g = G[:, i]
+        z = Y.T @ g
+        total += phi(1.0 - float(z @ z) / float(g @ g))
+    if lam > 0:
+        for i in range(p):
+            for j in range(p):
+                if i != j:
+                    d = G[:, i] - G[:, j]
+                    z = Y.T @ d
+                    total += lam / (p - 1) * phi(1.0 - float(z @ z) / float(d @ d))
+    return total
+
+
+@pytest.mark.parametrize("a,seed", [(1.5, 1), (1.5, 2), (3.0, 1), (3.0, 20), (4.0, 20)])
+def test_general_exponent_interior_fixed_point_is_stationary(seed, a):
+    """Sec. 2.2, Step 2: with the Taylor constant a every term is (1 - v)^(1/a).  An IRLS
+    fixed point away from every vertex must be stationary for that objective (written out
+    independently), and not for another exponent's: pins the weight exponent 1/a - 1.
+    (The inputs are the ones of this recipe that converge to an interior point; the floored
+    variant below covers the vertex solutions that large a prefers.)"""
     rng = np.random.default_rng(seed)
     n, p, m, lam = 12, 8, 2, 1.0
     G = rng.standard_normal((n, p)) * rng.uniform(0.5, 3, p)[None, :]
     res = fa_literal(G, m, lam, 1500, 0.0, a=a)
     Y = res["Y"]
     off = ~np.eye(p, dtype=bool)
-    if min((1 - res["v"]).min(), (1 - res["u"][off]).min()) < 1e-3:
-        pytest.skip("converged to a vertex, where the objective is not differentiable")
+    assert min((1 - res["v"]).min(), (1 - res["u"][off]).min()) > 1e-3    # interior
     assert abs(res["objective"][-1] - eq5_objective(Y, G, lam, a=a)) < 1e-7
     worst = worst_other = 0.0
     h = 1e-5
+    other = 2.0 if a != 2.0 else 3.0
     for _ in range(6):
         D = rng.standard_normal((n, m))
         D -= Y @ (Y.T @ D)
@@ -232,11 +260,43 @@ def test_general_exponent_fixed_point_is_stationary(seed, a):
         dd = (eq5_objective(_retract(Y, D, h), G, lam, a=a)
               - eq5_objective(_retract(Y, D, -h), G, lam, a=a)) / (2 * h)
         worst = max(worst, abs(dd))
-        do = (eq5_objective(_retract(Y, D, h), G, lam, a=2.0 if a != 2.0 else 3.0)
-              - eq5_objective(_retract(Y, D, -h), G, lam, a=2.0 if a != 2.0 else 3.0)) / (2 * h)
+        do = (eq5_objective(_retract(Y, D, h), G, lam, a=other)
+              - eq5_objective(_retract(Y, D, -h), G, lam, a=other)) / (2 * h)
         worst_other = max(worst_other, abs(do))
     assert worst < 1e-5
     assert worst_other > 1e-3
+
+
+@pytest.mark.parametrize("a", [1.5, 2.0, 3.0, 4.0, 6.0])
+@pytest.mark.parametrize("seed", [1, 2])
+def test_floored_irls_fixed_point_is_stationary_for_the_floored_objective(seed, a):
+    """The floor makes the IRLS a majorise-minimise scheme for Eq. 5 with every term continued
+    by its tangent below delta (eq5_floored): its fixed points are stationary points of that
+    smooth function also where gradients are explained exactly, which is where the iteration
+    ends up for large a.  Pins, for every exponent used anywhere (2, the GPU tests' 4, and 6):
+    the weight exponent, that the floor acts on the residual, and the ordered-pair factor."""
+    rng = np.random.default_rng(seed)
+    n, p, m, lam, delta = 12, 8, 2, 1.0, 0.05
+    G = rng.standard_normal((n, p)) * rng.uniform(0.5, 3, p)[None, :]
+    res = fa_literal(G, m, lam, 4000, 0.0, delta=delta, a=a)
+    Y = res["Y"]
+    worst = worst_other = worst_floor = 0.0
+    h = 1e-5
+    other = 2.0 if a != 2.0 else 4.0
+    for _ in range(6):
+        D = rng.standard_normal((n, m))
+        D -= Y @ (Y.T @ D)
+        D /= np.linalg.norm(D)
+        Yp, Ym = _retract(Y, D, h), _retract(Y, D, -h)
+        worst = max(worst, abs(eq5_floored(Yp, G, lam, a, delta)
+                               - eq5_floored(Ym, G, lam, a, delta)) / (2 * h))
+        worst_other = max(worst_other, abs(eq5_floored(Yp, G, lam, other, delta)
+                                           - eq5_floored(Ym, G, lam, other, delta)) / (2 * h))
+        worst_floor = max(worst_floor, abs(eq5_floored(Yp, G, lam, a, delta / 50)
+                                           - eq5_floored(Ym, G, lam, a, delta / 50)) / (2 * h))
+    assert worst < 1e-6
+    assert worst_other > 1e-3          # another exponent's objective is not stationary here
+    assert worst_floor > 1e-3 or (1 - res["v"]).min() > delta   # nor is another floor's
 
 
 def test_exponent_one_is_pca_whatever_the_iteration_count():
