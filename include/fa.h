@@ -42,7 +42,9 @@ typedef enum {
   FA_ERR_ALLOC = 2,      /* device/host allocation failed */
   FA_ERR_DEVICE = 3,     /* a HIP call failed */
   FA_ERR_NONFINITE = 4,  /* G holds NaN/Inf (detected on device from G^T G); out is NaN */
-  FA_ERR_ZERO_INPUT = 5  /* every gradient is zero; out is zero */
+  FA_ERR_ZERO_INPUT = 5, /* every gradient is zero; out is zero */
+  FA_ERR_TOO_LARGE = 6   /* fa_aggregate_static: p exceeds FA_STATIC_P_MAX, the size its fixed
+                            device-resident workspace was built for; nothing was enqueued */
 } fa_status;
 
 typedef enum { FA_F32 = 0, FA_BF16 = 1 } fa_dtype; /* storage type of G */
@@ -269,6 +271,32 @@ fa_status fa_get_timings(fa_ctx* ctx, float ms[4]);
  */
 fa_status fa_enqueue_kernel(fa_ctx* ctx, int which, const void* G, int64_t ldg, int p, int64_t n,
                             int m, double lambda, int iters, double tol, float* out);
+
+/*
+ * fa_aggregate for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  No context: the workspace (per-compute-unit partial
+ * Gram matrices, K, the p x p solvers' scratch, the coefficients; FA_STATIC_SCRATCH_BYTES in
+ * all) is a fixed array in the library's device image, one copy on every GPU the library runs
+ * on, held until the process ends.  The call makes no hipMalloc / hipFree and uses no
+ * allocating routine; the first call on a device looks the array's address up and sets kernel
+ * launch attributes (neither allocates).
+ *   G, ldg, p, n, m, lambda, iters, tol, out  as for fa_aggregate (worker-major storage only)
+ *   dtype    fa_dtype of G
+ *   stream   hipStream_t the work is enqueued on (NULL = the default stream), borrowed
+ * Tolerances, exponent and solver are the defaults of fa_default_config.  Runs on the current
+ * device; asynchronous.  Results are those of fa_aggregate, bit for bit, on a GPU of at most
+ * 256 compute units.  Data errors show in out only (NaN for non-finite input, zeros for
+ * all-zero input): there is no record to query.
+ * Limits: p <= FA_STATIC_P_MAX, else FA_ERR_TOO_LARGE (n is not limited: nothing in the
+ * workspace grows with n).  Other bad arguments: FA_ERR_ARG.  Nothing is enqueued on error.
+ * Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race and must be serialised by the caller; calls on different GPUs
+ * are independent.
+ */
+#define FA_STATIC_P_MAX 64
+#define FA_STATIC_SCRATCH_BYTES (6u << 20)
+fa_status fa_aggregate_static(const void* G, int64_t ldg, int p, int64_t n, int dtype, int m,
+                              double lambda, int iters, double tol, float* out, void* stream);
 
 const char* fa_status_string(fa_status s);
 const char* fa_version(void);

@@ -3,8 +3,8 @@
 every step of the path runs in the library's kernels.  PyTorch is used by callers for device
 memory and streams; this package only needs raw device addresses.
 """
-from ._binding import (FlagAggregator, FaError, FaInfoResult, library_path,
+from ._binding import (FlagAggregator, FaError, FaInfoResult, fa_aggregate_static, library_path,
                        load_library, EXPORTED_SYMBOLS)
 
-__all__ = ["FlagAggregator", "FaError", "FaInfoResult", "library_path",
+__all__ = ["FlagAggregator", "FaError", "FaInfoResult", "fa_aggregate_static", "library_path",
            "load_library", "EXPORTED_SYMBOLS"]

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_check_basis", "fa_aggregate_grouped", "fa_multikrum",
     "fa_set_profiling",
     "fa_get_timings", "fa_enqueue_kernel", "fa_aggregate_restream", "fa_get_restream_info",
-    "fa_status_string", "fa_version",
+    "fa_status_string", "fa_version", "fa_aggregate_static",
 )
 
 
@@ -90,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     lib.fa_aggregate_restream.restype = i32
     lib.fa_get_restream_info.argtypes = [vp, vp, vp, vp]
     lib.fa_get_restream_info.restype = i32
+    lib.fa_aggregate_static.argtypes = [vp, i64, i32, i64, i32, i32, dbl, i32, dbl, vp, vp]
+    lib.fa_aggregate_static.restype = i32
     lib.fa_status_string.argtypes = [i32]
     lib.fa_status_string.restype = ctypes.c_char_p
     lib.fa_version.argtypes = []
@@ -119,6 +121,27 @@ class FaInfoResult:
 def _check(status: int, where: str) -> None:
     if status != FA_OK:
         raise FaError(status, where)
+
+
+def fa_aggregate_static(G, m: int, lam: float, iters: int, tol: float, out):
+    """``fa_aggregate`` through the entry point that allocates nothing (no context; the
+    library's fixed device-resident workspace).  ``G``: ``[p, n]`` float32 or bfloat16 device
+    tensor with unit inner stride, ``out``: contiguous float32 device tensor of n elements,
+    both the caller's.  Enqueued on torch's current stream of the current device."""
+    import torch
+    if not G.is_cuda or G.dim() != 2 or G.stride(1) != 1 or G.dtype not in (torch.float32,
+                                                                             torch.bfloat16):
+        raise TypeError("G must be a float32/bfloat16 device tensor with unit inner stride")
+    p, n = G.shape
+    if not out.is_cuda or out.dtype != torch.float32 or out.numel() != n or not out.is_contiguous():
+        raise TypeError("out must be a contiguous float32 device tensor of n elements")
+    ldg = G.stride(0) if p > 1 else n
+    _check(load_library().fa_aggregate_static(
+        ctypes.c_void_p(G.data_ptr()), int(ldg), int(p), int(n),
+        FA_F32 if G.dtype == torch.float32 else FA_BF16, int(m), float(lam), int(iters),
+        float(tol), ctypes.c_void_p(out.data_ptr()),
+        ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)), "fa_aggregate_static")
+    return out
 
 
 class FlagAggregator:

@@ -4,7 +4,8 @@ import ctypes
 FA_P_MAX = 64
 FA_ITERS_MAX = 256
 
-FA_OK, FA_ERR_ARG, FA_ERR_ALLOC, FA_ERR_DEVICE, FA_ERR_NONFINITE, FA_ERR_ZERO_INPUT = range(6)
+(FA_OK, FA_ERR_ARG, FA_ERR_ALLOC, FA_ERR_DEVICE, FA_ERR_NONFINITE, FA_ERR_ZERO_INPUT,
+ FA_ERR_TOO_LARGE) = range(7)
 FA_F32, FA_BF16 = 0, 1
 FA_WORKER_MAJOR, FA_ROW_MAJOR = 0, 1
 FA_SOLVER_AUTO, FA_SOLVER_JACOBI16, FA_SOLVER_JACOBI = 0, 1, 2

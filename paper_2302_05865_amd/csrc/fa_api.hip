@@ -4,6 +4,7 @@
 
 #include <vector>
 #include <math.h>
+#include <pthread.h>
 #include <new>
 #include <stdlib.h>
 #include <string.h>
@@ -62,6 +63,7 @@ extern "C" const char* fa_status_string(fa_status s) {
     case FA_ERR_DEVICE: return "HIP call failed";
     case FA_ERR_NONFINITE: return "input holds NaN or Inf";
     case FA_ERR_ZERO_INPUT: return "all gradients are zero";
+    case FA_ERR_TOO_LARGE: return "p exceeds FA_STATIC_P_MAX, the limit of the static workspace";
   }
   return "unknown status";
 }
@@ -202,6 +204,108 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   c->has_solution = 1;
   c->last_p = p;
   c->last_m = m;
+  return FA_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// fa_aggregate without a context and without any allocation: the workspace is this array in
+// the device image (every GPU holds its own copy at its own address).  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the kernels get the looked-up
+// address, as they get the context's buffers in fa_aggregate.
+namespace {
+
+constexpr int kStaticBlocks = 256;                       // partial Grams: one per compute unit
+constexpr int kStaticTiles = (FA_STATIC_P_MAX / 16) * (FA_STATIC_P_MAX / 16 + 1) / 2;
+constexpr size_t kOffPartials = 0;
+constexpr size_t kOffK = kOffPartials + sizeof(double) * kStaticBlocks * kStaticTiles * 256;
+constexpr size_t kOffC = kOffK + sizeof(double) * FA_P_MAX * FA_P_MAX;
+constexpr size_t kOffGws = kOffC + sizeof(double) * (FA_P_MAX + 8);
+constexpr size_t kOffInfo = kOffGws + sizeof(double) * FA_GWS_DOUBLES;
+constexpr size_t kStaticUsed = kOffInfo + sizeof(fa_info);
+static_assert(kStaticUsed <= FA_STATIC_SCRATCH_BYTES, "the static workspace is too small");
+static_assert(kOffK % 256 == 0 && kOffC % 8 == 0 && kOffGws % 8 == 0 && kOffInfo % 8 == 0,
+              "alignment of the parts of the static workspace");
+
+constexpr int kMaxDevices = 64;
+struct StaticDev {
+  unsigned char* base;   // device address of `scratch` on this GPU; null until looked up
+  int blocks;            // Gram workgroups: min(compute units, kStaticBlocks)
+};
+StaticDev g_static_dev[kMaxDevices];
+pthread_mutex_t g_static_mu = PTHREAD_MUTEX_INITIALIZER;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[FA_STATIC_SCRATCH_BYTES];
+
+// the record of the previous call must not be mistaken for this one's
+__global__ void fa_static_clear_kernel(fa_info* info) {
+  if (threadIdx.x == 0) {
+    info->status = 0; info->p = 0; info->m = 0; info->rank = 0; info->iters_done = 0;
+    info->sweeps = 0;
+  }
+}
+
+// Once per device, with that device current: the address of its copy of the array, its
+// compute-unit count, the kernels' launch attributes.  None of these allocates.
+static fa_status static_setup(int dev, StaticDev* out) {
+  if (dev < 0 || dev >= kMaxDevices) return FA_ERR_DEVICE;
+  fa_status st = FA_OK;
+  pthread_mutex_lock(&g_static_mu);
+  if (!g_static_dev[dev].base) {
+    void* ptr = nullptr;
+    int cus = 0;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        fa_kernels_prepare() != hipSuccess || fa_irls64_prepare() != hipSuccess) {
+      st = FA_ERR_DEVICE;
+    } else {
+      g_static_dev[dev].blocks = cus > 0 && cus < kStaticBlocks ? cus : kStaticBlocks;
+      g_static_dev[dev].base = static_cast<unsigned char*>(ptr);
+    }
+  }
+  if (st == FA_OK) *out = g_static_dev[dev];
+  pthread_mutex_unlock(&g_static_mu);
+  return st;
+}
+
+extern "C" fa_status fa_aggregate_static(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                                         int m, double lambda, int iters, double tol, float* out,
+                                         void* stream) {
+  if (dtype != FA_F32 && dtype != FA_BF16) return FA_ERR_ARG;
+  if (p > FA_STATIC_P_MAX) return FA_ERR_TOO_LARGE;
+  if (!check_matrix_shape(G, ldg, p, n, dtype, FA_WORKER_MAJOR) || !out ||
+      ((uintptr_t)out & 15u) != 0)
+    return FA_ERR_ARG;
+  if (!check_solver_args(p, m, lambda, iters, tol)) return FA_ERR_ARG;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return FA_ERR_DEVICE;
+  StaticDev sd;
+  const fa_status sst = static_setup(dev, &sd);
+  if (sst != FA_OK) return sst;
+  hipStream_t st = (hipStream_t)stream;
+  double* partials = reinterpret_cast<double*>(sd.base + kOffPartials);
+  double* Kd = reinterpret_cast<double*>(sd.base + kOffK);
+  double* cd = reinterpret_cast<double*>(sd.base + kOffC);
+  double* gws = reinterpret_cast<double*>(sd.base + kOffGws);
+  fa_info* info_d = reinterpret_cast<fa_info*>(sd.base + kOffInfo);
+  fa_config cfg;
+  fa_default_config(&cfg);
+  hipLaunchKernelGGL(fa_static_clear_kernel, dim3(1), dim3(64), 0, st, info_d);
+  if (hipGetLastError() != hipSuccess) return FA_ERR_DEVICE;
+  int nparts = 0;
+  if (fa_launch_gram_partials(G, ldg, p, n, dtype, FA_WORKER_MAJOR, sd.blocks, partials, &nparts,
+                              nullptr, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_gram_reduce(partials, nparts, p, Kd, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_irls(Kd, p, m, lambda, iters, tol, cfg.clamp_delta, cfg.rank_tol, cfg.pair_tol,
+                     cfg.exponent_a, cd, info_d, gws, cfg.solver, cfg.wide_spin_budget, nullptr,
+                     st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_combine(G, ldg, p, n, dtype, FA_WORKER_MAJOR, cd, 1, out, 1 << 20, st,
+                        nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
   return FA_OK;
 }
 

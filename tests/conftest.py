@@ -26,7 +26,7 @@ def pytest_collection_modifyitems(config, items):
         # the terminal: a run that dies in a kernel still says which case it was in
         sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
         import gpu_util
-        gpu_util.set_reporter(config.pluginmanager.get_plugin("terminalreporter"))
+        gpu_util.set_capture_manager(config.pluginmanager.get_plugin("capturemanager"))
         return
     skip = pytest.mark.skip(reason="no GPU in this container")
     for item in items:

@@ -25,20 +25,20 @@ def rel_l2(a: np.ndarray, b: np.ndarray) -> float:
     return float(np.linalg.norm(a - b)) / (nb if nb > 0 else 1.0)
 
 
-_reporter = None
+_capture = None
 
 
-def set_reporter(reporter) -> None:
-    """conftest hands over pytest's terminal reporter, so that progress lines reach the
-    terminal while a long case is still running (captured output only shows up at its end)."""
-    global _reporter
-    _reporter = reporter
+def set_capture_manager(capman) -> None:
+    """conftest hands over pytest's capture manager, so that progress lines reach the terminal
+    while a long case is still running (captured output only shows up when a case fails)."""
+    global _capture
+    _capture = capman
 
 
 def announce(*args) -> None:
     line = "[gpu-case] " + " ".join(str(a) for a in args)
-    if _reporter is not None:
-        _reporter.ensure_newline()
-        _reporter.write_line(line, flush=True)
+    if _capture is not None:
+        with _capture.global_and_fixture_disabled():
+            print("\n" + line, flush=True)
     else:
         print(line, flush=True)

@@ -37,8 +37,8 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 def test_status_strings():
     lib = fa.load_library()
-    seen = {lib.fa_status_string(k) for k in range(6)}
-    assert len(seen) == 6 and all(s for s in seen)
+    seen = {lib.fa_status_string(k) for k in range(7)}
+    assert len(seen) == 7 and all(s for s in seen)
 
 
 def test_struct_layouts_match_the_header(tmp_path):
@@ -101,4 +101,10 @@ def test_argument_errors_are_synchronous_without_a_context():
     bad.wide_spin_budget = -1
     assert lib.fa_create(ctypes.byref(bad), ctypes.byref(ctx)) == defs.FA_ERR_ARG
     assert lib.fa_basis(None, None, 0, 1, 1, 1, None, 0) == defs.FA_ERR_ARG
+    # the entry point without a context: its size limit and its argument checks come before
+    # any HIP call
+    assert lib.fa_aggregate_static(None, 0, 65, 1, 0, 1, 0.0, 1, 0.0, None, None) == \
+        defs.FA_ERR_TOO_LARGE
+    assert lib.fa_aggregate_static(None, 0, 4, 1, 0, 1, 0.0, 1, 0.0, None, None) == defs.FA_ERR_ARG
+    assert lib.fa_aggregate_static(None, 0, 4, 1, 7, 1, 0.0, 1, 0.0, None, None) == defs.FA_ERR_ARG
     lib.fa_destroy(None)

@@ -1,0 +1,74 @@
+"""The entry point that allocates nothing (fa_aggregate_static: no context, the library's
+fixed device-resident workspace) against fa_aggregate, through the C ABI: same kernels, same
+launch shapes, so the outputs must agree bit for bit -- on two calls in a row, the second on a
+smaller input (the workspace keeps the first call's contents), for both storage types and a
+wide problem."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from paper_2302_05865_amd import FaError, FlagAggregator, fa_aggregate_static
+
+from gpu_util import announce, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(name, n, seed, iters=None):
+    w = si.WORKLOADS[name].with_n(n)
+    Gw, _ = si.make_inputs(w, seed)
+    return w, to_device(Gw), (w.iters if iters is None else iters)
+
+
+@pytest.mark.parametrize("first,second", [(("cfg2", 300_007), ("cfg1", 40_001)),
+                                          (("cfg5", 60_003), ("cfg4", 20_001)),
+                                          (("cfg4", 50_001), ("cfg2", 9_999))])
+def test_static_entry_matches_fa_aggregate_twice_in_a_row(first, second):
+    cases = [_pair(first[0], first[1], 0), _pair(second[0], second[1], 1)]
+    want = []
+    for w, dev, iters in cases:                       # the existing entry point, own contexts
+        agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype)
+        want.append(agg.fa_aggregate(dev, w.m, w.lam, iters, 0.0).clone())
+        assert agg.fa_get_info().status == 0
+        agg.close()
+    outs = [torch.full((w.n,), float("nan"), dtype=torch.float32, device="cuda")
+            for w, _, _ in cases]
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_allocated()
+    for (w, dev, iters), out in zip(cases, outs):     # two calls in a row, nothing in between
+        announce("static entry", w.name, "p", w.p, "n", w.n)
+        fa_aggregate_static(dev, w.m, w.lam, iters, 0.0, out)
+    torch.cuda.synchronize()
+    assert torch.cuda.memory_allocated() == before    # (torch's own allocator saw nothing)
+    for (w, _, _), out, ref in zip(cases, outs, want):
+        assert torch.equal(out, ref), w.name
+    # the second result once more, after the first: contents left behind do not matter
+    w, dev, iters = cases[1]
+    again = torch.empty_like(outs[1])
+    fa_aggregate_static(dev, w.m, w.lam, iters, 0.0, again)
+    assert torch.equal(again, want[1])
+
+
+def test_static_entry_rejects_what_it_cannot_hold():
+    dev = to_device(si.random_dense(4, 1000, seed=3))
+    out = torch.empty(1000, dtype=torch.float32, device="cuda")
+    with pytest.raises(FaError):
+        fa_aggregate_static(dev, 5, 1.0, 3, 0.0, out)            # m > p
+    with pytest.raises(FaError):
+        fa_aggregate_static(dev, 2, -1.0, 3, 0.0, out)           # lambda < 0
+    wide = torch.zeros((65, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(FaError) as err:
+        fa_aggregate_static(wide, 2, 1.0, 3, 0.0, torch.empty(64, device="cuda"))
+    assert err.value.status == 6                                  # FA_ERR_TOO_LARGE
+
+
+def test_static_entry_reports_data_errors_in_out():
+    Gw = si.random_dense(5, 4096, seed=4)
+    Gw[2, 100] = np.inf
+    out = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    fa_aggregate_static(to_device(Gw), 2, 1.0, 3, 0.0, out)
+    assert torch.isnan(out).all()
+    out = torch.ones(4096, dtype=torch.float32, device="cuda")
+    fa_aggregate_static(to_device(np.zeros((5, 4096), dtype=np.float32)), 2, 1.0, 3, 0.0, out)
+    assert (out == 0).all()
