@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--schedule", choices=["both", "gram-once", "restream"], default="both",
                     help="which schedules to run: the default two-pass one (the metric), the "
                          "re-streaming one (extra figures in the 'restream' object), or both")
+    ap.add_argument("--gram", choices=["auto", "fp64"], default="auto",
+                    help="accumulation of the Gram pass (fa_config.gram): the library's default, "
+                         "or fp64 everywhere")
     ap.add_argument("--alone", action="store_true",
                     help="also time each kernel in a back-to-back loop of its own")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -143,13 +146,18 @@ def main() -> int:
         Gw = None
         args.no_cpu_baseline = True
     else:
-        Gw, _ = si.make_inputs(w, 0)
-        Gw1, _ = si.make_inputs(w, 1)
+        # the two widest configurations at full size come from the chunked parallel generator
+        # (the sequential stream takes minutes for 4e9 deviates)
+        chunked = w.recipe in ("lowrank_noise", "two_cluster") and w.n >= (1 << 24)
+        make = (lambda sd: si.make_inputs_chunked(w, sd, threads=16)) if chunked else \
+               (lambda sd: si.make_inputs(w, sd))
+        Gw, _ = make(0)
+        Gw1, _ = make(1)
         devs = [upload(Gw), upload(Gw1)]
         del Gw1
     gen_s = time.time() - t0
     out = torch.empty(w.n, dtype=torch.float32, device="cuda")
-    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype)
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, gram=args.gram)
     counter = [0]
 
     def step():
@@ -246,7 +254,9 @@ def main() -> int:
     # against that roof when it is the nearer one (algorithmic flops: n p (p + 1), the
     # symmetric half of G^T G, one multiply and one add per term)
     gram_tflops = float(w.n) * w.p * (w.p + 1) / (kms[0] * 1e-3) / 1e12
-    if dom == "fa_gram_kernel" and gram_tflops / FP64_MFMA_PEAK_TFLOPS > gram_gbs / HBM_PEAK_GBS:
+    uses_lp = args.gram == "auto" and (w.dtype == "bf16" or w.p > 16)   # bf16 matrix-core pass
+    if (dom == "fa_gram_kernel" and not uses_lp and
+            gram_tflops / FP64_MFMA_PEAK_TFLOPS > gram_gbs / HBM_PEAK_GBS):
         roofline = {"kernel": dom, "bound": "mfma", "achieved": gram_tflops,
                     "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": gram_tflops / FP64_MFMA_PEAK_TFLOPS, "traffic": traffic.get(dom)}
@@ -291,7 +301,8 @@ def main() -> int:
         "data": "synthetic (drawn on the device)" if args.device_inputs else "synthetic",
         "config": {"workload": f"{w.name}: p={w.p} n={w.n} m={w.m} lambda={w.lam} "
                                f"iters={w.iters} storage={w.dtype}",
-                   "schedule": "gram-once", "inputs": "seeds 0 and 1 alternating"},
+                   "schedule": "gram-once", "inputs": "seeds 0 and 1 alternating",
+                   "gram": args.gram},
         "roofline": roofline,
         "kernels": kernels,
         "hbm_gbs": {"gram": gram_gbs, "combine": comb_gbs,

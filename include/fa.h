@@ -64,6 +64,19 @@ typedef enum { FA_WORKER_MAJOR = 0, FA_ROW_MAJOR = 1 } fa_layout;
  *   fa_aggregate_grouped). */
 typedef enum { FA_SOLVER_AUTO = 0, FA_SOLVER_JACOBI16 = 1, FA_SOLVER_JACOBI = 2 } fa_solver;
 
+/* How the Gram pass accumulates K = G^T G.
+ * FA_GRAM_AUTO: the fastest kernel that keeps the result well inside the parity gate:
+ *   fp32 storage, p <= 16: fp64 matrix-core accumulation of exact products (K good to ~1e-14
+ *     of sqrt(K_ii K_jj); the pass is HBM bound);
+ *   bf16 storage, or fp32 storage at p > 16, worker-major: bf16 matrix core -- exact products
+ *     of bf16 values (fp32 values are split exactly into three bf16 pieces), 32 rows summed in
+ *     fp32 by one matrix instruction, every such partial added in fp64.  K good to a few 1e-9
+ *     (measured; the fp64 matrix core would bound these passes at under half of HBM speed).
+ *     Needs |g| below about 1e18 (32-row sums of products must be finite in fp32).
+ * FA_GRAM_FP64: fp64 accumulation everywhere (also what row-major storage and the
+ *   re-streaming schedule always use). */
+typedef enum { FA_GRAM_AUTO = 0, FA_GRAM_FP64 = 1 } fa_gram_mode;
+
 typedef struct {
   int64_t n_max;      /* largest n this context will see (sizes the workspace) */
   int p_max;          /* largest p, 1..FA_P_MAX */
@@ -85,6 +98,7 @@ typedef struct {
                          Jacobi solver redoes the solve.  Default 1 << 22 (never reached in
                          practice); 0 = give up without polling, which makes every such solve
                          take the stand-by route (for testing it).  >= 0. */
+  int gram;           /* fa_gram_mode; default FA_GRAM_AUTO */
 } fa_config;
 
 /* What the last fa_aggregate / fa_irls call on the context found (all fp64). */
@@ -107,12 +121,12 @@ typedef struct {
 
 /* Fill *cfg with the defaults (n_max = 0, p_max = FA_P_MAX, FA_F32, NULL stream,
  * delta 1e-6, rank_tol 1e-12, pair_tol 1e-12, exponent_a 2, worker-major, FA_SOLVER_AUTO,
- * wide_spin_budget 1 << 22). */
+ * wide_spin_budget 1 << 22, FA_GRAM_AUTO). */
 void fa_default_config(fa_config* cfg);
 
 /* Allocate a context on the current HIP device: the per-block Gram partials
  * (sized from n_max, p_max) and the small p x p workspace.  Returns FA_ERR_ARG for
- * n_max < 1, p_max outside 1..FA_P_MAX, an unknown dtype, layout or solver, a negative
+ * n_max < 1, p_max outside 1..FA_P_MAX, an unknown dtype, layout or solver, gram mode, a negative
  * wide_spin_budget, or tolerances / exponent out of range. */
 fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx);
 

@@ -155,7 +155,7 @@ class FlagAggregator:
     def __init__(self, n_max: int, p_max: int = FA_P_MAX, dtype: str = "f32",
                  clamp_delta: float = 1e-6, rank_tol: float = 1e-12, pair_tol: float = 1e-12,
                  exponent_a: float = 2.0, layout: str = "worker_major", solver: str = "auto",
-                 wide_spin_budget: Optional[int] = None):
+                 wide_spin_budget: Optional[int] = None, gram: str = "auto"):
         import torch  # device memory and streams only
         self._torch = torch
         self._lib = load_library()
@@ -171,6 +171,7 @@ class FlagAggregator:
         cfg.exponent_a = exponent_a
         cfg.layout = {"worker_major": 0, "row_major": 1}[layout]
         cfg.solver = {"auto": 0, "jacobi16": 1, "jacobi": 2}[solver]
+        cfg.gram = {"auto": 0, "fp64": 1}[gram]
         if wide_spin_budget is not None:
             cfg.wide_spin_budget = int(wide_spin_budget)
         self.layout = layout

@@ -9,6 +9,7 @@ FA_ITERS_MAX = 256
 FA_F32, FA_BF16 = 0, 1
 FA_WORKER_MAJOR, FA_ROW_MAJOR = 0, 1
 FA_SOLVER_AUTO, FA_SOLVER_JACOBI16, FA_SOLVER_JACOBI = 0, 1, 2
+FA_GRAM_AUTO, FA_GRAM_FP64 = 0, 1
 
 
 class FaConfig(ctypes.Structure):
@@ -16,7 +17,8 @@ class FaConfig(ctypes.Structure):
                 ("stream", ctypes.c_void_p), ("clamp_delta", ctypes.c_double),
                 ("rank_tol", ctypes.c_double), ("pair_tol", ctypes.c_double),
                 ("exponent_a", ctypes.c_double), ("layout", ctypes.c_int),
-                ("solver", ctypes.c_int), ("wide_spin_budget", ctypes.c_int)]
+                ("solver", ctypes.c_int), ("wide_spin_budget", ctypes.c_int),
+                ("gram", ctypes.c_int)]
 
 
 class FaInfo(ctypes.Structure):

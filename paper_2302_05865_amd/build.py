@@ -21,6 +21,7 @@ SOURCES = {
     # kernels, whose larger tilings need the accumulator registers as extra space.
     "fa_irls16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "fa_irls64.hip": [],
+    "fa_gram_lp.hip": [],
     "fa_api.hip": [],
 }
 OBJ_DIR = os.path.join(HERE, "_build")

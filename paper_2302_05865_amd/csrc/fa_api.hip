@@ -53,6 +53,7 @@ extern "C" void fa_default_config(fa_config* cfg) {
   cfg->layout = FA_WORKER_MAJOR;
   cfg->solver = FA_SOLVER_AUTO;
   cfg->wide_spin_budget = 1 << 22;
+  cfg->gram = FA_GRAM_AUTO;
 }
 
 extern "C" const char* fa_status_string(fa_status s) {
@@ -78,6 +79,7 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   if (cfg->layout != FA_WORKER_MAJOR && cfg->layout != FA_ROW_MAJOR) return FA_ERR_ARG;
   if (cfg->solver < FA_SOLVER_AUTO || cfg->solver > FA_SOLVER_JACOBI) return FA_ERR_ARG;
   if (cfg->wide_spin_budget < 0) return FA_ERR_ARG;
+  if (cfg->gram != FA_GRAM_AUTO && cfg->gram != FA_GRAM_FP64) return FA_ERR_ARG;
   if (!(cfg->clamp_delta > 0.0) || !(cfg->rank_tol >= 0.0) || !(cfg->pair_tol >= 0.0) ||
       !(cfg->exponent_a >= 1.0) || !(cfg->exponent_a <= 1e6))
     return FA_ERR_ARG;
@@ -113,7 +115,8 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
     if (hipEventCreate(&c->tm_r[i].start) != hipSuccess ||
         hipEventCreate(&c->tm_r[i].stop) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
   // per-function launch attributes (large dynamic LDS) on this context's device
-  if (fa_kernels_prepare() != hipSuccess || fa_irls64_prepare() != hipSuccess) {
+  if (fa_kernels_prepare() != hipSuccess || fa_irls64_prepare() != hipSuccess ||
+      fa_gram_lp_prepare() != hipSuccess) {
     fa_destroy(c);
     return FA_ERR_DEVICE;
   }
@@ -184,7 +187,7 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   c->ev_recorded = 0;
   // S1: norms and Gram matrix, per-workgroup partials;  S2: their fixed-order sum
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
                               &nparts, nullptr, st, prof ? &c->tm[0] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, prof ? &c->tm[1] : nullptr) !=
@@ -257,7 +260,8 @@ static fa_status static_setup(int dev, StaticDev* out) {
     int cus = 0;
     if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        fa_kernels_prepare() != hipSuccess || fa_irls64_prepare() != hipSuccess) {
+        fa_kernels_prepare() != hipSuccess || fa_irls64_prepare() != hipSuccess ||
+        fa_gram_lp_prepare() != hipSuccess) {
       st = FA_ERR_DEVICE;
     } else {
       g_static_dev[dev].blocks = cus > 0 && cus < kStaticBlocks ? cus : kStaticBlocks;
@@ -294,7 +298,8 @@ extern "C" fa_status fa_aggregate_static(const void* G, int64_t ldg, int p, int6
   hipLaunchKernelGGL(fa_static_clear_kernel, dim3(1), dim3(64), 0, st, info_d);
   if (hipGetLastError() != hipSuccess) return FA_ERR_DEVICE;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, dtype, FA_WORKER_MAJOR, sd.blocks, partials, &nparts,
+  if (fa_launch_gram_partials(G, ldg, p, n, dtype, FA_WORKER_MAJOR, cfg.gram, sd.blocks, partials,
+                              &nparts,
                               nullptr, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(partials, nparts, p, Kd, st, nullptr) != hipSuccess)
@@ -328,7 +333,7 @@ extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg
   for (int it = 0; it < iters; ++it) {
     const bool last = it == iters - 1;
     // pass 1 over G: Gram matrix of the columns scaled by sqrt(w_i)/|g_i| (plain at first)
-    if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
+    if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
                                 &nparts, it == 0 ? nullptr : u_d, st,
                                 (prof && last) ? &c->tm_r[0] : nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
@@ -406,7 +411,7 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
                              double* K_host) {
   if (!check_matrix_args(c, G, ldg, p, n) || !K_host) return FA_ERR_ARG;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
                               &nparts, nullptr, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
@@ -420,7 +425,7 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
 extern "C" fa_status fa_gram_async(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n) {
   if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
                               &nparts, nullptr, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
@@ -499,8 +504,8 @@ extern "C" fa_status fa_aggregate_grouped(fa_ctx* c, const void* G, int64_t ldg,
       hipSuccess)
     return FA_ERR_DEVICE;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, q, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks,
-                              c->partials, &nparts, nullptr, st, nullptr) != hipSuccess)
+  if (fa_launch_gram_partials(G, ldg, q, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram,
+                              c->gram_max_blocks, c->partials, &nparts, nullptr, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, q, c->Kd, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
@@ -529,8 +534,8 @@ extern "C" fa_status fa_multikrum(fa_ctx* c, const void* G, int64_t ldg, int p, 
   c->ev_recorded = 0;
   c->has_solution = 0;                       // no basis belongs to this result
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks,
-                              c->partials, &nparts, nullptr, st, nullptr) != hipSuccess)
+  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram,
+                              c->gram_max_blocks, c->partials, &nparts, nullptr, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
@@ -593,7 +598,7 @@ extern "C" fa_status fa_enqueue_kernel(fa_ctx* c, int which, const void* G, int6
   hipError_t e = hipSuccess;
   if (which == 0) {
     if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
-    e = fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->gram_max_blocks, c->partials,
+    e = fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
                                 &c->last_nparts, nullptr, c->stream, nullptr);
   } else if (which == 1) {
     if (c->last_nparts < 1) return FA_ERR_ARG;

@@ -32,9 +32,19 @@ typedef struct { hipEvent_t start, stop; } fa_ktime;
 // *nparts receives how many partials were written.  layout: fa_layout (for FA_ROW_MAJOR ldg is
 // the row pitch in elements, p <= ldg <= 16 ceil(p/16)).  colscale (device, p doubles, may be
 // null): column i is scaled by colscale[i], i.e. the result is diag(u) K diag(u).
+// gram_mode: fa_gram_mode (FA_GRAM_AUTO hands the cases of fa_gram_lp_applies to the bf16
+// matrix-core kernel).
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
-                                   int layout, int max_blocks, double* partials, int* nparts,
-                                   const double* colscale, hipStream_t st, const fa_ktime* tm);
+                                   int layout, int gram_mode, int max_blocks, double* partials,
+                                   int* nparts, const double* colscale, hipStream_t st,
+                                   const fa_ktime* tm);
+// K1 on the bf16 matrix core (fa_gram_lp.hip): same partials, for worker-major G without
+// column scales, where fa_gram_lp_applies (bf16 storage, or fp32 storage at p > 16).
+bool fa_gram_lp_applies(int p, int dtype);
+hipError_t fa_launch_gram_lp_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                                      int max_blocks, double* partials, int* nparts,
+                                      hipStream_t st, const fa_ktime* tm);
+hipError_t fa_gram_lp_prepare(void);
 // K2: their fixed-order sum into Kd (p*p doubles, row-major).
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
                                  hipStream_t st, const fa_ktime* tm);

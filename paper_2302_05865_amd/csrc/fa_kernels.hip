@@ -15,6 +15,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "fa.h"
 #include "fa_internal.h"
@@ -676,7 +677,13 @@ __global__ __launch_bounds__(1024) void fa_gram_reduce_kernel(const double* __re
 
 // ------------------------------------------------------------------------------------------
 // K4: out[k] = sum_i c[i] G[k][i]  (Alg. 1: d = (1/p) Y Y^T G 1 = G c).  Each thread owns 16
-// bytes of every column (coalesced), accumulates in fp64 and writes fp32.
+// bytes of every column (coalesced 16-byte loads: four rows of fp32, eight of bf16).
+// fp32 storage: fp64 accumulation, one rounding to fp32 at the end; a thread's four outputs
+// are one 16-byte store and a wavefront's store covers 1 KiB without gaps.
+// bf16 storage: fp32 accumulation with c rounded to fp32 (per element at most (p + 1) 2^-24 of
+// sum_i |c_i g_i|).  A thread's eight outputs are 32 bytes; stored as they are, each of its two
+// stores would leave every other 16 bytes of a line to the other one, so the wavefront turns
+// its 2 KiB of outputs round through LDS and stores two gap-free KiB instead.
 #ifndef FA_COMBINE_NL
 #define FA_COMBINE_NL 8
 #endif
@@ -687,9 +694,11 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
                                                          int cstride, float* __restrict__ out) {
   constexpr int EPL = E::EPL;
   constexpr int NL = FA_COMBINE_NL;   // columns in flight per thread
-  __shared__ double cs[FA_P_MAX + NL];
+  typedef typename std::conditional<E::SIZE == 4, double, float>::type acc_t;
+  __shared__ acc_t cs[FA_P_MAX + NL];
+  __shared__ __attribute__((aligned(16))) float turn[E::SIZE == 2 ? 256 * 8 : 4];
   if (threadIdx.x < FA_P_MAX + NL)
-    cs[threadIdx.x] = (int)threadIdx.x < p ? c[(int64_t)threadIdx.x * cstride] : 0.0;
+    cs[threadIdx.x] = (int)threadIdx.x < p ? (acc_t)c[(int64_t)threadIdx.x * cstride] : (acc_t)0;
   __syncthreads();
   const int64_t ngroups = (n + EPL - 1) / EPL;
   for (int64_t gbase = (int64_t)blockIdx.x * 256; gbase < ngroups;
@@ -698,9 +707,9 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
     const int64_t row0 = gidx * EPL;
     const bool block_full = (gbase + 256) * EPL <= n;   // uniform: no row guards needed
     if (!block_full && gidx >= ngroups) continue;
-    double acc[EPL];
+    acc_t acc[EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = 0.0;
+    for (int e = 0; e < EPL; ++e) acc[e] = (acc_t)0;
     const unsigned char* src = G + row0 * E::SIZE;
     for (int c0 = 0; c0 < p; c0 += NL) {
       uint4 v[NL];
@@ -720,33 +729,52 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
       }
 #pragma unroll
       for (int u = 0; u < NL; ++u) {
-        const double cc = cs[c0 + u];
+        const acc_t cc = cs[c0 + u];
         if constexpr (E::SIZE == 4) {
           acc[0] += cc * (double)__uint_as_float(v[u].x);
           acc[1] += cc * (double)__uint_as_float(v[u].y);
           acc[2] += cc * (double)__uint_as_float(v[u].z);
           acc[3] += cc * (double)__uint_as_float(v[u].w);
         } else {
-          acc[0] += cc * (double)bf16_bits_to_f32(v[u].x & 0xffffu);
-          acc[1] += cc * (double)bf16_bits_to_f32(v[u].x >> 16);
-          acc[2] += cc * (double)bf16_bits_to_f32(v[u].y & 0xffffu);
-          acc[3] += cc * (double)bf16_bits_to_f32(v[u].y >> 16);
-          acc[4] += cc * (double)bf16_bits_to_f32(v[u].z & 0xffffu);
-          acc[5] += cc * (double)bf16_bits_to_f32(v[u].z >> 16);
-          acc[6] += cc * (double)bf16_bits_to_f32(v[u].w & 0xffffu);
-          acc[7] += cc * (double)bf16_bits_to_f32(v[u].w >> 16);
+          acc[0] = fmaf(cc, __uint_as_float(v[u].x << 16), acc[0]);
+          acc[1] = fmaf(cc, __uint_as_float(v[u].x & 0xffff0000u), acc[1]);
+          acc[2] = fmaf(cc, __uint_as_float(v[u].y << 16), acc[2]);
+          acc[3] = fmaf(cc, __uint_as_float(v[u].y & 0xffff0000u), acc[3]);
+          acc[4] = fmaf(cc, __uint_as_float(v[u].z << 16), acc[4]);
+          acc[5] = fmaf(cc, __uint_as_float(v[u].z & 0xffff0000u), acc[5]);
+          acc[6] = fmaf(cc, __uint_as_float(v[u].w << 16), acc[6]);
+          acc[7] = fmaf(cc, __uint_as_float(v[u].w & 0xffff0000u), acc[7]);
         }
       }
     }
     float* dst = out + row0;
-    if (row0 + EPL <= n) {
-#pragma unroll
-      for (int e = 0; e < EPL; e += 4)
-        store16_through(dst + e, make_float4((float)acc[e], (float)acc[e + 1], (float)acc[e + 2],
-                                             (float)acc[e + 3]));
+    if constexpr (E::SIZE == 4) {
+      if (row0 + 4 <= n) {
+        store16_through(dst, make_float4((float)acc[0], (float)acc[1], (float)acc[2],
+                                         (float)acc[3]));
+      } else {
+        for (int e = 0; e < 4; ++e)
+          if (row0 + e < n) dst[e] = (float)acc[e];
+      }
     } else {
-      for (int e = 0; e < EPL; ++e)
-        if (row0 + e < n) dst[e] = (float)acc[e];
+      if (block_full) {
+        // the wavefront's 512 outputs, in row order, through its own 2 KiB of LDS
+        const int lane = threadIdx.x & 63;
+        float* mine = turn + (threadIdx.x & ~63) * 8;
+        wave_lds_fence();        // the previous pass of this wavefront has read its part
+        *reinterpret_cast<float4*>(mine + lane * 8) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        *reinterpret_cast<float4*>(mine + lane * 8 + 4) =
+            make_float4(acc[4], acc[5], acc[6], acc[7]);
+        wave_lds_fence();
+        const float4 lo = *reinterpret_cast<const float4*>(mine + lane * 4);
+        const float4 hi = *reinterpret_cast<const float4*>(mine + 256 + lane * 4);
+        float* wdst = out + (gbase + (threadIdx.x & ~63)) * 8;    // the wavefront's first row
+        store16_through(wdst + lane * 4, lo);
+        store16_through(wdst + 256 + lane * 4, hi);
+      } else {
+        for (int e = 0; e < 8; ++e)
+          if (row0 + e < n) dst[e] = acc[e];
+      }
     }
   }
 }
@@ -1121,8 +1149,12 @@ static hipError_t prepare_gram_e() {
 }
 
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
-                                   int layout, int max_blocks, double* partials, int* nparts,
-                                   const double* colscale, hipStream_t st, const fa_ktime* tm) {
+                                   int layout, int gram_mode, int max_blocks, double* partials,
+                                   int* nparts, const double* colscale, hipStream_t st,
+                                   const fa_ktime* tm) {
+  if (gram_mode == FA_GRAM_AUTO && layout == FA_WORKER_MAJOR && !colscale &&
+      fa_gram_lp_applies(p, dtype))
+    return fa_launch_gram_lp_partials(G, ldg, p, n, dtype, max_blocks, partials, nparts, st, tm);
   if (layout == FA_ROW_MAJOR) {
     if (colscale) return hipErrorInvalidValue;    // the re-streaming schedule is worker-major only
     if (dtype == FA_F32)

@@ -48,13 +48,13 @@ def test_struct_layouts_match_the_header(tmp_path):
 #include <stddef.h>
 #include "fa.h"
 int main(void) {
-  printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %d %d\n", sizeof(fa_config),
+  printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %zu %d %d\n", sizeof(fa_config),
          sizeof(fa_info),
          offsetof(fa_info, objective), offsetof(fa_info, s), offsetof(fa_info, c),
          offsetof(fa_info, A), offsetof(fa_info, K), offsetof(fa_config, clamp_delta),
          offsetof(fa_config, exponent_a), offsetof(fa_config, layout),
-         offsetof(fa_config, solver), offsetof(fa_config, wide_spin_budget), FA_P_MAX,
-         FA_ITERS_MAX);
+         offsetof(fa_config, solver), offsetof(fa_config, wide_spin_budget),
+         offsetof(fa_config, gram), FA_P_MAX, FA_ITERS_MAX);
   return 0;
 }''')
     exe = tmp_path / "layout"
@@ -64,7 +64,7 @@ int main(void) {
     assert vals == [ctypes.sizeof(C), ctypes.sizeof(I), I.objective.offset, I.s.offset,
                     I.c.offset, I.A.offset, I.K.offset, C.clamp_delta.offset,
                     C.exponent_a.offset, C.layout.offset, C.solver.offset,
-                    C.wide_spin_budget.offset, defs.FA_P_MAX, defs.FA_ITERS_MAX]
+                    C.wide_spin_budget.offset, C.gram.offset, defs.FA_P_MAX, defs.FA_ITERS_MAX]
 
 
 def test_default_config_needs_no_gpu():
@@ -75,6 +75,7 @@ def test_default_config_needs_no_gpu():
     assert cfg.clamp_delta == 1e-6 and cfg.rank_tol == 1e-12 and cfg.pair_tol == 1e-12
     assert cfg.exponent_a == 2.0 and cfg.layout == defs.FA_WORKER_MAJOR
     assert cfg.solver == defs.FA_SOLVER_AUTO and cfg.wide_spin_budget == 1 << 22
+    assert cfg.gram == defs.FA_GRAM_AUTO
 
 
 def test_argument_errors_are_synchronous_without_a_context():
@@ -99,6 +100,9 @@ def test_argument_errors_are_synchronous_without_a_context():
     assert lib.fa_create(ctypes.byref(bad), ctypes.byref(ctx)) == defs.FA_ERR_ARG
     bad.solver = defs.FA_SOLVER_AUTO
     bad.wide_spin_budget = -1
+    assert lib.fa_create(ctypes.byref(bad), ctypes.byref(ctx)) == defs.FA_ERR_ARG
+    bad.wide_spin_budget = 0
+    bad.gram = 2                  # no such accumulation mode
     assert lib.fa_create(ctypes.byref(bad), ctypes.byref(ctx)) == defs.FA_ERR_ARG
     assert lib.fa_basis(None, None, 0, 1, 1, 1, None, 0) == defs.FA_ERR_ARG
     # the entry point without a context: its size limit and its argument checks come before

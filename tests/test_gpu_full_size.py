@@ -46,13 +46,29 @@ def test_full_size(name):
     announce(name, "rel_l2", e_out, "proj", e_proj, "gap", info.eigengap, "sweeps", info.sweeps)
     assert info.status == 0 and info.iters_done == w.iters
     assert e_out <= 1e-4 and e_proj <= 1e-4
-    # the Gram matrix entry by entry against the oracle's R^T R.  Both sides add up n products
-    # per entry in fp64 (relative rounding ~1e-16 sqrt(n) in the worst order); 1e-11 of
-    # sqrt(K_ii K_jj) leaves a decade over that at n = 1.24e8.
+    # the Gram matrix entry by entry against the oracle's R^T R.  fp64 accumulation (cfg2,
+    # cfg3; cfg4/cfg5 through a context that asks for it): both sides add up n products per
+    # entry in fp64 (relative rounding ~1e-16 sqrt(n) in the worst order); 1e-11 of
+    # sqrt(K_ii K_jj) leaves a decade over that at n = 1.24e8.  The default route of cfg4/cfg5
+    # (bf16 matrix core: 32-row sums rounded to fp32 once) is held to 2e-8: the measured bias
+    # of sums of squares is 3.5e-9, the random part has averaged out at this n.
     d = np.sqrt(np.diag(ref["K"]))
     e_K = np.abs(info.K - ref["K"]) / np.outer(d, d)
     announce(name, "max Gram error / sqrt(K_ii K_jj)", e_K.max())
-    assert e_K.max() <= 1e-11
+    wide = name in ("cfg4", "cfg5")
+    assert e_K.max() <= (2e-8 if wide else 1e-11)
+    if wide:
+        exact = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, gram="fp64")
+        out64 = exact.fa_aggregate(dev, w.m, w.lam, w.iters, 0.0)
+        info64 = exact.fa_get_info()
+        e_K64 = np.abs(info64.K - ref["K"]) / np.outer(d, d)
+        e_out64 = rel_l2(out64.cpu().numpy().astype(np.float64), ref["out"])
+        e_proj64 = projector_difference(info64.A, ref["A"], ref["R"])
+        announce(name, "fp64 Gram route: max Gram error", e_K64.max(), "rel_l2", e_out64, "proj",
+                 e_proj64)
+        assert e_K64.max() <= 1e-11 and e_out64 <= 1e-4 and e_proj64 <= 1e-4
+        exact.close()
+        del out64
     assert np.allclose(info.v, ref["v"], atol=1e-6)
     # sampled outputs recomputed one by one from the definition out[k] = sum_i c_i G[k, i]:
     # random rows, and rows of the last 1 % of n (in the last gradients of cfg4/cfg5 those sit
