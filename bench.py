@@ -32,10 +32,24 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 FP64_MFMA_PEAK_TFLOPS = 78.6   # MI355X fp64 matrix, published
 
-# HBM traffic of the two streaming kernels per launch, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script (profiles/pmc_cfg2.md: counter values, calibration
-# against a plain copy of known size, and the commands).
-MEASURED_TRAFFIC_BYTES = {"fa_gram_kernel": 6.726e8, "fa_combine_kernel": 7.183e8}
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of the streaming kernels from the committed rocprofv3 --pmc summary
+    of `workload` (profiles/pmc_<workload>.md; its line `traffic_bytes_per_launch: name=bytes
+    ...` holds FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a
+    plain copy of known size).  Returns ({kernel: bytes}, file name) or ({}, None)."""
+    if not workload:
+        return {}, None
+    rel = os.path.join("profiles", f"pmc_{workload}.md")
+    try:
+        for line in open(os.path.join(ROOT, rel)):
+            if line.startswith("traffic_bytes_per_launch:"):
+                pairs = (tok.split("=") for tok in line.split(":", 1)[1].split())
+                return {k: float(v) for k, v in pairs}, rel
+    except OSError:
+        pass
+    return {}, None
 
 
 def main() -> int:
@@ -244,37 +258,52 @@ def main() -> int:
     comb_bytes = float(w.n) * w.p * es + 4.0 * w.n     # G read once + out written
     gram_gbs = gram_bytes / (kms[0] * 1e-3) / 1e9
     comb_gbs = comb_bytes / (kms[3] * 1e-3) / 1e9
+    # which Gram kernel ran: the bf16 matrix-core pass (bf16 storage, or fp32 at p > 16, unless
+    # fp64 accumulation was asked for) or the fp64 matrix-core pass
+    uses_lp = args.gram == "auto" and (w.dtype == "bf16" or w.p > 16)
+    k1_name = "fa_gram_lp_kernel" if uses_lp else "fa_gram_kernel"
+    k3_name = "fa_irls16_kernel" if w.p <= 16 else "fa_irls64_kernel"
+    # HBM traffic per launch as measured with rocprofv3 --pmc: read from the committed summary
+    # of this workload, if there is one (never typed in here); null otherwise
+    traffic, traffic_src = read_traffic(w.name if not args.n else None)
     # the roofline entry is for the longer of the two streaming kernels
-    dom = "fa_gram_kernel" if kms[0] >= kms[3] else "fa_combine_kernel"
-    dom_gbs = gram_gbs if dom == "fa_gram_kernel" else comb_gbs
-    traffic = MEASURED_TRAFFIC_BYTES if w.name == "cfg2" and not args.n else {}
+    dom = k1_name if kms[0] >= kms[3] else "fa_combine_kernel"
+    dom_gbs = gram_gbs if dom == k1_name else comb_gbs
     roofline = {"kernel": dom, "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic.get(dom)}
-    # the Gram pass of a wide problem is bound by the fp64 matrix core, not by HBM: price it
-    # against that roof when it is the nearer one (algorithmic flops: n p (p + 1), the
+                "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic.get(dom),
+                "traffic_source": traffic_src if traffic.get(dom) is not None else None}
+    # the fp64 Gram pass of a wide problem is bound by the fp64 matrix core, not by HBM: price
+    # it against that roof when it is the nearer one (algorithmic flops: n p (p + 1), the
     # symmetric half of G^T G, one multiply and one add per term)
     gram_tflops = float(w.n) * w.p * (w.p + 1) / (kms[0] * 1e-3) / 1e12
-    uses_lp = args.gram == "auto" and (w.dtype == "bf16" or w.p > 16)   # bf16 matrix-core pass
-    if (dom == "fa_gram_kernel" and not uses_lp and
+    if (dom == "fa_gram_kernel" and
             gram_tflops / FP64_MFMA_PEAK_TFLOPS > gram_gbs / HBM_PEAK_GBS):
-        roofline = {"kernel": dom, "bound": "mfma", "achieved": gram_tflops,
-                    "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": gram_tflops / FP64_MFMA_PEAK_TFLOPS, "traffic": traffic.get(dom)}
-    k3_name = "fa_irls16_kernel" if w.p <= 16 else "fa_irls64_kernel"
+        roofline.update({"bound": "mfma", "achieved": gram_tflops, "peak": FP64_MFMA_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": gram_tflops / FP64_MFMA_PEAK_TFLOPS})
+    k1 = {"ms_in_step": kms_in[0], "algorithmic_bytes": gram_bytes, "GB/s": gram_gbs,
+          "frac_hbm_peak": gram_gbs / HBM_PEAK_GBS, "traffic": traffic.get(k1_name)}
+    if not uses_lp:
+        k1.update({"TFLOP/s": gram_tflops,
+                   "frac_fp64_mfma_peak": gram_tflops / FP64_MFMA_PEAK_TFLOPS})
     kernels = {
-        "fa_gram_kernel": {"ms_in_step": kms_in[0], "algorithmic_bytes": gram_bytes,
-                           "GB/s": gram_gbs, "frac_hbm_peak": gram_gbs / HBM_PEAK_GBS,
-                           "TFLOP/s": gram_tflops,
-                           "frac_fp64_mfma_peak": gram_tflops / FP64_MFMA_PEAK_TFLOPS,
-                           "traffic": traffic.get("fa_gram_kernel")},
+        k1_name: k1,
         "fa_gram_reduce_kernel": {"ms_in_step": kms_in[1]},
-        k3_name: {"ms_in_step": kms_in[2], "bound": "latency",
+        k3_name: {"ms_in_step": kms_in[2], "bound": "latency (one workgroup)",
                   "purification_steps": info.sweeps},
         "fa_combine_kernel": {"ms_in_step": kms_in[3],
                               "algorithmic_bytes": comb_bytes, "GB/s": comb_gbs,
                               "frac_hbm_peak": comb_gbs / HBM_PEAK_GBS,
                               "traffic": traffic.get("fa_combine_kernel")},
     }
+    whole_gbs = (gram_bytes + comb_bytes) / (ms_per_step * 1e-3) / 1e9
+    # what the roofline entry does not show: the share of the step spent in the kernels that
+    # stream nothing (partial reduction and the single-workgroup p x p solver), and the rate at
+    # which the whole step moves its algorithmic bytes
+    step = {"algorithmic_bytes": gram_bytes + comb_bytes, "GB/s": whole_gbs,
+            "hbm_frac": whole_gbs / HBM_PEAK_GBS,
+            "frac_of_step_not_streaming": float((kms_in[1] + kms_in[2]) / kms_in.sum()),
+            "ms_streaming": float(kms_in[0] + kms_in[3]),
+            "ms_not_streaming": float(kms_in[1] + kms_in[2])}
 
     restream = None if not do_rs else {
         "aggregations_per_s": rsteps / r_elapsed, "ms_per_aggregation": 1e3 * r_elapsed / rsteps,
@@ -305,8 +334,8 @@ def main() -> int:
                    "gram": args.gram},
         "roofline": roofline,
         "kernels": kernels,
-        "hbm_gbs": {"gram": gram_gbs, "combine": comb_gbs,
-                    "whole_step": (gram_bytes + comb_bytes) / (ms_per_step * 1e-3) / 1e9},
+        "step": step,
+        "hbm_gbs": {"gram": gram_gbs, "combine": comb_gbs, "whole_step": whole_gbs},
     }
     if do_rs:
         result["restream"] = restream
@@ -332,6 +361,25 @@ def main() -> int:
                                             f"R-factor oracle, {cpu_s:.2f} s)"}
         result["parity"] = {"rel_l2_out": rel, "projector_diff": proj,
                             "eigengap_at_m": info.eigengap, "rank": info.rank}
+        if w.p * w.n <= 200_000_000:
+            # The cost structure Sec. 4 ("Potential Limitation") describes: a thin SVD of the
+            # n x p re-weighted matrix in every IRLS iteration, lambda = 0.  The oracle's literal
+            # routine does exactly that; a bounded sample (a few solves) is timed and scaled to
+            # the workload's iteration count.
+            from oracle import as_f64_matrix, fa_literal
+            lit_iters = w.iters if w.n <= 1_000_000 else 2
+            Gm = as_f64_matrix(Gw)
+            t0 = time.perf_counter()
+            fa_literal(Gm, w.m, 0.0, lit_iters, 0.0)
+            lit_s = time.perf_counter() - t0
+            del Gm
+            per_solve = lit_s / lit_iters
+            result["cpu_baseline_paper_literal"] = {
+                "value": 1.0 / (per_solve * w.iters), "unit": "aggregations/s", "cores": cores,
+                "kind": "oracle (literal form: n x p SVD per IRLS iteration, lambda = 0)",
+                "seconds_per_irls_iteration": per_solve,
+                "sample": f"{lit_iters} of {w.iters} solves of {w.name} seed 0 "
+                          f"({lit_s:.1f} s), scaled to {w.iters}"}
     result["input_generation_s"] = gen_s
     print(json.dumps(result))
     return 0

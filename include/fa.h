@@ -213,6 +213,32 @@ fa_status fa_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, in
                    int64_t ldy);
 
 /*
+ * The Gram pass spread over the arrival of the gradients (Alg. 1: in every round the parameter
+ * server receives the gradients of the p workers; they come in one after another, and the
+ * aggregation step need not wait for the last one to start on S1).
+ *   fa_gram_begin   starts a round of p gradients of n elements: nothing has arrived.
+ *   fa_gram_update  gradient i is now in its place in G (worker-major storage as for
+ *                   fa_aggregate: element k at G + (i*ldg + k) * elem_size).  One pass over
+ *                   gradient i and the gradients that arrived before it extends K by row and
+ *                   column i: K_ij = g_i . g_j, exact products added in fp64 (as accurate as the
+ *                   fp64 Gram pass).  The places of gradients that have not arrived are not
+ *                   read.  Asynchronous on the context's stream; a gradient may be announced
+ *                   once per round, in any order.
+ *   fa_aggregate_arrived  once all p have arrived: the rest of fa_aggregate (S3-S6: p x p IRLS
+ *                   on the K built so far, then out = G c), same arguments and results; the
+ *                   Gram pass itself is not run again.  FA_ERR_ARG while a gradient is missing.
+ * When the last gradient lands, only its own row of K is left to do: a pass that reads what the
+ * one-shot Gram pass reads, but does p multiply-adds per coordinate instead of p (p + 1) / 2
+ * matrix-core ones.  In total the updates read p (p + 1) / 2 gradients instead of p: the price
+ * of starting early, paid while the server would otherwise wait for stragglers.
+ * Worker-major contexts only (a gradient arrives as one contiguous vector).
+ */
+fa_status fa_gram_begin(fa_ctx* ctx, int p, int64_t n);
+fa_status fa_gram_update(fa_ctx* ctx, const void* G, int64_t ldg, int i);
+fa_status fa_aggregate_arrived(fa_ctx* ctx, const void* G, int64_t ldg, int m, double lambda,
+                               int iters, double tol, float* out);
+
+/*
  * Workers that send several gradients (Sec. 2.1; Sec. 2.2, the extension to g_i in
  * R^{n x k}; Appendix D): the q columns of G are
  * nworkers blocks of consecutive columns, block i of sizes_host[i] >= 1 columns (host memory,

@@ -25,7 +25,8 @@ EXPORTED_SYMBOLS = (
     "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_check_basis", "fa_aggregate_grouped", "fa_multikrum",
     "fa_set_profiling",
     "fa_get_timings", "fa_enqueue_kernel", "fa_aggregate_restream", "fa_get_restream_info",
-    "fa_status_string", "fa_version", "fa_aggregate_static",
+    "fa_status_string", "fa_version", "fa_aggregate_static", "fa_gram_begin", "fa_gram_update",
+    "fa_aggregate_arrived",
 )
 
 
@@ -92,6 +93,12 @@ def load_library() -> ctypes.CDLL:
     lib.fa_get_restream_info.restype = i32
     lib.fa_aggregate_static.argtypes = [vp, i64, i32, i64, i32, i32, dbl, i32, dbl, vp, vp]
     lib.fa_aggregate_static.restype = i32
+    lib.fa_gram_begin.argtypes = [vp, i32, i64]
+    lib.fa_gram_begin.restype = i32
+    lib.fa_gram_update.argtypes = [vp, vp, i64, i32]
+    lib.fa_gram_update.restype = i32
+    lib.fa_aggregate_arrived.argtypes = [vp, vp, i64, i32, dbl, i32, dbl, vp]
+    lib.fa_aggregate_arrived.restype = i32
     lib.fa_status_string.argtypes = [i32]
     lib.fa_status_string.restype = ctypes.c_char_p
     lib.fa_version.argtypes = []
@@ -296,6 +303,28 @@ class FlagAggregator:
         _check(self._lib.fa_gram(self._ctx, ptr, ldg, p, n, K.ctypes.data_as(ctypes.c_void_p)),
                "fa_gram")
         return K
+
+    def fa_gram_begin(self, p: int, n: int) -> None:
+        _check(self._lib.fa_gram_begin(self._ctx, int(p), int(n)), "fa_gram_begin")
+
+    def fa_gram_update(self, G, i: int) -> None:
+        """Gradient ``i`` (row i of the ``[p, n]`` buffer ``G``) has arrived."""
+        ptr, ldg, p, n = self._matrix(G)
+        self._use_current_stream()
+        _check(self._lib.fa_gram_update(self._ctx, ptr, ldg, int(i)), "fa_gram_update")
+
+    def fa_aggregate_arrived(self, G, m: int, lam: float, iters: int, tol: float, out=None):
+        ptr, ldg, p, n = self._matrix(G)
+        torch = self._torch
+        if out is None:
+            out = torch.empty(n, dtype=torch.float32, device=G.device)
+        if not out.is_cuda or out.dtype != torch.float32 or out.numel() != n or not out.is_contiguous():
+            raise TypeError("out must be a contiguous float32 device tensor of n elements")
+        self._use_current_stream()
+        _check(self._lib.fa_aggregate_arrived(self._ctx, ptr, ldg, int(m), float(lam), int(iters),
+                                              float(tol), ctypes.c_void_p(out.data_ptr())),
+               "fa_aggregate_arrived")
+        return out
 
     def fa_gram_async(self, G) -> None:
         ptr, ldg, p, n = self._matrix(G)

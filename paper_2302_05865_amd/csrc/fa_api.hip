@@ -36,6 +36,9 @@ struct fa_ctx {
   int ev_recorded_r;
   int ev_recorded;
   int last_nparts;    // partial Grams written by the last Gram pass
+  int arr_p;          // fa_gram_begin: gradients expected this round (0: no round open)
+  int64_t arr_n;
+  uint64_t arrived;   // bit j: gradient j has been announced by fa_gram_update
 };
 
 static int elem_size(int dtype) { return dtype == FA_F32 ? 4 : 2; }
@@ -419,6 +422,56 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
   if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
   if (hipMemcpy(K_host, c->Kd, sizeof(double) * p * p, hipMemcpyDeviceToHost) != hipSuccess)
     return FA_ERR_DEVICE;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_gram_begin(fa_ctx* c, int p, int64_t n) {
+  if (!c || p < 1 || p > c->cfg.p_max || n < 1 || n > c->cfg.n_max) return FA_ERR_ARG;
+  if (c->cfg.layout != FA_WORKER_MAJOR) return FA_ERR_ARG;
+  c->arr_p = p;
+  c->arr_n = n;
+  c->arrived = 0;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_gram_update(fa_ctx* c, const void* G, int64_t ldg, int i) {
+  if (!c || c->arr_p < 1 || i < 0 || i >= c->arr_p) return FA_ERR_ARG;
+  if ((c->arrived >> i) & 1u) return FA_ERR_ARG;              // announced twice
+  if (!check_matrix_args(c, G, ldg, c->arr_p, c->arr_n)) return FA_ERR_ARG;
+  // partial rows go to the Gram pass's partial buffer (at least 256 doubles per compute unit)
+  int max_parts = c->gram_max_blocks * 256 / FA_ROW_JB;
+  if (max_parts > 1024) max_parts = 1024;
+  if (fa_launch_gram_row(G, ldg, c->arr_p, c->arr_n, c->cfg.dtype, i, c->arrived, c->partials,
+                         max_parts, c->Kd, c->stream) != hipSuccess)
+    return FA_ERR_DEVICE;
+  c->arrived |= (uint64_t)1 << i;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_aggregate_arrived(fa_ctx* c, const void* G, int64_t ldg, int m,
+                                          double lambda, int iters, double tol, float* out) {
+  if (!c || c->arr_p < 1) return FA_ERR_ARG;
+  const int p = c->arr_p;
+  const int64_t n = c->arr_n;
+  const uint64_t all = p == 64 ? ~(uint64_t)0 : (((uint64_t)1 << p) - 1);
+  if (c->arrived != all) return FA_ERR_ARG;                   // a gradient is still missing
+  if (!check_matrix_args(c, G, ldg, p, n) || !out || ((uintptr_t)out & 15u) != 0)
+    return FA_ERR_ARG;
+  if (!check_solver_args(p, m, lambda, iters, tol)) return FA_ERR_ARG;
+  hipStream_t st = c->stream;
+  c->ev_recorded = 0;
+  if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
+                     c->cfg.pair_tol, c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->cfg.solver,
+                     c->cfg.wide_spin_budget, nullptr, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cd, 1, out,
+                        c->combine_max_blocks, st, nullptr) != hipSuccess)
+    return FA_ERR_DEVICE;
+  c->last_nparts = 0;
+  c->has_solution = 1;
+  c->last_p = p;
+  c->last_m = m;
+  c->arr_p = 0;                                                // the round is over
   return FA_OK;
 }
 

@@ -45,6 +45,13 @@ hipError_t fa_launch_gram_lp_partials(const void* G, int64_t ldg, int p, int64_t
                                       int max_blocks, double* partials, int* nparts,
                                       hipStream_t st, const fa_ktime* tm);
 hipError_t fa_gram_lp_prepare(void);
+// Row and column i of K from one pass over gradient i and the resident gradients (bit j of
+// `resident` set: gradient j is in place; i itself is always included): K[i][j] = K[j][i] =
+// g_i . g_j in fp64.  partials: max_parts * FA_ROW_JB doubles of scratch.  Worker-major G.
+#define FA_ROW_JB 16          // gradients paired with gradient i in one pass
+hipError_t fa_launch_gram_row(const void* G, int64_t ldg, int p, int64_t n, int dtype, int i,
+                              uint64_t resident, double* partials, int max_parts, double* Kd,
+                              hipStream_t st);
 // K2: their fixed-order sum into Kd (p*p doubles, row-major).
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
                                  hipStream_t st, const fa_ktime* tm);

@@ -780,6 +780,135 @@ __global__ __launch_bounds__(256) void fa_combine_kernel(const unsigned char* __
 }
 
 // ------------------------------------------------------------------------------------------
+// One row of the Gram matrix: k_u = g_i . g_{cols[u]} for up to FA_ROW_JB resident gradients,
+// for a parameter server that extends K as the gradients arrive (Alg. 1: the server receives
+// the p workers' gradients) instead of waiting for all of them.  Each thread owns 16 bytes of
+// gradient i and of every listed gradient per pass; products of the stored values are exact
+// in fp64 and are added in fp64.  Static chunk -> workgroup map, fixed-order sums inside the
+// workgroup: one partial row per workgroup, bitwise reproducible.
+struct fa_row_cols { int idx[FA_ROW_JB]; };
+
+template <typename E>
+__global__ __launch_bounds__(256) void fa_gram_row_kernel(const unsigned char* __restrict__ G,
+                                                          int64_t ldg, int64_t n, int i,
+                                                          fa_row_cols cols, int nj,
+                                                          double* __restrict__ partials) {
+  constexpr int EPL = E::EPL;
+  __shared__ double red[4][FA_ROW_JB];
+  double acc[FA_ROW_JB];
+#pragma unroll
+  for (int u = 0; u < FA_ROW_JB; ++u) acc[u] = 0.0;
+  const unsigned char* gi = G + (int64_t)i * ldg * E::SIZE;
+  const int64_t ngroups = (n + EPL - 1) / EPL;
+  for (int64_t gbase = (int64_t)blockIdx.x * 256; gbase < ngroups;
+       gbase += (int64_t)gridDim.x * 256) {
+    const int64_t row0 = (gbase + threadIdx.x) * EPL;
+    const bool block_full = (gbase + 256) * EPL <= n;   // uniform
+    uint4 xi, xj[FA_ROW_JB];
+    if (block_full) {
+      xi = load16_stream(gi + row0 * E::SIZE);
+#pragma unroll
+      for (int u = 0; u < FA_ROW_JB; ++u)   // entries past nj repeat the last listed gradient
+        xj[u] = load16_stream(G + ((int64_t)cols.idx[u] * ldg + row0) * E::SIZE);
+    } else {
+      xi = load16_guarded<E>(gi, row0, n);
+#pragma unroll
+      for (int u = 0; u < FA_ROW_JB; ++u)
+        xj[u] = load16_guarded<E>(G + (int64_t)cols.idx[u] * ldg * E::SIZE, row0, n);
+    }
+    double a[EPL];
+    {
+      const uint32_t w[4] = {xi.x, xi.y, xi.z, xi.w};
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        if constexpr (E::SIZE == 4) a[e] = (double)__uint_as_float(w[e]);
+        else a[e] = (double)bf16_bits_to_f32((w[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < FA_ROW_JB; ++u) {
+      const uint32_t w[4] = {xj[u].x, xj[u].y, xj[u].z, xj[u].w};
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        double b;
+        if constexpr (E::SIZE == 4) b = (double)__uint_as_float(w[e]);
+        else b = (double)bf16_bits_to_f32((w[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+        acc[u] = fma(a[e], b, acc[u]);
+      }
+    }
+  }
+  // fixed butterfly inside each wavefront, wavefronts in order
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int u = 0; u < FA_ROW_JB; ++u) {
+    double x = acc[u];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+    if (lane == 0) red[wave][u] = x;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < FA_ROW_JB)
+    partials[(int64_t)blockIdx.x * FA_ROW_JB + threadIdx.x] =
+        (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+// Fixed-order sum of the partial rows (four interleaved strands per entry, then a fixed
+// tree) into row and column i of K (row-major p x p).
+__global__ __launch_bounds__(64 * FA_ROW_JB) void fa_gram_row_reduce_kernel(
+    const double* __restrict__ partials, int nparts, fa_row_cols cols, int nj, int i, int p,
+    double* __restrict__ K) {
+  __shared__ double sh[FA_ROW_JB][64];
+  const int u = threadIdx.x >> 6, s = threadIdx.x & 63;
+  double a = 0.0;
+  for (int b = s; b < nparts; b += 64) a += partials[(int64_t)b * FA_ROW_JB + u];
+  sh[u][s] = a;
+  __syncthreads();
+  if (s == 0 && u < nj) {
+    double t[64];
+#pragma unroll
+    for (int k = 0; k < 64; ++k) t[k] = sh[u][k];
+#pragma unroll
+    for (int w = 32; w >= 1; w >>= 1)
+#pragma unroll
+      for (int k = 0; k < w; ++k) t[k] += t[k + w];
+    const int j = cols.idx[u];
+    K[i * p + j] = t[0];
+    K[j * p + i] = t[0];
+  }
+}
+
+hipError_t fa_launch_gram_row(const void* G, int64_t ldg, int p, int64_t n, int dtype, int i,
+                              uint64_t resident, double* partials, int max_parts, double* Kd,
+                              hipStream_t st) {
+  const int epl = dtype == FA_F32 ? 4 : 8;
+  const int64_t ngroups = (n + epl - 1) / epl;
+  int64_t blocks = (ngroups + 255) / 256;
+  if (blocks > max_parts) blocks = max_parts;
+  // gradient i against itself and against every resident one, FA_ROW_JB of them per pass
+  int list[FA_P_MAX], nl = 0;
+  for (int j = 0; j < p; ++j)
+    if (j == i || ((resident >> j) & 1u)) list[nl++] = j;
+  for (int a0 = 0; a0 < nl; a0 += FA_ROW_JB) {
+    fa_row_cols cols;
+    const int nj = nl - a0 < FA_ROW_JB ? nl - a0 : FA_ROW_JB;
+    for (int u = 0; u < FA_ROW_JB; ++u) cols.idx[u] = list[a0 + (u < nj ? u : nj - 1)];
+    if (dtype == FA_F32)
+      hipLaunchKernelGGL((fa_gram_row_kernel<ElemF32>), dim3((unsigned)blocks), dim3(256), 0, st,
+                         (const unsigned char*)G, ldg, n, i, cols, nj, partials);
+    else
+      hipLaunchKernelGGL((fa_gram_row_kernel<ElemBF16>), dim3((unsigned)blocks), dim3(256), 0, st,
+                         (const unsigned char*)G, ldg, n, i, cols, nj, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(fa_gram_row_reduce_kernel, dim3(1), dim3(64 * FA_ROW_JB), 0, st,
+                       (const double*)partials, (int)blocks, cols, nj, i, p, Kd);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------------
 // Y = G A for MB columns of A at once (the basis of Sec. 2.1 materialised: column a of Y is
 // sum_i A[i][a] g_i): the aggregate pass with MB coefficient vectors, so G is read once per MB
 // columns of Y instead of once per column.  A is row-major p x lda in device memory; column a

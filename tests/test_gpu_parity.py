@@ -144,6 +144,68 @@ def test_gram_with_row_stride_and_determinism(agg_f32):
     assert np.array_equal(K1, K2)          # fixed-order reduction: bitwise reproducible
 
 
+# -------------------------------------------- Gram matrix built as the gradients arrive
+@pytest.mark.parametrize("name,n", [("cfg1", 33_333), ("cfg2", 100_003), ("cfg4", 60_001),
+                                    ("cfg5", 20_011)])
+def test_gram_built_on_arrival_equals_the_one_shot_path(name, n):
+    """fa_gram_begin / fa_gram_update / fa_aggregate_arrived: the gradients land one by one in
+    a buffer whose other places still hold NaN (they must not be read); each arrival extends K
+    by one row and column.  At the end K is the fp64 Gram matrix (<= 1e-12) and the aggregate
+    is the oracle's, and fa_aggregate's on the assembled buffer."""
+    announce("gram on arrival", name, n)
+    w = si.WORKLOADS[name].with_n(n)
+    Gw, _ = si.make_inputs(w, 3)
+    full = to_device(Gw)
+    nan = np.full(Gw.shape, 0x7FC0, np.uint16) if Gw.dtype == np.uint16 else \
+        np.full(Gw.shape, np.nan, np.float32)
+    buf = to_device(nan)                      # same 16-byte row pitch as `full`
+    assert torch.isnan(buf.float()).all()
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, gram="fp64")
+    agg.fa_gram_begin(w.p, w.n)
+    order = np.random.default_rng(5).permutation(w.p)
+    for i in order:
+        buf[i] = full[i]
+        agg.fa_gram_update(buf, int(i))
+    with pytest.raises(FaError):
+        agg.fa_gram_update(buf, int(order[0]))            # announced twice
+    out = agg.fa_aggregate_arrived(buf, w.m, w.lam, w.iters, 0.0)
+    info = agg.fa_get_info()
+    G = as_f64_matrix(Gw)
+    Kref = G.T @ G
+    scale = np.sqrt(np.outer(np.diag(Kref), np.diag(Kref)))
+    assert info.status == 0
+    assert np.max(np.abs(info.K - Kref) / scale) <= 1e-12
+    ref = fa_scaled(Gw, w.m, w.lam, w.iters, 0.0)
+    got = out.cpu().numpy().astype(np.float64)
+    assert rel_l2(got, ref["out"]) <= GATE
+    assert projector_difference(info.A, ref["A"], ref["R"]) <= GATE
+    one_shot = agg.fa_aggregate(full, w.m, w.lam, w.iters, 0.0).cpu().numpy().astype(np.float64)
+    assert rel_l2(got, one_shot) <= 1e-6
+    with pytest.raises(FaError):                            # the round is over
+        agg.fa_aggregate_arrived(buf, w.m, w.lam, w.iters, 0.0)
+    agg.close()
+
+
+def test_gram_on_arrival_argument_errors(agg_f32):
+    announce("gram on arrival: errors")
+    dev = to_device(si.random_dense(5, 1000, seed=8))
+    with pytest.raises(FaError):
+        agg_f32.fa_gram_update(dev, 0)                      # no round open
+    agg_f32.fa_gram_begin(5, 1000)
+    with pytest.raises(FaError):
+        agg_f32.fa_gram_update(dev, 5)                      # no such gradient
+    for i in range(4):
+        agg_f32.fa_gram_update(dev, i)
+    with pytest.raises(FaError):                            # gradient 4 is still missing
+        agg_f32.fa_aggregate_arrived(dev, 2, 1.0, 3, 0.0)
+    agg_f32.fa_gram_update(dev, 4)
+    a = agg_f32.fa_aggregate_arrived(dev, 2, 1.0, 3, 0.0)
+    b = agg_f32.fa_aggregate(dev, 2, 1.0, 3, 0.0)
+    assert rel_l2(a.cpu().numpy().astype(np.float64), b.cpu().numpy().astype(np.float64)) <= 1e-6
+    with pytest.raises(FaError):
+        agg_f32.fa_gram_begin(65, 1000)
+
+
 # ---------------------------------------------------------------------------------- K4
 @pytest.mark.parametrize("p", [1, 7, 15, 16, 33, 64])
 @pytest.mark.parametrize("n", [1, 6, 1025, 250_003])
