@@ -156,8 +156,10 @@ fa_status fa_aggregate(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n
  * The same aggregation under the re-streaming schedule, for measurement: every IRLS solve
  * passes over G twice, the way an implementation that re-does an n-sized decomposition per
  * iteration does (Sec. 3 "Implementation Details"; the cost discussed in Sec. 4).  Per solve:
- *   pass 1  weighted Gram matrix  G^T W G  with W = diag(w_i / |g_i|^2) applied as column
- *           scales inside the Gram kernel (plain G^T G for the first, uniform-weight solve),
+ *   pass 1  weighted Gram matrix  G^T W G  with W = diag(w_i / |g_i|^2): G is streamed again
+ *           and the weights are applied to the p x p sums, G^T W G = W^(1/2) (G^T G) W^(1/2)
+ *           (applied to the columns inside the kernel they cost a fifth of the pass; plain
+ *           G^T G for the first, uniform-weight solve),
  *   then one weighted PCA in p x p space (the pairwise terms of Eq. 5 are linear in G^T G),
  *   pass 2  projections Y^T g_i of all gradients on the new basis by streaming G (Y = G A is
  *           formed tile by tile in registers and never stored), from which the explained

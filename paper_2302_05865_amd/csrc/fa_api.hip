@@ -191,9 +191,9 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   // S1: norms and Gram matrix, per-workgroup partials;  S2: their fixed-order sum
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
-                              &nparts, nullptr, st, prof ? &c->tm[0] : nullptr) != hipSuccess)
+                              &nparts, st, prof ? &c->tm[0] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, prof ? &c->tm[1] : nullptr) !=
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, nullptr, st, prof ? &c->tm[1] : nullptr) !=
       hipSuccess)
     return FA_ERR_DEVICE;
   // S3-S5: p x p IRLS and coefficients
@@ -302,10 +302,9 @@ extern "C" fa_status fa_aggregate_static(const void* G, int64_t ldg, int p, int6
   if (hipGetLastError() != hipSuccess) return FA_ERR_DEVICE;
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, dtype, FA_WORKER_MAJOR, cfg.gram, sd.blocks, partials,
-                              &nparts,
-                              nullptr, st, nullptr) != hipSuccess)
+                              &nparts, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(partials, nparts, p, Kd, st, nullptr) != hipSuccess)
+  if (fa_launch_gram_reduce(partials, nparts, p, Kd, nullptr, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls(Kd, p, m, lambda, iters, tol, cfg.clamp_delta, cfg.rank_tol, cfg.pair_tol,
                      cfg.exponent_a, cd, info_d, gws, cfg.solver, cfg.wide_spin_budget, nullptr,
@@ -335,12 +334,16 @@ extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg
   int nparts = 0;
   for (int it = 0; it < iters; ++it) {
     const bool last = it == iters - 1;
-    // pass 1 over G: Gram matrix of the columns scaled by sqrt(w_i)/|g_i| (plain at first)
-    if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
-                                &nparts, it == 0 ? nullptr : u_d, st,
+    // pass 1 over G: Gram matrix of the columns scaled by u_i = sqrt(w_i)/|g_i| (plain at
+    // first); the scales are applied to the p x p sums, G^T W G = diag(u) (G^T G) diag(u)
+    // (fp64 accumulation whatever the context's mode: the streamed residuals 1 - v of pass 2
+    // are differences of exact projections and need a basis that is orthonormal to 1e-13)
+    if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, FA_GRAM_FP64,
+                                c->gram_max_blocks, c->partials, &nparts, st,
                                 (prof && last) ? &c->tm_r[0] : nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
-    if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, nullptr) != hipSuccess)
+    if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, it == 0 ? nullptr : u_d, st,
+                              nullptr) != hipSuccess)
       return FA_ERR_DEVICE;
     // one weighted PCA with the current weights
     if (fa_launch_irls(c->Kd, p, m, lambda, 1, 0.0, c->cfg.clamp_delta, c->cfg.rank_tol,
@@ -415,9 +418,9 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
   if (!check_matrix_args(c, G, ldg, p, n) || !K_host) return FA_ERR_ARG;
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
-                              &nparts, nullptr, c->stream, nullptr) != hipSuccess)
+                              &nparts, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, nullptr, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
   if (hipMemcpy(K_host, c->Kd, sizeof(double) * p * p, hipMemcpyDeviceToHost) != hipSuccess)
@@ -479,9 +482,9 @@ extern "C" fa_status fa_gram_async(fa_ctx* c, const void* G, int64_t ldg, int p,
   if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
-                              &nparts, nullptr, c->stream, nullptr) != hipSuccess)
+                              &nparts, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, c->stream, nullptr) != hipSuccess)
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, nullptr, c->stream, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   return FA_OK;
 }
@@ -558,9 +561,9 @@ extern "C" fa_status fa_aggregate_grouped(fa_ctx* c, const void* G, int64_t ldg,
     return FA_ERR_DEVICE;
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, q, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram,
-                              c->gram_max_blocks, c->partials, &nparts, nullptr, st, nullptr) != hipSuccess)
+                              c->gram_max_blocks, c->partials, &nparts, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, q, c->Kd, st, nullptr) != hipSuccess)
+  if (fa_launch_gram_reduce(c->partials, nparts, q, c->Kd, nullptr, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls_grouped(c->Kd, q, nworkers, c->sizes_d, m, lambda, iters, tol,
                              c->cfg.clamp_delta, c->cfg.rank_tol, c->cfg.pair_tol,
@@ -588,9 +591,9 @@ extern "C" fa_status fa_multikrum(fa_ctx* c, const void* G, int64_t ldg, int p, 
   c->has_solution = 0;                       // no basis belongs to this result
   int nparts = 0;
   if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram,
-                              c->gram_max_blocks, c->partials, &nparts, nullptr, st, nullptr) != hipSuccess)
+                              c->gram_max_blocks, c->partials, &nparts, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, st, nullptr) != hipSuccess)
+  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, nullptr, st, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   // scores in the solvers' workspace, the selection in the block-width buffer
   if (fa_launch_krum(c->Kd, p, f, q, c->cd, c->gws, c->sizes_d, st) != hipSuccess)
@@ -652,10 +655,10 @@ extern "C" fa_status fa_enqueue_kernel(fa_ctx* c, int which, const void* G, int6
   if (which == 0) {
     if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
     e = fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
-                                &c->last_nparts, nullptr, c->stream, nullptr);
+                                &c->last_nparts, c->stream, nullptr);
   } else if (which == 1) {
     if (c->last_nparts < 1) return FA_ERR_ARG;
-    e = fa_launch_gram_reduce(c->partials, c->last_nparts, p, c->Kd, c->stream, nullptr);
+    e = fa_launch_gram_reduce(c->partials, c->last_nparts, p, c->Kd, nullptr, c->stream, nullptr);
   } else if (which == 2) {
     if (!check_solver_args(p, m, lambda, iters, tol)) return FA_ERR_ARG;
     e = fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,

@@ -30,14 +30,11 @@ typedef struct { hipEvent_t start, stop; } fa_ktime;
 // K1: partial Grams of G, one per launched workgroup, into `partials` (up to max_blocks *
 // T(T+1)/2 * 256 doubles, T = ceil(p/16)); max_blocks = workgroups (one per compute unit);
 // *nparts receives how many partials were written.  layout: fa_layout (for FA_ROW_MAJOR ldg is
-// the row pitch in elements, p <= ldg <= 16 ceil(p/16)).  colscale (device, p doubles, may be
-// null): column i is scaled by colscale[i], i.e. the result is diag(u) K diag(u).
-// gram_mode: fa_gram_mode (FA_GRAM_AUTO hands the cases of fa_gram_lp_applies to the bf16
-// matrix-core kernel).
+// the row pitch in elements, p <= ldg <= 16 ceil(p/16)).  gram_mode: fa_gram_mode
+// (FA_GRAM_AUTO hands the cases of fa_gram_lp_applies to the bf16 matrix-core kernel).
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int layout, int gram_mode, int max_blocks, double* partials,
-                                   int* nparts, const double* colscale, hipStream_t st,
-                                   const fa_ktime* tm);
+                                   int* nparts, hipStream_t st, const fa_ktime* tm);
 // K1 on the bf16 matrix core (fa_gram_lp.hip): same partials, for worker-major G without
 // column scales, where fa_gram_lp_applies (bf16 storage, or fp32 storage at p > 16).
 bool fa_gram_lp_applies(int p, int dtype);
@@ -52,9 +49,11 @@ hipError_t fa_gram_lp_prepare(void);
 hipError_t fa_launch_gram_row(const void* G, int64_t ldg, int p, int64_t n, int dtype, int i,
                               uint64_t resident, double* partials, int max_parts, double* Kd,
                               hipStream_t st);
-// K2: their fixed-order sum into Kd (p*p doubles, row-major).
+// K2: their fixed-order sum into Kd (p*p doubles, row-major).  colscale (device, p doubles,
+// may be null): entry (i, j) is multiplied by colscale[i] colscale[j], i.e. the result is
+// diag(u) K diag(u), the Gram matrix of the columns scaled by u.
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
-                                 hipStream_t st, const fa_ktime* tm);
+                                 const double* colscale, hipStream_t st, const fa_ktime* tm);
 
 // K3: p x p solver.  Kd p*p doubles; cd p doubles out; info_d device fa_info; gws global
 // workspace of FA_GWS_DOUBLES doubles.  solver: 0 = default (matrix-core purification, with

@@ -1,8 +1,9 @@
 // HIP kernels of the Flag Aggregator hot path for gfx950 (MI355X), and their launchers.
 //
 //   K1 fa_gram_kernel        norms + Gram matrix K = G^T G, one streaming pass over G
-//                            (optionally of scaled columns: diag(u) K diag(u))
+//                            (fp64 matrix core; the bf16 matrix-core pass is fa_gram_lp.hip)
 //   K2 fa_gram_reduce_kernel fixed-order reduction of the per-workgroup partial results
+//                            (optionally scaled: diag(u) K diag(u), a weighted Gram matrix)
 //   K3 fa_irls_kernel        the p x p part for any p <= 64: normalisation, IRLS (weighted
 //                            PCA by Jacobi), coefficients c with out = G c
 //                            (p <= 16 has its own kernel, fa_irls16.hip)
@@ -150,20 +151,17 @@ __device__ __forceinline__ void unpack4(const unsigned char* src, double* x) {
   }
 }
 
-// SCALED: column i is multiplied by colscale[i] on its way into the matrix core, so the
-// result is diag(u) G^T G diag(u) (the weighted Gram matrix of a re-weighted PCA).
 // ROWS: G is stored row by row ("interleaved": element i of coordinate k at G + (k*ldg + i)
 // * elem_size, ldg <= 16 T).  A tile of R rows is then one contiguous span of memory; it is
 // read with the same 16-byte coalesced loads, and each lane scatters the four (eight)
 // elements of its pieces to their [column][row] places in LDS.  Where the elements of a piece
 // go is the same for every tile, so it is worked out once.
-template <int T, int CPL, typename E, int WAVES, bool SCALED, bool ROWS>
+template <int T, int CPL, typename E, int WAVES, bool ROWS>
 __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
                                                      const unsigned char* __restrict__ G,
                                                      int64_t ldg, int p, int64_t n,
                                                      int64_t ntiles,
-                                                     double* __restrict__ partials,
-                                                     const double* __restrict__ colscale) {
+                                                     double* __restrict__ partials) {
   constexpr int EPL = E::EPL;
   constexpr int LPC = 64 / CPL;            // lanes per column in one load instruction
   constexpr int R = LPC * EPL;             // rows per tile
@@ -199,13 +197,6 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
     const int col = cg * CPL + lcol;
     colon[cg] = col < p;
     colbase[cg] = G + (int64_t)(colon[cg] ? col : p - 1) * ldg * E::SIZE;
-  }
-
-  double us[T];                            // scale of this lane's operand column in block tt
-#pragma unroll
-  for (int tt = 0; tt < T; ++tt) {
-    us[tt] = 1.0;
-    if constexpr (SCALED) us[tt] = (tt * 16 + c16 < p) ? colscale[tt * 16 + c16] : 0.0;
   }
 
   // interleaved storage: (row in tile, column) of the first element of each of this lane's
@@ -274,13 +265,7 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
       if (colon[cg])
         *reinterpret_cast<uint4*>(lds + (cg * CPL + lcol) * CS + lrow * E::SIZE) = regs[cg];
   };
-  auto operand = [&](const unsigned char* src, int tt, double* x) {
-    unpack4<E>(src, x);
-    if constexpr (SCALED) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) x[j] *= us[tt];
-    }
-  };
+  auto operand = [&](const unsigned char* src, int tt, double* x) { unpack4<E>(src, x); };
 
   wave_lds_fence();
   int64_t tile = wid;
@@ -625,10 +610,13 @@ __global__ __launch_bounds__(256) void fa_restream_weights_kernel(const fa_info*
 // result does not depend on timing.  One 1024-thread block per 64 entries.
 // TM = 0: the tiles are the upper-triangular tile pairs of a symmetric p x p matrix.
 // TM > 0: the tiles are the T x TM blocks of a p x m matrix (row-major, leading dimension m).
+// colscale (may be null; symmetric case only): entry (i, j) is multiplied by u_i u_j, which
+// makes the result the Gram matrix G^T W G of the columns scaled by u = W^(1/2).
 __global__ __launch_bounds__(1024) void fa_gram_reduce_kernel(const double* __restrict__ partials,
                                                               int nparts, int T, int p,
                                                               double* __restrict__ K, int TM,
-                                                              int m) {
+                                                              int m,
+                                                              const double* __restrict__ colscale) {
   const int NTP = TM > 0 ? T * TM : T * (T + 1) / 2;
   const int ei = threadIdx.x & 63, g = threadIdx.x >> 6;   // entry, strand 0..15
   const int E = blockIdx.x * 64 + ei;                      // entry in [0, NTP*256)
@@ -669,8 +657,9 @@ __global__ __launch_bounds__(1024) void fa_gram_reduce_kernel(const double* __re
         if (k == tp) { ta = aa; tb = bb; }
     const int gi = ta * 16 + 4 * r + (l >> 4), gj = tb * 16 + (l & 15);
     if (gi < p && gj < p && gi <= gj) {
-      K[gi * p + gj] = tot;
-      K[gj * p + gi] = tot;
+      const double v = colscale ? tot * (colscale[gi] * colscale[gj]) : tot;
+      K[gi * p + gj] = v;
+      K[gj * p + gi] = v;
     }
   }
 }
@@ -1225,10 +1214,10 @@ size_t fa_irls_lds_bytes(int p, int* big_in_global) {
 
 // ------------------------------------------------------------------------------------------
 // launchers (host).  Shapes are validated by the callers in fa_api.hip.
-template <int T, int CPL, typename E, int WAVES, bool SCALED, bool ROWS>
+template <int T, int CPL, typename E, int WAVES, bool ROWS>
 static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
-                                double* partials, int* nparts, const double* colscale,
-                                hipStream_t st, const fa_ktime* tm) {
+                                double* partials, int* nparts, hipStream_t st,
+                                const fa_ktime* tm) {
   static_assert(WAVES <= FA_GRAM_WAVES_PER_CU, "partials buffer is sized for this many");
   constexpr int R = (64 / CPL) * E::EPL;
   constexpr int CS = R * E::SIZE + 16;
@@ -1240,9 +1229,9 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
   int64_t wgs = (ntiles + WAVES - 1) / WAVES;
   if (wgs > max_blocks) wgs = max_blocks;
   *nparts = (int)wgs;
-  FA_LAUNCH(tm, (fa_gram_kernel<T, CPL, E, WAVES, SCALED, ROWS>), dim3((unsigned)wgs),
-            dim3(64 * WAVES), lds_bytes, st, (const unsigned char*)G, ldg, p, n, ntiles, partials,
-            colscale);
+  FA_LAUNCH(tm, (fa_gram_kernel<T, CPL, E, WAVES, ROWS>), dim3((unsigned)wgs),
+            dim3(64 * WAVES), lds_bytes, st, (const unsigned char*)G, ldg, p, n, ntiles,
+            partials);
   return hipGetLastError();
 }
 
@@ -1250,27 +1239,27 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
 #define FA_GRAM_TILINGS(X) \
   X(1, FA_GRAM_CPL1, FA_GRAM_W1) X(2, FA_GRAM_CPL2, FA_GRAM_W2) X(3, 4, 8) X(4, FA_GRAM_CPL4, FA_GRAM_W4)
 
-template <typename E, bool SCALED, bool ROWS>
+template <typename E, bool ROWS>
 static hipError_t launch_gram_e(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
-                                double* partials, int* nparts, const double* colscale,
-                                hipStream_t st, const fa_ktime* tm) {
+                                double* partials, int* nparts, hipStream_t st,
+                                const fa_ktime* tm) {
   switch ((p + 15) / 16) {
 #define FA_X(t, cpl, w)                                                                        \
-    case t: return launch_gram_t<t, cpl, E, w, SCALED, ROWS>(G, ldg, p, n, max_blocks, partials, \
-                                                             nparts, colscale, st, tm);
+    case t: return launch_gram_t<t, cpl, E, w, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, \
+                                                     st, tm);
     FA_GRAM_TILINGS(FA_X)
 #undef FA_X
   }
   return hipErrorInvalidValue;
 }
 
-template <typename E, bool SCALED, bool ROWS>
+template <typename E, bool ROWS>
 static hipError_t prepare_gram_e() {
   hipError_t e = hipSuccess;
 #define FA_X(t, cpl, w)                                                                          \
   if (e == hipSuccess)                                                                           \
     e = hipFuncSetAttribute(                                                                     \
-        reinterpret_cast<const void*>(fa_gram_kernel<t, cpl, E, w, SCALED, ROWS>),               \
+        reinterpret_cast<const void*>(fa_gram_kernel<t, cpl, E, w, ROWS>),                       \
         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   FA_GRAM_TILINGS(FA_X)
 #undef FA_X
@@ -1279,30 +1268,23 @@ static hipError_t prepare_gram_e() {
 
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int layout, int gram_mode, int max_blocks, double* partials,
-                                   int* nparts, const double* colscale, hipStream_t st,
-                                   const fa_ktime* tm) {
-  if (gram_mode == FA_GRAM_AUTO && layout == FA_WORKER_MAJOR && !colscale &&
-      fa_gram_lp_applies(p, dtype))
+                                   int* nparts, hipStream_t st, const fa_ktime* tm) {
+  if (gram_mode == FA_GRAM_AUTO && layout == FA_WORKER_MAJOR && fa_gram_lp_applies(p, dtype))
     return fa_launch_gram_lp_partials(G, ldg, p, n, dtype, max_blocks, partials, nparts, st, tm);
-  if (layout == FA_ROW_MAJOR) {
-    if (colscale) return hipErrorInvalidValue;    // the re-streaming schedule is worker-major only
-    if (dtype == FA_F32)
-      return launch_gram_e<ElemF32, false, true>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
-    return launch_gram_e<ElemBF16, false, true>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
-  }
+  const bool rows = layout == FA_ROW_MAJOR;
   if (dtype == FA_F32)
-    return colscale ? launch_gram_e<ElemF32, true, false>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm)
-                    : launch_gram_e<ElemF32, false, false>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
-  return colscale ? launch_gram_e<ElemBF16, true, false>(G, ldg, p, n, max_blocks, partials, nparts, colscale, st, tm)
-                  : launch_gram_e<ElemBF16, false, false>(G, ldg, p, n, max_blocks, partials, nparts, nullptr, st, tm);
+    return rows ? launch_gram_e<ElemF32, true>(G, ldg, p, n, max_blocks, partials, nparts, st, tm)
+                : launch_gram_e<ElemF32, false>(G, ldg, p, n, max_blocks, partials, nparts, st, tm);
+  return rows ? launch_gram_e<ElemBF16, true>(G, ldg, p, n, max_blocks, partials, nparts, st, tm)
+              : launch_gram_e<ElemBF16, false>(G, ldg, p, n, max_blocks, partials, nparts, st, tm);
 }
 
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
-                                 hipStream_t st, const fa_ktime* tm) {
+                                 const double* colscale, hipStream_t st, const fa_ktime* tm) {
   const int T = (p + 15) / 16;
   const int NTP = T * (T + 1) / 2;
   FA_LAUNCH(tm, fa_gram_reduce_kernel, dim3(NTP * 4), dim3(1024), 0, st, partials, nparts, T, p,
-            Kd, 0, 0);
+            Kd, 0, 0, colscale);
   return hipGetLastError();
 }
 
@@ -1310,7 +1292,7 @@ hipError_t fa_launch_proj_reduce(const double* partials, int nparts, int p, int 
                                  hipStream_t st, const fa_ktime* tm) {
   const int T = (p + 15) / 16, TM = (m + 15) / 16;
   FA_LAUNCH(tm, fa_gram_reduce_kernel, dim3(T * TM * 4), dim3(1024), 0, st, partials, nparts, T,
-            p, Td, TM, m);
+            p, Td, TM, m, (const double*)nullptr);
   return hipGetLastError();
 }
 
@@ -1335,7 +1317,8 @@ hipError_t fa_launch_cross(const float* Y, int64_t ldy, int m, const void* G, in
   if (e != hipSuccess) return e;
   const int ncols = 16 * TMr + p;
   hipLaunchKernelGGL(fa_gram_reduce_kernel, dim3(TMr * TC * 4), dim3(1024), 0, st,
-                     (const double*)partials, (int)stripes, TMr, m, Wd, TC, ncols);
+                     (const double*)partials, (int)stripes, TMr, m, Wd, TC, ncols,
+                     (const double*)nullptr);
   return hipGetLastError();
 }
 
@@ -1506,12 +1489,10 @@ hipError_t fa_kernels_prepare(void) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   // the streaming kernels that claim a whole compute unit's LDS
-  if (e == hipSuccess) e = prepare_gram_e<ElemF32, false, false>();
-  if (e == hipSuccess) e = prepare_gram_e<ElemF32, true, false>();
-  if (e == hipSuccess) e = prepare_gram_e<ElemF32, false, true>();
-  if (e == hipSuccess) e = prepare_gram_e<ElemBF16, false, false>();
-  if (e == hipSuccess) e = prepare_gram_e<ElemBF16, true, false>();
-  if (e == hipSuccess) e = prepare_gram_e<ElemBF16, false, true>();
+  if (e == hipSuccess) e = prepare_gram_e<ElemF32, false>();
+  if (e == hipSuccess) e = prepare_gram_e<ElemF32, true>();
+  if (e == hipSuccess) e = prepare_gram_e<ElemBF16, false>();
+  if (e == hipSuccess) e = prepare_gram_e<ElemBF16, true>();
   if (e == hipSuccess) e = prepare_proj_e<ElemF32>();
   if (e == hipSuccess) e = prepare_proj_e<ElemBF16>();
   if (e == hipSuccess)
