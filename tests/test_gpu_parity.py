@@ -844,3 +844,35 @@ def test_multi_krum_argument_errors_and_no_basis(agg_f32):
     agg_f32.fa_multikrum(dev, 1, 5)
     with pytest.raises(FaError):
         agg_f32.fa_basis(dev, 2)              # no basis belongs to a Multi-Krum result
+
+
+@pytest.mark.parametrize("name,n", [("cfg2", 2_000_003), ("cfg5", 200_001)])
+def test_two_contexts_on_two_streams_give_the_results_of_the_sequence(name, n):
+    """Independent gradient sets, one context and one stream each, in flight together (the
+    streaming passes of one beside the p x p solver of the other): every result is bit for bit
+    what the same call returns when nothing else runs."""
+    w = si.WORKLOADS[name].with_n(n)
+    devs = [to_device(si.make_inputs(w, seed)[0]) for seed in (0, 1)]
+    aggs = [FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype) for _ in range(2)]
+    try:
+        refs = []
+        for i in range(2):
+            refs.append(aggs[0].fa_aggregate(devs[i], w.m, w.lam, w.iters, 0.0).clone())
+        torch.cuda.synchronize()
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        outs = [torch.empty_like(refs[0]) for _ in range(2)]
+        announce(f"two streams {name} n={n}")
+        for rep in range(6):
+            for o in outs:
+                o.fill_(float("nan"))
+            torch.cuda.synchronize()
+            for i in range(4):
+                with torch.cuda.stream(streams[i & 1]):
+                    aggs[i & 1].fa_aggregate(devs[i & 1], w.m, w.lam, w.iters, 0.0, out=outs[i & 1])
+            torch.cuda.synchronize()
+            for i in range(2):
+                assert torch.equal(outs[i], refs[i]), (rep, i)
+                assert aggs[i].fa_get_info().status == 0
+    finally:
+        for a in aggs:
+            a.close()
