@@ -68,9 +68,10 @@ def main() -> int:
     ap.add_argument("--schedule", choices=["both", "gram-once", "restream"], default="both",
                     help="which schedules to run: the default two-pass one (the metric), the "
                          "re-streaming one (extra figures in the 'restream' object), or both")
-    ap.add_argument("--gram", choices=["auto", "fp64"], default="auto",
-                    help="accumulation of the Gram pass (fa_config.gram): the library's default, "
-                         "or fp64 everywhere")
+    ap.add_argument("--gram", choices=["auto", "fp64", "bf16"], default="auto",
+                    help="accumulation of the Gram pass (fa_config.gram): the library's default "
+                         "(bf16 matrix core where it applies, from 2^20 rows on), fp64 "
+                         "everywhere, or the bf16 matrix core wherever it applies")
     ap.add_argument("--alone", action="store_true",
                     help="also time each kernel in a back-to-back loop of its own")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -292,7 +293,8 @@ def main() -> int:
     comb_gbs = comb_bytes / (kms[3] * 1e-3) / 1e9
     # which Gram kernel ran: the bf16 matrix-core pass (bf16 storage, or fp32 at p > 16, unless
     # fp64 accumulation was asked for) or the fp64 matrix-core pass
-    uses_lp = args.gram == "auto" and (w.dtype == "bf16" or w.p > 16)
+    uses_lp = (args.gram == "bf16" or (args.gram == "auto" and w.n >= (1 << 20))) and \
+              (w.dtype == "bf16" or w.p > 16)
     k1_name = "fa_gram_lp_kernel" if uses_lp else "fa_gram_kernel"
     k3_name = "fa_irls16_kernel" if w.p <= 16 else "fa_irls64_kernel"
     # HBM traffic per launch as measured with rocprofv3 --pmc: read from the committed summary

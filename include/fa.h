@@ -65,17 +65,23 @@ typedef enum { FA_WORKER_MAJOR = 0, FA_ROW_MAJOR = 1 } fa_layout;
 typedef enum { FA_SOLVER_AUTO = 0, FA_SOLVER_JACOBI16 = 1, FA_SOLVER_JACOBI = 2 } fa_solver;
 
 /* How the Gram pass accumulates K = G^T G.
- * FA_GRAM_AUTO: the fastest kernel that keeps the result well inside the parity gate:
- *   fp32 storage, p <= 16: fp64 matrix-core accumulation of exact products (K good to ~1e-14
- *     of sqrt(K_ii K_jj); the pass is HBM bound);
- *   bf16 storage, or fp32 storage at p > 16, worker-major: bf16 matrix core -- exact products
- *     of bf16 values (fp32 values are split exactly into three bf16 pieces), 32 rows summed in
- *     fp32 by one matrix instruction, every such partial added in fp64.  K good to a few 1e-9
- *     (measured; the fp64 matrix core would bound these passes at under half of HBM speed).
- *     Needs |g| below about 1e18 (32-row sums of products must be finite in fp32).
- * FA_GRAM_FP64: fp64 accumulation everywhere (also what row-major storage and the
- *   re-streaming schedule always use). */
-typedef enum { FA_GRAM_AUTO = 0, FA_GRAM_FP64 = 1 } fa_gram_mode;
+ * FA_GRAM_FP64: fp64 matrix-core accumulation of exact products (K good to ~1e-14 of
+ *   sqrt(K_ii K_jj)).  HBM bound for fp32 storage at p <= 16; for bf16 storage and for p > 16
+ *   the fp64 matrix core bounds the pass at under half of HBM speed.  Also what row-major
+ *   storage and the re-streaming schedule always use.
+ * FA_GRAM_BF16_MATRIX: bf16 storage, or fp32 storage at p > 16, worker-major: bf16 matrix
+ *   core -- exact products of bf16 values (fp32 values are split exactly into three bf16
+ *   pieces), 32 rows summed in fp32 by one matrix instruction, every such partial added in
+ *   fp64.  K good to 2^-21 of sqrt(K_ii K_jj) at worst and to a few 1e-9 from a few thousand
+ *   rows on (measured).  Needs |g| below about 1e18 (32-row sums of products must be finite in
+ *   fp32).  Cases the kernel does not cover (fp32 storage at p <= 16, row-major) take the
+ *   fp64 route.
+ * FA_GRAM_AUTO: FA_GRAM_BF16_MATRIX from FA_GRAM_AUTO_MIN_ROWS rows on, where the pass is a
+ *   visible share of the aggregation and the few 1e-9 stay well inside the parity gate;
+ *   FA_GRAM_FP64 below, where the pass costs microseconds either way and a subspace with a
+ *   small eigengap feels every digit of K. */
+typedef enum { FA_GRAM_AUTO = 0, FA_GRAM_FP64 = 1, FA_GRAM_BF16_MATRIX = 2 } fa_gram_mode;
+#define FA_GRAM_AUTO_MIN_ROWS (1 << 20)
 
 typedef struct {
   int64_t n_max;      /* largest n this context will see (sizes the workspace) */

@@ -178,7 +178,7 @@ class FlagAggregator:
         cfg.exponent_a = exponent_a
         cfg.layout = {"worker_major": 0, "row_major": 1}[layout]
         cfg.solver = {"auto": 0, "jacobi16": 1, "jacobi": 2}[solver]
-        cfg.gram = {"auto": 0, "fp64": 1}[gram]
+        cfg.gram = {"auto": 0, "fp64": 1, "bf16": 2}[gram]
         if wide_spin_budget is not None:
             cfg.wide_spin_budget = int(wide_spin_budget)
         self.layout = layout

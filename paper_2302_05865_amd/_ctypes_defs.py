@@ -9,7 +9,8 @@ FA_ITERS_MAX = 256
 FA_F32, FA_BF16 = 0, 1
 FA_WORKER_MAJOR, FA_ROW_MAJOR = 0, 1
 FA_SOLVER_AUTO, FA_SOLVER_JACOBI16, FA_SOLVER_JACOBI = 0, 1, 2
-FA_GRAM_AUTO, FA_GRAM_FP64 = 0, 1
+FA_GRAM_AUTO, FA_GRAM_FP64, FA_GRAM_BF16_MATRIX = 0, 1, 2
+FA_GRAM_AUTO_MIN_ROWS = 1 << 20
 
 
 class FaConfig(ctypes.Structure):

@@ -82,7 +82,8 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   if (cfg->layout != FA_WORKER_MAJOR && cfg->layout != FA_ROW_MAJOR) return FA_ERR_ARG;
   if (cfg->solver < FA_SOLVER_AUTO || cfg->solver > FA_SOLVER_JACOBI) return FA_ERR_ARG;
   if (cfg->wide_spin_budget < 0) return FA_ERR_ARG;
-  if (cfg->gram != FA_GRAM_AUTO && cfg->gram != FA_GRAM_FP64) return FA_ERR_ARG;
+  if (cfg->gram != FA_GRAM_AUTO && cfg->gram != FA_GRAM_FP64 && cfg->gram != FA_GRAM_BF16_MATRIX)
+    return FA_ERR_ARG;
   if (!(cfg->clamp_delta > 0.0) || !(cfg->rank_tol >= 0.0) || !(cfg->pair_tol >= 0.0) ||
       !(cfg->exponent_a >= 1.0) || !(cfg->exponent_a <= 1e6))
     return FA_ERR_ARG;

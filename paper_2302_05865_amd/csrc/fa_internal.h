@@ -31,7 +31,8 @@ typedef struct { hipEvent_t start, stop; } fa_ktime;
 // T(T+1)/2 * 256 doubles, T = ceil(p/16)); max_blocks = workgroups (one per compute unit);
 // *nparts receives how many partials were written.  layout: fa_layout (for FA_ROW_MAJOR ldg is
 // the row pitch in elements, p <= ldg <= 16 ceil(p/16)).  gram_mode: fa_gram_mode
-// (FA_GRAM_AUTO hands the cases of fa_gram_lp_applies to the bf16 matrix-core kernel).
+// (FA_GRAM_BF16_MATRIX, and FA_GRAM_AUTO from FA_GRAM_AUTO_MIN_ROWS rows on, hand the cases of
+// fa_gram_lp_applies to the bf16 matrix-core kernel).
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int layout, int gram_mode, int max_blocks, double* partials,
                                    int* nparts, hipStream_t st, const fa_ktime* tm);

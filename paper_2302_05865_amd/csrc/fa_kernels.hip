@@ -1269,7 +1269,9 @@ static hipError_t prepare_gram_e() {
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int layout, int gram_mode, int max_blocks, double* partials,
                                    int* nparts, hipStream_t st, const fa_ktime* tm) {
-  if (gram_mode == FA_GRAM_AUTO && layout == FA_WORKER_MAJOR && fa_gram_lp_applies(p, dtype))
+  const bool want_lp = gram_mode == FA_GRAM_BF16_MATRIX ||
+                       (gram_mode == FA_GRAM_AUTO && n >= FA_GRAM_AUTO_MIN_ROWS);
+  if (want_lp && layout == FA_WORKER_MAJOR && fa_gram_lp_applies(p, dtype))
     return fa_launch_gram_lp_partials(G, ldg, p, n, dtype, max_blocks, partials, nparts, st, tm);
   const bool rows = layout == FA_ROW_MAJOR;
   if (dtype == FA_F32)

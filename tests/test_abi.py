@@ -102,7 +102,7 @@ def test_argument_errors_are_synchronous_without_a_context():
     bad.wide_spin_budget = -1
     assert lib.fa_create(ctypes.byref(bad), ctypes.byref(ctx)) == defs.FA_ERR_ARG
     bad.wide_spin_budget = 0
-    bad.gram = 2                  # no such accumulation mode
+    bad.gram = 3                  # no such accumulation mode
     assert lib.fa_create(ctypes.byref(bad), ctypes.byref(ctx)) == defs.FA_ERR_ARG
     assert lib.fa_basis(None, None, 0, 1, 1, 1, None, 0) == defs.FA_ERR_ARG
     # the entry point without a context: its size limit and its argument checks come before

@@ -23,16 +23,19 @@ pytestmark = pytest.mark.gpu
 GATE = 1e-4
 
 
+# The default accumulation of the Gram pass switches to the bf16 matrix core at 2^20 rows; the
+# cases here are smaller, so the contexts ask for that route by name ("bf16": wherever the
+# kernel covers the case) or for fp64 accumulation.
 @pytest.fixture(scope="module")
 def agg_f32():
-    a = FlagAggregator(n_max=1 << 22, p_max=64, dtype="f32")
+    a = FlagAggregator(n_max=1 << 22, p_max=64, dtype="f32", gram="bf16")
     yield a
     a.close()
 
 
 @pytest.fixture(scope="module")
 def agg_bf16():
-    a = FlagAggregator(n_max=1 << 22, p_max=64, dtype="bf16")
+    a = FlagAggregator(n_max=1 << 22, p_max=64, dtype="bf16", gram="bf16")
     yield a
     a.close()
 
@@ -53,27 +56,26 @@ def agg_bf16_fp64gram():
 
 def gram_tol(p, n, dtype, mode):
     """Bound on |K - G^T G| / sqrt(K_ii K_jj) by accumulation route.  fp64 accumulation of
-    exact products: 1e-12.  bf16 matrix core (bf16 storage; fp32 storage at p > 16, unless the
-    context asks for fp64): each 32-row partial is rounded to fp32 once (six times for the
+    exact products: 1e-12.  bf16 matrix core (bf16 storage; fp32 storage at p > 16, when the
+    context asks for it or, by default, from 2^20 rows on): each 32-row partial is rounded to fp32 once (six times for the
     pieces of fp32 values), |error| <= a few 2^-24 of the partial's sqrt(K_ii K_jj) share, and
     the shares add up to at most sqrt(K_ii K_jj): 2^-21 whatever n.  From a few thousand rows on
     the roundings average out and what is left is the measured bias of sums of squares,
     3.5e-9: held to 2e-8."""
-    lp = mode == "auto" and (dtype == "bf16" or p > 16)
+    lp = mode == "bf16" and (dtype == "bf16" or p > 16)
     if not lp:
         return 1e-12
     return 2.0 ** -21 if n < 4096 else 2e-8
 
 
 # ----------------------------------------------------------------------------- K1 + K2
-@pytest.mark.parametrize("mode", ["auto", "fp64"])
-@pytest.mark.parametrize("p", [1, 2, 7, 15, 16, 17, 31, 32, 33, 48, 64])
+# fp32 storage at p <= 16 accumulates in fp64 whatever the context asks for: one mode there
+@pytest.mark.parametrize("p,mode", [(p, mode) for p in (1, 2, 7, 15, 16, 17, 31, 32, 33, 48, 64)
+                                    for mode in ("bf16", "fp64") if p > 16 or mode == "bf16"])
 @pytest.mark.parametrize("n", [1, 3, 255, 257, 4099, 300_001])
 def test_gram_matches_fp64_definition(agg_f32, agg_f32_fp64gram, p, n, mode):
-    if mode == "fp64" and p <= 16:
-        pytest.skip("fp32 storage at p <= 16 accumulates in fp64 in either mode")
     announce("gram f32", mode, p, n)
-    agg = agg_f32 if mode == "auto" else agg_f32_fp64gram
+    agg = agg_f32 if mode == "bf16" else agg_f32_fp64gram
     Gw = si.random_dense(p, n, seed=p * 1000 + n % 997, scale=3.0)
     K = agg.fa_gram(to_device(Gw))
     G = as_f64_matrix(Gw)
@@ -83,12 +85,12 @@ def test_gram_matches_fp64_definition(agg_f32, agg_f32_fp64gram, p, n, mode):
     assert np.array_equal(K, K.T)
 
 
-@pytest.mark.parametrize("mode", ["auto", "fp64"])
+@pytest.mark.parametrize("mode", ["bf16", "fp64"])
 @pytest.mark.parametrize("p", [3, 16, 32, 40, 64])
 @pytest.mark.parametrize("n", [5, 1023, 100_003])
 def test_gram_bf16_storage(agg_bf16, agg_bf16_fp64gram, p, n, mode):
     announce("gram bf16", mode, p, n)
-    agg = agg_bf16 if mode == "auto" else agg_bf16_fp64gram
+    agg = agg_bf16 if mode == "bf16" else agg_bf16_fp64gram
     Gw = si.f32_to_bf16_bits(si.random_dense(p, n, seed=p + n, scale=2.0).reshape(-1)).reshape(p, n)
     K = agg.fa_gram(to_device(Gw))
     G = as_f64_matrix(Gw)
@@ -96,6 +98,27 @@ def test_gram_bf16_storage(agg_bf16, agg_bf16_fp64gram, p, n, mode):
     scale = np.sqrt(np.outer(np.diag(ref), np.diag(ref))) + 1e-300
     assert np.max(np.abs(K - ref) / scale) <= gram_tol(p, n, "bf16", mode)
     assert np.array_equal(K, K.T)
+
+
+@pytest.mark.parametrize("dtype,p", [("f32", 40), ("bf16", 12)])
+def test_default_gram_route_switches_at_the_documented_size(agg_f32, agg_bf16, agg_f32_fp64gram,
+                                                            agg_bf16_fp64gram, dtype, p):
+    """fa_config.gram = FA_GRAM_AUTO: fp64 accumulation below FA_GRAM_AUTO_MIN_ROWS rows, the
+    bf16 matrix core from there on -- bit for bit what the contexts that name the route return."""
+    from paper_2302_05865_amd._ctypes_defs import FA_GRAM_AUTO_MIN_ROWS
+    auto = FlagAggregator(n_max=FA_GRAM_AUTO_MIN_ROWS + 8, p_max=p, dtype=dtype)
+    named_fp64 = agg_f32_fp64gram if dtype == "f32" else agg_bf16_fp64gram
+    named_bf16 = agg_f32 if dtype == "f32" else agg_bf16
+    for n, named in ((FA_GRAM_AUTO_MIN_ROWS - 1, named_fp64), (FA_GRAM_AUTO_MIN_ROWS, named_bf16)):
+        announce("default gram route", dtype, p, n)
+        Gw = si.random_dense(p, n, seed=n % 1000 + p, scale=1.3)
+        if dtype == "bf16":
+            Gw = si.f32_to_bf16_bits(Gw.reshape(-1)).reshape(p, n)
+        dev = to_device(Gw)
+        assert np.array_equal(auto.fa_gram(dev), named.fa_gram(dev))
+    # and the two routes differ at all at this size (else the comparison shows nothing)
+    assert not np.array_equal(named_fp64.fa_gram(dev), named_bf16.fa_gram(dev))
+    auto.close()
 
 
 @pytest.mark.parametrize("dtype,p,n", [("bf16", 15, 70_001), ("bf16", 64, 50_003),
@@ -507,7 +530,7 @@ def test_restream_with_duplicate_and_zero_columns(agg_f32):
 
 
 # ------------------------------------------------- the 16 < p <= 64 matrix-core p x p solver
-@pytest.mark.parametrize("mode", ["fp64", "auto"])
+@pytest.mark.parametrize("mode", ["fp64", "bf16"])
 @pytest.mark.parametrize("p,m", [(17, 9), (24, 5), (33, 17), (40, 20), (48, 47), (64, 32)])
 @pytest.mark.parametrize("lam", [0.0, 1.0])
 def test_wide_problems_all_tile_counts(agg_f32, agg_f32_fp64gram, p, m, lam, mode):
@@ -517,7 +540,7 @@ def test_wide_problems_all_tile_counts(agg_f32, agg_f32_fp64gram, p, m, lam, mod
     amplifies by up to 1e3) the whole path is held to the gate."""
     announce("wide", mode, p, m, lam)
     tol = 1e-6 if mode == "fp64" else GATE
-    agg_f32 = agg_f32 if mode == "auto" else agg_f32_fp64gram
+    agg_f32 = agg_f32 if mode == "bf16" else agg_f32_fp64gram
     rng = np.random.default_rng(p)
     n = 20_011
     mu = rng.standard_normal(n)
@@ -821,7 +844,7 @@ def test_multi_krum_matches_the_published_rule(name, n, f, q, layout):
     w = si.WORKLOADS[name].with_n(n)
     Gw, _ = si.make_inputs(w, 0)
     ref = multi_krum(as_f64_matrix(Gw), f, q)
-    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, layout=layout)
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, layout=layout, gram="bf16")
     dev = _rows_device(Gw) if layout == "row_major" else to_device(Gw)
     out, scores, selected = agg.fa_multikrum(dev, f, q)
     # integer decisions: the same set (the workloads have no near-ties apart from exact
