@@ -78,9 +78,11 @@ hipError_t fa_kernels_prepare(void);
 hipError_t fa_irls64_prepare(void);
 // K3 for p <= 16 (latency-tuned single-workgroup solver, static LDS).
 // mlast: 258 doubles; the fast path leaves the last weighted-PCA matrix there (16 x 16, then
-// rank and m) for fa_launch_gap.  use_purification = 0 forces the Jacobi path.
+// rank and m) for fa_launch_gap.  use_purification = 0 forces the Jacobi path.  exponent_a:
+// the constant a of Sec. 2.2 Step 2 (terms residual^(1/a); 2 is Eq. 5).
 hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                            double delta, double rank_tol, double pair_tol, double* cd,
+                            double delta, double exponent_a, double rank_tol, double pair_tol,
+                            double* cd,
                             fa_info* info_d, double* mlast, int use_purification,
                             fa_resume* rs, hipStream_t st, const fa_ktime* tm);
 // K3 for 16 < p <= 64 (sixteen wavefronts, tiled matrix-core products).  tiles_ws:

@@ -73,6 +73,16 @@ __device__ __forceinline__ double rsq_nr(double x) {
 //   tan = N / D,  c = D / sqrt(D^2 + N^2),  s = N / sqrt(D^2 + N^2)
 // (the small-angle root of the Jacobi equation; two reciprocal square roots, no division).
 // *big: the off-diagonal entry exceeded 1e-9 relative to sqrt(|A_aa A_bb|).
+// One term of the objective, residual^(1/a), and the weight the majorisation step gives it,
+// max(residual, delta)^(1/a - 1), for the constant a of Sec. 2.2 Step 2 (expo = 1/a; a = 2,
+// expo = 1/2, is Eq. 5 and has its own square-root code where these are used).
+__device__ __forceinline__ double term_pow(double rho, double expo) {
+  return rho > 0.0 ? pow(rho, expo) : 0.0;
+}
+__device__ __forceinline__ double weight_pow(double rho, double delta, double expo) {
+  return pow(rho > delta ? rho : delta, expo - 1.0);
+}
+
 __device__ __forceinline__ void rotation(double aaa, double abb, double aab, double* c, double* s,
                                          bool* active, bool* big) {
   const double dd = fabs(aaa * abb);
@@ -376,7 +386,7 @@ __device__ FA_CHOL_ATTR int pivoted_cholesky(const double* S, double* rows, int*
 // Returns 1 when the solve was completed here (including the error statuses), 0 when the
 // caller must fall back to the Jacobi path.
 __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, double lambda,
-                     double tol, double delta, double rank_tol, double pair_tol,
+                     double tol, double delta, double expo, double rank_tol, double pair_tol,
                      double* __restrict__ cg, fa_info* __restrict__ info,
                      double* __restrict__ mlast, Fmem& fm, fa_resume* rs) {
   const int lane = threadIdx.x & 63;
@@ -632,17 +642,38 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     rhoj = qjj * dj * dj;                                // 1 - v_j
     // sqrt(rho) = rho * rsqrt(rho) and max(rho, delta)^(-1/2) = min(rsqrt(rho), delta^(-1/2)):
     // one reciprocal square root per residual, no division
-    rsj = rsq_nr<2>(rhoj > 1e-300 ? rhoj : 1e-300);
-    double part = (q4 == 0 && livej) ? rhoj * rsj : 0.0;
+    double part, wnext;
+    if (expo == 0.5) {
+      rsj = rsq_nr<2>(rhoj > 1e-300 ? rhoj : 1e-300);
+      part = (q4 == 0 && livej) ? rhoj * rsj : 0.0;
+      wnext = rsj < rs_delta ? rsj : rs_delta;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const double qii = fm.Zs[4 * r + q4];
-      const double dz2 = fma(-2.0, qz[r], qii + qjj);
-      const double rho = (dz2 > 0.0 ? dz2 : 0.0) * d2inv[r];
-      const bool lp = d2inv[r] > 0.0;
-      const double rs = rsq_nr<2>(rho > 1e-300 ? rho : 1e-300);
-      part += lp ? coef * (rho * rs) : 0.0;            // ordered pair (i, j)
-      cp[r] = lp ? -2.0 * coef * d2inv[r] * (rs < rs_delta ? rs : rs_delta) : 0.0;
+      for (int r = 0; r < 4; ++r) {
+        const double qii = fm.Zs[4 * r + q4];
+        const double dz2 = fma(-2.0, qz[r], qii + qjj);
+        const double rho = (dz2 > 0.0 ? dz2 : 0.0) * d2inv[r];
+        const bool lp = d2inv[r] > 0.0;
+        const double rs = rsq_nr<2>(rho > 1e-300 ? rho : 1e-300);
+        part += lp ? coef * (rho * rs) : 0.0;            // ordered pair (i, j)
+        cp[r] = lp ? -2.0 * coef * d2inv[r] * (rs < rs_delta ? rs : rs_delta) : 0.0;
+      }
+    } else {
+      // the general exponent: same places, powers instead of square roots (rolled: this code
+      // runs once per solve, and five inlined copies of pow() are a thousand instructions)
+      part = (q4 == 0 && livej) ? term_pow(rhoj, expo) : 0.0;
+      wnext = weight_pow(rhoj, delta, expo);
+#pragma unroll 1
+      for (int r = 0; r < 4; ++r) {
+        const double qii = fm.Zs[4 * r + q4];
+        const double qzr = r == 0 ? qz[0] : r == 1 ? qz[1] : r == 2 ? qz[2] : qz[3];
+        const double di2 = r == 0 ? d2inv[0] : r == 1 ? d2inv[1] : r == 2 ? d2inv[2] : d2inv[3];
+        const double dz2 = fma(-2.0, qzr, qii + qjj);
+        const double rho = (dz2 > 0.0 ? dz2 : 0.0) * di2;
+        const bool lp = di2 > 0.0;
+        part += lp ? coef * term_pow(rho, expo) : 0.0;
+        const double cv = lp ? -2.0 * coef * di2 * weight_pow(rho, delta, expo) : 0.0;
+        if (r == 0) cp[0] = cv; else if (r == 1) cp[1] = cv; else if (r == 2) cp[2] = cv; else cp[3] = cv;
+      }
     }
     wave_fence();
     const double obj = wave_sum(part);
@@ -651,7 +682,7 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     const bool stop = it0 + it > 0 && fabs(prev_obj - obj) < tol;
     prev_obj = obj;
     if (stop) break;
-    wj = livej ? (rsj < rs_delta ? rsj : rs_delta) : 0.0;
+    wj = livej ? wnext : 0.0;
   }
 
   // ---- epilogue: basis of range(P), A = B U_m, c = A (U_m^T R 1) / p ---------------------
@@ -724,7 +755,8 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
 
 __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict__ Kg,
                                                         int p, int m, int iters, double lambda,
-                                                        double tol, double delta, double rank_tol,
+                                                        double tol, double delta, double expo,
+                                                        double rank_tol,
                                                         double pair_tol, double* __restrict__ cg,
                                                         fa_info* __restrict__ info,
                                                         double* __restrict__ mlast,
@@ -735,7 +767,7 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
   const int tid = threadIdx.x;
   if (use_purification) {
     if (tid < 64) {
-      const int ok = fastp::solve(Kg, p, m, iters, lambda, tol, delta, rank_tol, pair_tol, cg,
+      const int ok = fastp::solve(Kg, p, m, iters, lambda, tol, delta, expo, rank_tol, pair_tol, cg,
                                   info, mlast, fm, rs);
       if (tid == 0) fast_done = ok;
     }
@@ -874,7 +906,7 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
       const double d2 = sm.dinv[tid] * sm.dinv[tid];
       sm.v[tid] = top * d2;
       sm.rho[tid] = bot * d2;
-      if (sm.s[tid] > 0.0) part += sqrt(bot * d2);
+      if (sm.s[tid] > 0.0) part += expo == 0.5 ? sqrt(bot * d2) : term_pow(bot * d2, expo);
     }
     cpair = 0.0;
     if (coef > 0.0 && ri != ci) {
@@ -888,8 +920,9 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
           bot += sm.pos[a] >= m ? x * x : 0.0;
         }
         const double rho = bot * dinv2;
-        part += coef * sqrt(rho);                  // ordered pair (ri, ci)
-        cpair = -2.0 * coef * dinv2 / sqrt(rho > delta ? rho : delta);
+        part += coef * (expo == 0.5 ? sqrt(rho) : term_pow(rho, expo));   // ordered pair (ri, ci)
+        cpair = -2.0 * coef * dinv2 *
+                (expo == 0.5 ? 1.0 / sqrt(rho > delta ? rho : delta) : weight_pow(rho, delta, expo));
       }
     }
     const double obj = block_sum(part, sm);
@@ -900,7 +933,8 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
     if (stop) break;
     if (tid < p) {
       const double rho = sm.rho[tid];
-      sm.w[tid] = sm.s[tid] > 0.0 ? 1.0 / sqrt(rho > delta ? rho : delta) : 0.0;
+      sm.w[tid] = sm.s[tid] <= 0.0 ? 0.0
+                  : expo == 0.5 ? 1.0 / sqrt(rho > delta ? rho : delta) : weight_pow(rho, delta, expo);
     }
     __syncthreads();
   }
@@ -959,10 +993,12 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
 }
 
 hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                            double delta, double rank_tol, double pair_tol, double* cd,
+                            double delta, double exponent_a, double rank_tol, double pair_tol,
+                            double* cd,
                             fa_info* info_d, double* mlast, int use_purification,
                             fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
   FA_LAUNCH(tm, fa_irls16_kernel, dim3(1), dim3(256), 0, st, Kd, p, m, iters, lambda, tol, delta,
-            rank_tol, pair_tol, cd, info_d, mlast, use_purification, rs);
+            exponent_a == 2.0 ? 0.5 : 1.0 / exponent_a, rank_tol, pair_tol, cd, info_d, mlast,
+            use_purification, rs);
   return hipGetLastError();
 }
