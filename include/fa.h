@@ -60,8 +60,8 @@ typedef enum { FA_WORKER_MAJOR = 0, FA_ROW_MAJOR = 1 } fa_layout;
  * FA_SOLVER_AUTO: projector by matrix-core purification, no eigen-decomposition; a solve it
  *   cannot finish (eigenvalues m and m+1 tied) is redone by a Jacobi solver.
  * FA_SOLVER_JACOBI16: the p <= 16 Jacobi eigensolver (p > 16: as FA_SOLVER_AUTO).
- * FA_SOLVER_JACOBI: the any-p Jacobi eigensolver (always used for fa_aggregate_grouped, and
- *   for exponent_a != 2 at p > 16; at p <= 16 every solver knows the exponent). */
+ * FA_SOLVER_JACOBI: the any-p Jacobi eigensolver (always used for fa_aggregate_grouped).
+ * Every solver knows exponent_a. */
 typedef enum { FA_SOLVER_AUTO = 0, FA_SOLVER_JACOBI16 = 1, FA_SOLVER_JACOBI = 2 } fa_solver;
 
 /* How the Gram pass accumulates K = G^T G.

@@ -76,6 +76,16 @@ hipError_t fa_launch_irls_grouped(const double* Kd, int q, int nworkers, const i
 // the current device; called by fa_create.
 hipError_t fa_kernels_prepare(void);
 hipError_t fa_irls64_prepare(void);
+// One term of the objective, residual^(1/a), and the weight the majorisation step gives it,
+// max(residual, delta)^(1/a - 1), for the constant a of Sec. 2.2 Step 2 (expo = 1/a; a = 2,
+// expo = 1/2, is Eq. 5 and has its own square-root code in the matrix-core solvers).
+__device__ __forceinline__ double fa_term_pow(double rho, double expo) {
+  return rho > 0.0 ? pow(rho, expo) : 0.0;
+}
+__device__ __forceinline__ double fa_weight_pow(double rho, double delta, double expo) {
+  return pow(rho > delta ? rho : delta, expo - 1.0);
+}
+
 // K3 for p <= 16 (latency-tuned single-workgroup solver, static LDS).
 // mlast: 258 doubles; the fast path leaves the last weighted-PCA matrix there (16 x 16, then
 // rank and m) for fa_launch_gap.  use_purification = 0 forces the Jacobi path.  exponent_a:
@@ -87,9 +97,11 @@ hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int i
                             fa_resume* rs, hipStream_t st, const fa_ktime* tm);
 // K3 for 16 < p <= 64 (sixteen wavefronts, tiled matrix-core products).  tiles_ws:
 // FA_GWS_TILES doubles; mlast as above with N = 16 ceil(p/16).  May leave
-// info_d->status = FA_ST_RETRY, in which case the any-p kernel must run next.
+// info_d->status = FA_ST_RETRY, in which case the any-p kernel must run next.  exponent_a as
+// for fa_launch_irls16.
 hipError_t fa_launch_irls64(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                            double delta, double rank_tol, double pair_tol, double* cd,
+                            double delta, double exponent_a, double rank_tol, double pair_tol,
+                            double* cd,
                             fa_info* info_d, double* tiles_ws, double* mlast, int spin_budget,
                             fa_resume* rs, hipStream_t st, const fa_ktime* tm);
 // eigengap (mu_m - mu_{m+1}) / mu_1 of the N x N matrix left in mlast (then rank, m), into

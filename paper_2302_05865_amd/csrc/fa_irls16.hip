@@ -73,16 +73,6 @@ __device__ __forceinline__ double rsq_nr(double x) {
 //   tan = N / D,  c = D / sqrt(D^2 + N^2),  s = N / sqrt(D^2 + N^2)
 // (the small-angle root of the Jacobi equation; two reciprocal square roots, no division).
 // *big: the off-diagonal entry exceeded 1e-9 relative to sqrt(|A_aa A_bb|).
-// One term of the objective, residual^(1/a), and the weight the majorisation step gives it,
-// max(residual, delta)^(1/a - 1), for the constant a of Sec. 2.2 Step 2 (expo = 1/a; a = 2,
-// expo = 1/2, is Eq. 5 and has its own square-root code where these are used).
-__device__ __forceinline__ double term_pow(double rho, double expo) {
-  return rho > 0.0 ? pow(rho, expo) : 0.0;
-}
-__device__ __forceinline__ double weight_pow(double rho, double delta, double expo) {
-  return pow(rho > delta ? rho : delta, expo - 1.0);
-}
-
 __device__ __forceinline__ void rotation(double aaa, double abb, double aab, double* c, double* s,
                                          bool* active, bool* big) {
   const double dd = fabs(aaa * abb);
@@ -660,8 +650,8 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
     } else {
       // the general exponent: same places, powers instead of square roots (rolled: this code
       // runs once per solve, and five inlined copies of pow() are a thousand instructions)
-      part = (q4 == 0 && livej) ? term_pow(rhoj, expo) : 0.0;
-      wnext = weight_pow(rhoj, delta, expo);
+      part = (q4 == 0 && livej) ? fa_term_pow(rhoj, expo) : 0.0;
+      wnext = fa_weight_pow(rhoj, delta, expo);
 #pragma unroll 1
       for (int r = 0; r < 4; ++r) {
         const double qii = fm.Zs[4 * r + q4];
@@ -670,8 +660,8 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
         const double dz2 = fma(-2.0, qzr, qii + qjj);
         const double rho = (dz2 > 0.0 ? dz2 : 0.0) * di2;
         const bool lp = di2 > 0.0;
-        part += lp ? coef * term_pow(rho, expo) : 0.0;
-        const double cv = lp ? -2.0 * coef * di2 * weight_pow(rho, delta, expo) : 0.0;
+        part += lp ? coef * fa_term_pow(rho, expo) : 0.0;
+        const double cv = lp ? -2.0 * coef * di2 * fa_weight_pow(rho, delta, expo) : 0.0;
         if (r == 0) cp[0] = cv; else if (r == 1) cp[1] = cv; else if (r == 2) cp[2] = cv; else cp[3] = cv;
       }
     }
@@ -906,7 +896,7 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
       const double d2 = sm.dinv[tid] * sm.dinv[tid];
       sm.v[tid] = top * d2;
       sm.rho[tid] = bot * d2;
-      if (sm.s[tid] > 0.0) part += expo == 0.5 ? sqrt(bot * d2) : term_pow(bot * d2, expo);
+      if (sm.s[tid] > 0.0) part += expo == 0.5 ? sqrt(bot * d2) : fa_term_pow(bot * d2, expo);
     }
     cpair = 0.0;
     if (coef > 0.0 && ri != ci) {
@@ -920,9 +910,9 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
           bot += sm.pos[a] >= m ? x * x : 0.0;
         }
         const double rho = bot * dinv2;
-        part += coef * (expo == 0.5 ? sqrt(rho) : term_pow(rho, expo));   // ordered pair (ri, ci)
+        part += coef * (expo == 0.5 ? sqrt(rho) : fa_term_pow(rho, expo));   // ordered pair (ri, ci)
         cpair = -2.0 * coef * dinv2 *
-                (expo == 0.5 ? 1.0 / sqrt(rho > delta ? rho : delta) : weight_pow(rho, delta, expo));
+                (expo == 0.5 ? 1.0 / sqrt(rho > delta ? rho : delta) : fa_weight_pow(rho, delta, expo));
       }
     }
     const double obj = block_sum(part, sm);
@@ -934,7 +924,7 @@ __global__ __launch_bounds__(256) void fa_irls16_kernel(const double* __restrict
     if (tid < p) {
       const double rho = sm.rho[tid];
       sm.w[tid] = sm.s[tid] <= 0.0 ? 0.0
-                  : expo == 0.5 ? 1.0 / sqrt(rho > delta ? rho : delta) : weight_pow(rho, delta, expo);
+                  : expo == 0.5 ? 1.0 / sqrt(rho > delta ? rho : delta) : fa_weight_pow(rho, delta, expo);
     }
     __syncthreads();
   }

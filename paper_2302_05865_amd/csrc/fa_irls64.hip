@@ -147,10 +147,13 @@ struct Small {
 
 }  // namespace
 
-template <int T>
+// GEN: terms residual^(1/a) with the constant a of Sec. 2.2 Step 2 other than Eq. 5's a = 2 (a
+// kernel of its own: the powers must not take registers from the a = 2 code)
+template <int T, bool GEN>
 __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __restrict__ Kg, int p,
                                                              int m, int iters, double lambda,
                                                              double tol, double delta,
+                                                             double expo,
                                                              double rank_tol, double pair_tol,
                                                              double* __restrict__ cg,
                                                              fa_info* __restrict__ info,
@@ -562,31 +565,63 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     double part = 0.0;
     if (wave < NTP) {
       v4d cpn;
+      if constexpr (!GEN) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int i = 16 * uI + 4 * r + q4, j = 16 * uJ + c16;
-        double cv = 0.0;
-        if (i == j) {
-          // |(I - P) r_j|^2 / |g_j|^2 = 1 - v_j
-          const double rho = gq[r] * sm.dinv[j] * sm.dinv[j];
-          const bool livej = sm.s[j] > 0.0;
-          const double rsj = rsq2(rho > 1e-300 ? rho : 1e-300);
-          if (livej) part += rho * rsj;
-          sm.rho[j] = rho;
-          sm.wn[j] = livej ? (rsj < rs_delta ? rsj : rs_delta) : 0.0;
-        } else {
-          const double d2i = D2I[eidx<T>(i, j)];
-          if (d2i > 0.0 && coef > 0.0) {
-            double num = sm.gd[i] + sm.gd[j] - 2.0 * gq[r];
-            num = num > 0.0 ? num : 0.0;
-            const double rho = num * d2i;
-            const double rsv = rsq2(rho > 1e-300 ? rho : 1e-300);
-            // ordered pairs: an off-diagonal tile stands for its mirror image too
-            part += (uI == uJ ? 1.0 : 2.0) * coef * (rho * rsv);
-            cv = -2.0 * coef * d2i * (rsv < rs_delta ? rsv : rs_delta);
+        for (int r = 0; r < 4; ++r) {
+          const int i = 16 * uI + 4 * r + q4, j = 16 * uJ + c16;
+          double cv = 0.0;
+          if (i == j) {
+            // |(I - P) r_j|^2 / |g_j|^2 = 1 - v_j
+            const double rho = gq[r] * sm.dinv[j] * sm.dinv[j];
+            const bool livej = sm.s[j] > 0.0;
+            const double rsj = rsq2(rho > 1e-300 ? rho : 1e-300);
+            if (livej) part += rho * rsj;
+            sm.rho[j] = rho;
+            sm.wn[j] = livej ? (rsj < rs_delta ? rsj : rs_delta) : 0.0;
+          } else {
+            const double d2i = D2I[eidx<T>(i, j)];
+            if (d2i > 0.0 && coef > 0.0) {
+              double num = sm.gd[i] + sm.gd[j] - 2.0 * gq[r];
+              num = num > 0.0 ? num : 0.0;
+              const double rho = num * d2i;
+              const double rsv = rsq2(rho > 1e-300 ? rho : 1e-300);
+              // ordered pairs: an off-diagonal tile stands for its mirror image too
+              part += (uI == uJ ? 1.0 : 2.0) * coef * (rho * rsv);
+              cv = -2.0 * coef * d2i * (rsv < rs_delta ? rsv : rs_delta);
+            }
           }
+          cpn[r] = cv;
         }
-        cpn[r] = cv;
+      } else {
+        // the general exponent: same places, powers instead of square roots (rolled: once per
+        // solve, and inlined copies of pow() are long)
+#pragma unroll 1
+        for (int r = 0; r < 4; ++r) {
+          const int i = 16 * uI + 4 * r + q4, j = 16 * uJ + c16;
+          const double gqr = r == 0 ? gq[0] : r == 1 ? gq[1] : r == 2 ? gq[2] : gq[3];
+          double rho = 0.0, scale = 0.0;       // residual; factor of its term in the objective
+          bool diag = i == j, use = false;
+          double d2i = 0.0;
+          if (diag) {
+            rho = gqr * sm.dinv[j] * sm.dinv[j];
+            use = sm.s[j] > 0.0;
+            scale = 1.0;
+          } else {
+            d2i = D2I[eidx<T>(i, j)];
+            if (d2i > 0.0 && coef > 0.0) {
+              double num = sm.gd[i] + sm.gd[j] - 2.0 * gqr;
+              num = num > 0.0 ? num : 0.0;
+              rho = num * d2i;
+              use = true;
+              scale = (uI == uJ ? 1.0 : 2.0) * coef;
+            }
+          }
+          const double tv = fa_term_pow(rho, expo), wv = fa_weight_pow(rho, delta, expo);
+          if (use) part += scale * tv;
+          if (diag) { sm.rho[j] = rho; sm.wn[j] = use ? wv : 0.0; }
+          const double cv = (!diag && use) ? -2.0 * coef * d2i * wv : 0.0;
+          if (r == 0) cpn[0] = cv; else if (r == 1) cpn[1] = cv; else if (r == 2) cpn[2] = cv; else cpn[3] = cv;
+        }
       }
       store_tile<T>(B2, uI, uJ, lane, cpn);
       if (uI != uJ) store_tile_transposed<T>(B2, uI, uJ, lane, cpn);
@@ -737,35 +772,46 @@ static constexpr size_t lds_bytes() {
 
 template <int T>
 static hipError_t launch_t(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                           double delta, double rank_tol, double pair_tol, double* cd,
+                           double delta, double expo, double rank_tol, double pair_tol, double* cd,
                            fa_info* info_d, double* tiles_ws, double* mlast, int spin_budget,
                            fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
-  FA_LAUNCH(tm, fa_irls64_kernel<T>, dim3(1), dim3(NTHREADS), lds_bytes<T>(), st, Kd, p, m, iters,
-            lambda, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs);
+  if (expo == 0.5)
+    FA_LAUNCH(tm, (fa_irls64_kernel<T, false>), dim3(1), dim3(NTHREADS), lds_bytes<T>(), st, Kd, p,
+              m, iters, lambda, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast,
+              spin_budget, rs);
+  else
+    FA_LAUNCH(tm, (fa_irls64_kernel<T, true>), dim3(1), dim3(NTHREADS), lds_bytes<T>(), st, Kd, p,
+              m, iters, lambda, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast,
+              spin_budget, rs);
   return hipGetLastError();
 }
 
+template <int T, bool GEN>
+static hipError_t prepare_t() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<T, GEN>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<T>());
+}
+
 hipError_t fa_irls64_prepare(void) {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<2>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)lds_bytes<2>());
-  if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<3>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<3>());
-  if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<4>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<4>());
+  hipError_t e = prepare_t<2, false>();
+  if (e == hipSuccess) e = prepare_t<3, false>();
+  if (e == hipSuccess) e = prepare_t<4, false>();
+  if (e == hipSuccess) e = prepare_t<2, true>();
+  if (e == hipSuccess) e = prepare_t<3, true>();
+  if (e == hipSuccess) e = prepare_t<4, true>();
   return e;
 }
 
 hipError_t fa_launch_irls64(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                            double delta, double rank_tol, double pair_tol, double* cd,
+                            double delta, double exponent_a, double rank_tol, double pair_tol,
+                            double* cd,
                             fa_info* info_d, double* tiles_ws, double* mlast, int spin_budget,
                             fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
+  const double expo = exponent_a == 2.0 ? 0.5 : 1.0 / exponent_a;
   switch ((p + 15) / 16) {
-    case 2: return launch_t<2>(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
-    case 3: return launch_t<3>(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
-    case 4: return launch_t<4>(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+    case 2: return launch_t<2>(Kd, p, m, lambda, iters, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+    case 3: return launch_t<3>(Kd, p, m, lambda, iters, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+    case 4: return launch_t<4>(Kd, p, m, lambda, iters, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
   }
   return hipErrorInvalidValue;
 }

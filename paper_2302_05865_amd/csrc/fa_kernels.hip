@@ -1399,15 +1399,14 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
                           double* cd,
                           fa_info* info_d, double* gws, int solver, int spin_budget,
                           fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
-  // other exponents than Eq. 5's: the p <= 16 kernel and the any-p kernel know them
-  if (exponent_a != 2.0 && p > 16) solver = 2;
   if (p <= 16 && solver != 2)
     return fa_launch_irls16(Kd, p, m, lambda, iters, tol, delta, exponent_a, rank_tol, pair_tol, cd,
                             info_d,
                             gws + FA_GWS_MLAST_OFF, solver == 0 ? 1 : 0, rs, st, tm);
   int retry_only = 0;
   if (p > 16 && solver == 0) {
-    hipError_t e = fa_launch_irls64(Kd, p, m, lambda, iters, tol, delta, rank_tol, pair_tol, cd,
+    hipError_t e = fa_launch_irls64(Kd, p, m, lambda, iters, tol, delta, exponent_a, rank_tol,
+                                    pair_tol, cd,
                                     info_d, gws + FA_GWS_GENERIC, gws + FA_GWS_MLAST_OFF,
                                     spin_budget, rs, st, tm);
     if (e != hipSuccess) return e;
