@@ -2,7 +2,6 @@
 // ownership, and the order in which the kernels are enqueued.  No arithmetic happens here.
 #include <hip/hip_runtime.h>
 
-#include <vector>
 #include <math.h>
 #include <pthread.h>
 #include <new>
@@ -30,6 +29,7 @@ struct fa_ctx {
   fa_resume* rs_d;    // IRLS state of the re-streaming schedule
   double* Pd;         // streamed projections, FA_P_MAX^2
   int* sizes_d;       // FA_P_MAX: block widths of fa_aggregate_grouped
+  double* check_h;    // pinned host staging of fa_check_basis: FA_P_MAX * 2 FA_P_MAX doubles
   fa_ktime tm[4];     // per-kernel begin/end events (profiling)
   fa_ktime tm_r[2];   // re-streaming schedule: weighted Gram pass and projection pass of the
                       // last iteration
@@ -110,6 +110,8 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   ok = ok && hipMalloc((void**)&c->rs_d, sizeof(fa_resume)) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->Pd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->sizes_d, sizeof(int) * FA_P_MAX) == hipSuccess;
+  ok = ok && hipHostMalloc((void**)&c->check_h, sizeof(double) * FA_P_MAX * 2 * FA_P_MAX,
+                           hipHostMallocDefault) == hipSuccess;
   if (!ok) { fa_destroy(c); return FA_ERR_ALLOC; }
   if (hipMemset(c->info_d, 0, sizeof(fa_info)) != hipSuccess) { fa_destroy(c); return FA_ERR_DEVICE; }
   for (int i = 0; i < 4; ++i)
@@ -139,6 +141,7 @@ extern "C" void fa_destroy(fa_ctx* c) {
   if (c->rs_d) (void)hipFree(c->rs_d);
   if (c->Pd) (void)hipFree(c->Pd);
   if (c->sizes_d) (void)hipFree(c->sizes_d);
+  if (c->check_h) (void)hipHostFree(c->check_h);
   for (int i = 0; i < 4; ++i) {
     if (c->tm[i].start) (void)hipEventDestroy(c->tm[i].start);
     if (c->tm[i].stop) (void)hipEventDestroy(c->tm[i].stop);
@@ -529,16 +532,10 @@ extern "C" fa_status fa_basis(fa_ctx* c, const void* G, int64_t ldg, int p, int6
   // column a of Y = G * A[:, a]; A is row-major p x m inside the device-side record
   const double* A = reinterpret_cast<const double*>(reinterpret_cast<const char*>(c->info_d) +
                                                     offsetof(fa_info, A));
-  if (c->cfg.layout == FA_WORKER_MAJOR) {   // G read once per eight columns of Y
-    if (fa_launch_combine_multi(G, ldg, p, n, c->cfg.dtype, A, m, Y, ldy, c->combine_max_blocks,
-                                c->stream) != hipSuccess)
-      return FA_ERR_DEVICE;
-    return FA_OK;
-  }
-  for (int a = 0; a < m; ++a)
-    if (fa_launch_combine(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, A + a, m, Y + (int64_t)a * ldy,
-                          c->combine_max_blocks, c->stream, nullptr) != hipSuccess)
-      return FA_ERR_DEVICE;
+  // G is read once per eight columns of Y, whatever its layout
+  if (fa_launch_combine_multi(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, A, m, Y, ldy,
+                              c->combine_max_blocks, c->stream) != hipSuccess)
+    return FA_ERR_DEVICE;
   return FA_OK;
 }
 
@@ -630,13 +627,8 @@ extern "C" fa_status fa_check_basis(fa_ctx* c, const void* G, int64_t ldg, int p
   if (fa_launch_cross(Y, ldy, m, G, ldg, p, n, c->cfg.dtype, c->cfg.layout, max_parts,
                       c->partials, c->gws, c->stream) != hipSuccess)
     return FA_ERR_DEVICE;
-  std::vector<double> W;
-  try {
-    W.resize((size_t)m * ncols);
-  } catch (...) {
-    return FA_ERR_ALLOC;    // no exception crosses the C boundary
-  }
-  if (hipMemcpyAsync(W.data(), c->gws, W.size() * sizeof(double), hipMemcpyDeviceToHost,
+  double* W = c->check_h;      // m <= FA_P_MAX rows of ncols <= 2 FA_P_MAX
+  if (hipMemcpyAsync(W, c->gws, (size_t)m * ncols * sizeof(double), hipMemcpyDeviceToHost,
                      c->stream) != hipSuccess)
     return FA_ERR_DEVICE;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;

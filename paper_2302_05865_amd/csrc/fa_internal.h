@@ -126,10 +126,10 @@ hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int d
                              const double* c, int cstride, float* out, int max_blocks,
                              hipStream_t st, const fa_ktime* tm);
 
-// Y = G A, m columns at once (worker-major G): column a of Y at Y + a*ldy.
+// Y = G A, eight columns per pass over G (either layout): column a of Y at Y + a*ldy.
 hipError_t fa_launch_combine_multi(const void* G, int64_t ldg, int p, int64_t n, int dtype,
-                                   const double* A, int m, float* Y, int64_t ldy, int max_blocks,
-                                   hipStream_t st);
+                                   int layout, const double* A, int m, float* Y, int64_t ldy,
+                                   int max_blocks, hipStream_t st);
 // Multi-Krum in p-space: coefficients (1/q on the q selected workers), scores and the 0/1
 // selection from the Gram matrix; f = Byzantine workers provided for (p - f - 2 >= 1).
 hipError_t fa_launch_krum(const double* Kd, int p, int f, int q, double* cd, double* scores_d,

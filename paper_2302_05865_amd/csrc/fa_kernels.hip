@@ -470,20 +470,26 @@ __global__ __launch_bounds__(64 * WAVES) void fa_proj_kernel(
 // contiguous span of its 256 rows with coalesced 16-byte loads, scattering the elements to
 // LDS as [column][row]; then thread r adds up row r (fp64) and the workgroup writes 256
 // consecutive outputs.
-template <typename E>
+#define FA_ROWS_MULTI 8   // columns of a materialised basis per pass over row-major G
+// MB > 1: up to MB combinations from one pass over G (column a of the output, at out + a*ldo,
+// uses the coefficients c[i*cstride + a]): the materialised basis Y = G A of row-major storage.
+template <typename E, int MB>
 __global__ __launch_bounds__(256) void fa_combine_rows_kernel(const unsigned char* __restrict__ G,
                                                               int ldr, int p, int64_t n,
                                                               const double* __restrict__ c,
-                                                              int cstride, float* __restrict__ out,
+                                                              int cstride, int ncols,
+                                                              float* __restrict__ out, int64_t ldo,
                                                               unsigned magic) {
   constexpr int EPL = E::EPL;
   constexpr int RB = 256;                  // rows per workgroup pass
   constexpr int PITCH = RB + 1;            // LDS words per column
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   float* tile = reinterpret_cast<float*>(lds_raw);          // p * PITCH floats
-  __shared__ double cs[FA_P_MAX];
-  if (threadIdx.x < FA_P_MAX)
-    cs[threadIdx.x] = (int)threadIdx.x < p ? c[(int64_t)threadIdx.x * cstride] : 0.0;
+  __shared__ double cs[MB][FA_P_MAX];
+  for (int idx = threadIdx.x; idx < MB * FA_P_MAX; idx += 256) {
+    const int a = idx / FA_P_MAX, i = idx % FA_P_MAX;
+    cs[a][i] = (i < p && a < ncols) ? c[(int64_t)i * cstride + a] : 0.0;
+  }
   const int64_t nblk = (n + RB - 1) / RB;
   for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
     const int64_t row_base = blk * RB;
@@ -524,14 +530,28 @@ __global__ __launch_bounds__(256) void fa_combine_rows_kernel(const unsigned cha
     __syncthreads();
     const int r = (int)threadIdx.x;
     if (r < rows_here) {
-      double a0 = 0.0, a1 = 0.0;
-      int i = 0;
-      for (; i + 1 < p; i += 2) {
-        a0 = fma(cs[i], (double)tile[i * PITCH + r], a0);
-        a1 = fma(cs[i + 1], (double)tile[(i + 1) * PITCH + r], a1);
+      if constexpr (MB == 1) {
+        double a0 = 0.0, a1 = 0.0;
+        int i = 0;
+        for (; i + 1 < p; i += 2) {
+          a0 = fma(cs[0][i], (double)tile[i * PITCH + r], a0);
+          a1 = fma(cs[0][i + 1], (double)tile[(i + 1) * PITCH + r], a1);
+        }
+        if (i < p) a0 = fma(cs[0][i], (double)tile[i * PITCH + r], a0);
+        out[row_base + r] = (float)(a0 + a1);
+      } else {
+        double acc[MB];
+#pragma unroll
+        for (int a = 0; a < MB; ++a) acc[a] = 0.0;
+        for (int i = 0; i < p; ++i) {
+          const double t = (double)tile[i * PITCH + r];
+#pragma unroll
+          for (int a = 0; a < MB; ++a) acc[a] = fma(cs[a][i], t, acc[a]);
+        }
+#pragma unroll
+        for (int a = 0; a < MB; ++a)
+          if (a < ncols) out[(int64_t)a * ldo + row_base + r] = (float)acc[a];
       }
-      if (i < p) a0 = fma(cs[i], (double)tile[i * PITCH + r], a0);
-      out[row_base + r] = (float)(a0 + a1);
     }
   }
 }
@@ -908,10 +928,13 @@ __global__ __launch_bounds__(256) void fa_combine_multi_kernel(
     const double* __restrict__ A, int lda, int ncols, float* __restrict__ Y, int64_t ldy) {
   constexpr int EPL = E::EPL;
   constexpr int NL = 4;                     // columns of G in flight per thread
-  __shared__ double cs[(FA_P_MAX + NL) * MB];
+  // fp32 storage: fp64 sums, one rounding per output; bf16 storage: fp32 sums with the
+  // coefficients rounded to fp32, as in the aggregate pass of that storage
+  typedef typename std::conditional<E::SIZE == 4, double, float>::type acc_t;
+  __shared__ acc_t cs[(FA_P_MAX + NL) * MB];
   for (int t = threadIdx.x; t < (FA_P_MAX + NL) * MB; t += 256) {
     const int i = t / MB, a = t - i * MB;
-    cs[t] = (i < p && a < ncols) ? A[(int64_t)i * lda + a] : 0.0;
+    cs[t] = (i < p && a < ncols) ? (acc_t)A[(int64_t)i * lda + a] : (acc_t)0;
   }
   __syncthreads();
   const int64_t ngroups = (n + EPL - 1) / EPL;
@@ -921,11 +944,11 @@ __global__ __launch_bounds__(256) void fa_combine_multi_kernel(
     const int64_t row0 = gidx * EPL;
     const bool block_full = (gbase + 256) * EPL <= n;   // uniform: no row guards needed
     if (!block_full && gidx >= ngroups) continue;
-    double acc[MB][EPL];
+    acc_t acc[MB][EPL];
 #pragma unroll
     for (int a = 0; a < MB; ++a)
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[a][e] = 0.0;
+      for (int e = 0; e < EPL; ++e) acc[a][e] = (acc_t)0;
     const unsigned char* src = G + row0 * E::SIZE;
     for (int c0 = 0; c0 < p; c0 += NL) {
       uint4 v[NL];
@@ -937,21 +960,24 @@ __global__ __launch_bounds__(256) void fa_combine_multi_kernel(
       }
 #pragma unroll
       for (int u = 0; u < NL; ++u) {
-        double x[EPL];
+        acc_t x[EPL];
         if constexpr (E::SIZE == 4) {
           x[0] = (double)__uint_as_float(v[u].x); x[1] = (double)__uint_as_float(v[u].y);
           x[2] = (double)__uint_as_float(v[u].z); x[3] = (double)__uint_as_float(v[u].w);
         } else {
-          x[0] = (double)bf16_bits_to_f32(v[u].x & 0xffffu); x[1] = (double)bf16_bits_to_f32(v[u].x >> 16);
-          x[2] = (double)bf16_bits_to_f32(v[u].y & 0xffffu); x[3] = (double)bf16_bits_to_f32(v[u].y >> 16);
-          x[4] = (double)bf16_bits_to_f32(v[u].z & 0xffffu); x[5] = (double)bf16_bits_to_f32(v[u].z >> 16);
-          x[6] = (double)bf16_bits_to_f32(v[u].w & 0xffffu); x[7] = (double)bf16_bits_to_f32(v[u].w >> 16);
+          x[0] = __uint_as_float(v[u].x << 16); x[1] = __uint_as_float(v[u].x & 0xffff0000u);
+          x[2] = __uint_as_float(v[u].y << 16); x[3] = __uint_as_float(v[u].y & 0xffff0000u);
+          x[4] = __uint_as_float(v[u].z << 16); x[5] = __uint_as_float(v[u].z & 0xffff0000u);
+          x[6] = __uint_as_float(v[u].w << 16); x[7] = __uint_as_float(v[u].w & 0xffff0000u);
         }
 #pragma unroll
         for (int a = 0; a < MB; ++a) {
-          const double cc = cs[(c0 + u) * MB + a];
+          const acc_t cc = cs[(c0 + u) * MB + a];
 #pragma unroll
-          for (int e = 0; e < EPL; ++e) acc[a][e] = fma(cc, x[e], acc[a][e]);
+          for (int e = 0; e < EPL; ++e) {
+            if constexpr (E::SIZE == 4) acc[a][e] = fma(cc, x[e], acc[a][e]);
+            else acc[a][e] = fmaf(cc, x[e], acc[a][e]);
+          }
         }
       }
     }
@@ -1014,8 +1040,29 @@ __global__ __launch_bounds__(64) void fa_krum_kernel(const double* __restrict__ 
 
 // Y (+ a*ldy, a < m) = G A, A row-major p x m in device memory; worker-major G only.
 hipError_t fa_launch_combine_multi(const void* G, int64_t ldg, int p, int64_t n, int dtype,
-                                   const double* A, int m, float* Y, int64_t ldy, int max_blocks,
-                                   hipStream_t st) {
+                                   int layout, const double* A, int m, float* Y, int64_t ldy,
+                                   int max_blocks, hipStream_t st) {
+  if (layout == FA_ROW_MAJOR) {
+    const int ldr = (int)ldg;
+    const size_t lds = (size_t)p * 257 * sizeof(float);
+    const unsigned magic = (unsigned)((0x100000000ull + (unsigned)ldr - 1) / (unsigned)ldr);
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    for (int a0 = 0; a0 < m; a0 += FA_ROWS_MULTI) {
+      const int nc = m - a0 < FA_ROWS_MULTI ? m - a0 : FA_ROWS_MULTI;
+      if (dtype == FA_F32)
+        hipLaunchKernelGGL((fa_combine_rows_kernel<ElemF32, FA_ROWS_MULTI>), dim3((unsigned)blocks),
+                           dim3(256), lds, st, (const unsigned char*)G, ldr, p, n, A + a0, m, nc,
+                           Y + (int64_t)a0 * ldy, ldy, magic);
+      else
+        hipLaunchKernelGGL((fa_combine_rows_kernel<ElemBF16, FA_ROWS_MULTI>), dim3((unsigned)blocks),
+                           dim3(256), lds, st, (const unsigned char*)G, ldr, p, n, A + a0, m, nc,
+                           Y + (int64_t)a0 * ldy, ldy, magic);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
   constexpr int MB = 8;
   const int epl = dtype == FA_F32 ? 4 : 8;
   const int64_t ngroups = (n + epl - 1) / epl;
@@ -1028,13 +1075,9 @@ hipError_t fa_launch_combine_multi(const void* G, int64_t ldg, int p, int64_t n,
                          0, st, (const unsigned char*)G, ldg, p, n, A + a0, m, nc,
                          Y + (int64_t)a0 * ldy, ldy);
     else
-      hipLaunchKernelGGL((fa_combine_multi_kernel<ElemBF16, 4>), dim3((unsigned)blocks), dim3(256),
-                         0, st, (const unsigned char*)G, ldg, p, n, A + a0, m, nc < 4 ? nc : 4,
+      hipLaunchKernelGGL((fa_combine_multi_kernel<ElemBF16, MB>), dim3((unsigned)blocks), dim3(256),
+                         0, st, (const unsigned char*)G, ldg, p, n, A + a0, m, nc,
                          Y + (int64_t)a0 * ldy, ldy);
-    if (dtype != FA_F32 && nc > 4)
-      hipLaunchKernelGGL((fa_combine_multi_kernel<ElemBF16, 4>), dim3((unsigned)blocks), dim3(256),
-                         0, st, (const unsigned char*)G, ldg, p, n, A + a0 + 4, m, nc - 4,
-                         Y + (int64_t)(a0 + 4) * ldy, ldy);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -1499,13 +1542,21 @@ hipError_t fa_kernels_prepare(void) {
   if (e == hipSuccess) e = prepare_proj_e<ElemF32>();
   if (e == hipSuccess) e = prepare_proj_e<ElemBF16>();
   if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemF32>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemF32, 1>),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             FA_P_MAX * 257 * (int)sizeof(float));
   if (e == hipSuccess)
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemBF16>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemBF16, 1>),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             FA_P_MAX * 257 * (int)sizeof(float));
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemF32, FA_ROWS_MULTI>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, FA_P_MAX * 257 * (int)sizeof(float));
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemBF16, FA_ROWS_MULTI>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, FA_P_MAX * 257 * (int)sizeof(float));
   return e;
 }
 
@@ -1520,11 +1571,11 @@ hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int d
     int64_t blocks = (n + 255) / 256;
     if (blocks > 256 * 8) blocks = 256 * 8;
     if (dtype == FA_F32)
-      FA_LAUNCH(tm, (fa_combine_rows_kernel<ElemF32>), dim3((unsigned)blocks), dim3(256), lds, st,
-                (const unsigned char*)G, ldr, p, n, c, cstride, out, magic);
+      FA_LAUNCH(tm, (fa_combine_rows_kernel<ElemF32, 1>), dim3((unsigned)blocks), dim3(256), lds,
+                st, (const unsigned char*)G, ldr, p, n, c, cstride, 1, out, (int64_t)0, magic);
     else
-      FA_LAUNCH(tm, (fa_combine_rows_kernel<ElemBF16>), dim3((unsigned)blocks), dim3(256), lds, st,
-                (const unsigned char*)G, ldr, p, n, c, cstride, out, magic);
+      FA_LAUNCH(tm, (fa_combine_rows_kernel<ElemBF16, 1>), dim3((unsigned)blocks), dim3(256), lds,
+                st, (const unsigned char*)G, ldr, p, n, c, cstride, 1, out, (int64_t)0, magic);
     return hipGetLastError();
   }
   const int epl = dtype == FA_F32 ? 4 : 8;
