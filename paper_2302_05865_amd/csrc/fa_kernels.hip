@@ -467,10 +467,16 @@ __global__ __launch_bounds__(64 * WAVES) void fa_proj_kernel(
 }
 
 // K4 for interleaved storage (G row by row, row pitch ldr elements): a workgroup copies the
-// contiguous span of its 256 rows with coalesced 16-byte loads, scattering the elements to
-// LDS as [column][row]; then thread r adds up row r (fp64) and the workgroup writes 256
-// consecutive outputs.
+// contiguous span of its 256 rows to LDS as it is, 16 bytes per lane per load and per LDS
+// write (no decoding of rows and columns on the way); then thread r adds up row r (fp64) and
+// the workgroup writes 256 consecutive outputs.  Rows of 16 k elements would put a wavefront's
+// reads of element i on a few banks only, so the copy leaves 16 bytes free after every 256:
+// byte b of the span sits at b + 16 (b / 256).
 #define FA_ROWS_MULTI 8   // columns of a materialised basis per pass over row-major G
+__host__ __device__ inline size_t fa_rows_lds_bytes(int ldr, int es) {
+  const size_t span = (size_t)256 * ldr * es;
+  return span + (span >> 8) * 16 + 16;
+}
 // MB > 1: up to MB combinations from one pass over G (column a of the output, at out + a*ldo,
 // uses the coefficients c[i*cstride + a]): the materialised basis Y = G A of row-major storage.
 template <typename E, int MB>
@@ -478,13 +484,10 @@ __global__ __launch_bounds__(256) void fa_combine_rows_kernel(const unsigned cha
                                                               int ldr, int p, int64_t n,
                                                               const double* __restrict__ c,
                                                               int cstride, int ncols,
-                                                              float* __restrict__ out, int64_t ldo,
-                                                              unsigned magic) {
+                                                              float* __restrict__ out, int64_t ldo) {
   constexpr int EPL = E::EPL;
   constexpr int RB = 256;                  // rows per workgroup pass
-  constexpr int PITCH = RB + 1;            // LDS words per column
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  float* tile = reinterpret_cast<float*>(lds_raw);          // p * PITCH floats
+  extern __shared__ __attribute__((aligned(16))) unsigned char tile[];
   __shared__ double cs[MB][FA_P_MAX];
   for (int idx = threadIdx.x; idx < MB * FA_P_MAX; idx += 256) {
     const int a = idx / FA_P_MAX, i = idx % FA_P_MAX;
@@ -495,56 +498,52 @@ __global__ __launch_bounds__(256) void fa_combine_rows_kernel(const unsigned cha
     const int64_t row_base = blk * RB;
     const int rows_here = (int)(n - row_base < RB ? n - row_base : RB);
     const int lim = rows_here * ldr;                        // elements of this span
+    const int npieces = (lim + EPL - 1) / EPL;              // 16-byte pieces, the last one ragged
     const unsigned char* base = G + row_base * ldr * E::SIZE;
     __syncthreads();                                        // the previous pass has been read
+    // (fetching the next span into registers before the rows are added up was measured:
+    // 126 instead of 134 us at a pitch of 16 fp32 values, 140 instead of 130 at 15)
     constexpr int PCH = 4;                                  // pieces in flight per thread
-    for (int eb = (int)threadIdx.x * EPL; eb < lim; eb += 256 * EPL * PCH) {
+    for (int pb = (int)threadIdx.x; pb < npieces; pb += 256 * PCH) {
       uint4 v[PCH];
 #pragma unroll
       for (int q = 0; q < PCH; ++q) {
-        const int e0 = eb + q * 256 * EPL;
+        const int pc = pb + q * 256;
         v[q] = make_uint4(0u, 0u, 0u, 0u);
-        if (e0 + EPL <= lim) v[q] = load16_stream(base + (int64_t)e0 * E::SIZE);
-        else if (e0 < lim) v[q] = load16_guarded<E>(base, e0, lim);
+        if ((pc + 1) * EPL <= lim) v[q] = load16_stream(base + (int64_t)pc * 16);
+        else if (pc < npieces) v[q] = load16_guarded<E>(base, (int64_t)pc * EPL, lim);
       }
 #pragma unroll
       for (int q = 0; q < PCH; ++q) {
-        const int e0 = eb + q * 256 * EPL;
-        if (e0 >= lim) continue;
-        const uint32_t wds[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
-        // e0 / ldr (exact for e0 < 2^16; the multiplier of ldr = 1 would not fit 32 bits)
-        int r = ldr == 1 ? e0 : (int)__umulhi((unsigned)e0, magic);
-        int col = e0 - r * ldr;
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-          if (col < p && e0 + j < lim) {
-            float f;
-            if constexpr (E::SIZE == 4) f = __uint_as_float(wds[j]);
-            else f = bf16_bits_to_f32((wds[j >> 1] >> (16 * (j & 1))) & 0xffffu);
-            tile[col * PITCH + r] = f;
-          }
-          if (++col == ldr) { col = 0; ++r; }
-        }
+        const int pc = pb + q * 256;
+        if (pc < npieces) *reinterpret_cast<uint4*>(tile + pc * 16 + (pc >> 4) * 16) = v[q];
       }
     }
     __syncthreads();
     const int r = (int)threadIdx.x;
     if (r < rows_here) {
+      const int b0 = r * ldr * E::SIZE;                     // first byte of row r in the span
+      auto elem = [&](int i) -> double {
+        const int b = b0 + i * E::SIZE;
+        const unsigned char* at = tile + b + (b >> 8) * 16;
+        if constexpr (E::SIZE == 4) return (double)*reinterpret_cast<const float*>(at);
+        else return (double)bf16_bits_to_f32(*reinterpret_cast<const uint16_t*>(at));
+      };
       if constexpr (MB == 1) {
         double a0 = 0.0, a1 = 0.0;
         int i = 0;
         for (; i + 1 < p; i += 2) {
-          a0 = fma(cs[0][i], (double)tile[i * PITCH + r], a0);
-          a1 = fma(cs[0][i + 1], (double)tile[(i + 1) * PITCH + r], a1);
+          a0 = fma(cs[0][i], elem(i), a0);
+          a1 = fma(cs[0][i + 1], elem(i + 1), a1);
         }
-        if (i < p) a0 = fma(cs[0][i], (double)tile[i * PITCH + r], a0);
+        if (i < p) a0 = fma(cs[0][i], elem(i), a0);
         out[row_base + r] = (float)(a0 + a1);
       } else {
         double acc[MB];
 #pragma unroll
         for (int a = 0; a < MB; ++a) acc[a] = 0.0;
         for (int i = 0; i < p; ++i) {
-          const double t = (double)tile[i * PITCH + r];
+          const double t = elem(i);
 #pragma unroll
           for (int a = 0; a < MB; ++a) acc[a] = fma(cs[a][i], t, acc[a]);
         }
@@ -1044,8 +1043,7 @@ hipError_t fa_launch_combine_multi(const void* G, int64_t ldg, int p, int64_t n,
                                    int max_blocks, hipStream_t st) {
   if (layout == FA_ROW_MAJOR) {
     const int ldr = (int)ldg;
-    const size_t lds = (size_t)p * 257 * sizeof(float);
-    const unsigned magic = (unsigned)((0x100000000ull + (unsigned)ldr - 1) / (unsigned)ldr);
+    const size_t lds = fa_rows_lds_bytes(ldr, dtype == FA_F32 ? 4 : 2);
     int64_t blocks = (n + 255) / 256;
     if (blocks > 256 * 8) blocks = 256 * 8;
     for (int a0 = 0; a0 < m; a0 += FA_ROWS_MULTI) {
@@ -1053,11 +1051,11 @@ hipError_t fa_launch_combine_multi(const void* G, int64_t ldg, int p, int64_t n,
       if (dtype == FA_F32)
         hipLaunchKernelGGL((fa_combine_rows_kernel<ElemF32, FA_ROWS_MULTI>), dim3((unsigned)blocks),
                            dim3(256), lds, st, (const unsigned char*)G, ldr, p, n, A + a0, m, nc,
-                           Y + (int64_t)a0 * ldy, ldy, magic);
+                           Y + (int64_t)a0 * ldy, ldy);
       else
         hipLaunchKernelGGL((fa_combine_rows_kernel<ElemBF16, FA_ROWS_MULTI>), dim3((unsigned)blocks),
                            dim3(256), lds, st, (const unsigned char*)G, ldr, p, n, A + a0, m, nc,
-                           Y + (int64_t)a0 * ldy, ldy, magic);
+                           Y + (int64_t)a0 * ldy, ldy);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
@@ -1544,19 +1542,19 @@ hipError_t fa_kernels_prepare(void) {
   if (e == hipSuccess)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemF32, 1>),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                            FA_P_MAX * 257 * (int)sizeof(float));
+                            (int)fa_rows_lds_bytes(FA_P_MAX, 4));
   if (e == hipSuccess)
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemBF16, 1>),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                            FA_P_MAX * 257 * (int)sizeof(float));
+                            (int)fa_rows_lds_bytes(FA_P_MAX, 4));
   if (e == hipSuccess)
     e = hipFuncSetAttribute(
         reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemF32, FA_ROWS_MULTI>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, FA_P_MAX * 257 * (int)sizeof(float));
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)fa_rows_lds_bytes(FA_P_MAX, 4));
   if (e == hipSuccess)
     e = hipFuncSetAttribute(
         reinterpret_cast<const void*>(fa_combine_rows_kernel<ElemBF16, FA_ROWS_MULTI>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, FA_P_MAX * 257 * (int)sizeof(float));
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)fa_rows_lds_bytes(FA_P_MAX, 4));
   return e;
 }
 
@@ -1565,17 +1563,15 @@ hipError_t fa_launch_combine(const void* G, int64_t ldg, int p, int64_t n, int d
                              hipStream_t st, const fa_ktime* tm) {
   if (layout == FA_ROW_MAJOR) {
     const int ldr = (int)ldg;
-    const size_t lds = (size_t)p * 257 * sizeof(float);
-    // ceil(2^32 / ldr): floor(e * magic / 2^32) = e / ldr for every e < 2^16
-    const unsigned magic = (unsigned)((0x100000000ull + (unsigned)ldr - 1) / (unsigned)ldr);
+    const size_t lds = fa_rows_lds_bytes(ldr, dtype == FA_F32 ? 4 : 2);
     int64_t blocks = (n + 255) / 256;
     if (blocks > 256 * 8) blocks = 256 * 8;
     if (dtype == FA_F32)
       FA_LAUNCH(tm, (fa_combine_rows_kernel<ElemF32, 1>), dim3((unsigned)blocks), dim3(256), lds,
-                st, (const unsigned char*)G, ldr, p, n, c, cstride, 1, out, (int64_t)0, magic);
+                st, (const unsigned char*)G, ldr, p, n, c, cstride, 1, out, (int64_t)0);
     else
       FA_LAUNCH(tm, (fa_combine_rows_kernel<ElemBF16, 1>), dim3((unsigned)blocks), dim3(256), lds,
-                st, (const unsigned char*)G, ldr, p, n, c, cstride, 1, out, (int64_t)0, magic);
+                st, (const unsigned char*)G, ldr, p, n, c, cstride, 1, out, (int64_t)0);
     return hipGetLastError();
   }
   const int epl = dtype == FA_F32 ? 4 : 8;
