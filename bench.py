@@ -72,6 +72,9 @@ def main() -> int:
                     help="accumulation of the Gram pass (fa_config.gram): the library's default "
                          "(bf16 matrix core where it applies, from 2^20 rows on), fp64 "
                          "everywhere, or the bf16 matrix core wherever it applies")
+    ap.add_argument("--sets-in-flight", type=int, default=2,
+                    help="extra figure: this many independent gradient sets, one context and "
+                         "stream each, aggregated side by side (1: leave the leg out)")
     ap.add_argument("--alone", action="store_true",
                     help="also time each kernel in a back-to-back loop of its own")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -241,37 +244,44 @@ def main() -> int:
     if do_rs:
         rsteps, r_elapsed, rms = time_restream()
 
-    # ---- two independent gradient sets in flight (extra figure; `value` is the sequence above) --
+    # ---- independent gradient sets in flight (extra figure; `value` is the sequence above) ------
     # The p x p solver keeps one compute unit busy and streams nothing.  A caller that has
     # independent sets to aggregate (several models or parameter groups) can give each its own
     # context and stream, so that the streaming passes of one set run beside the solver of the
     # other.  Same kernels, same results (compared bit for bit below).
-    def time_two_sets():
-        agg2 = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, gram=args.gram)
-        aggs, outs = [agg, agg2], [out, torch.empty_like(out)]
-        streams = [torch.cuda.Stream(), torch.cuda.Stream()]      # default priority
+    def time_sets_in_flight(nsets):
+        aggs = [agg] + [FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, gram=args.gram)
+                        for _ in range(nsets - 1)]
+        outs = [out] + [torch.empty_like(out) for _ in range(nsets - 1)]
+        streams = [torch.cuda.Stream() for _ in range(nsets)]      # default priority
         refs = []
         for i in range(2):
             aggs[0].fa_aggregate(devs[i], w.m, w.lam, w.iters, 0.0, out=outs[0])
             refs.append(outs[0].clone())
         torch.cuda.synchronize()
 
-        def go(i):
-            with torch.cuda.stream(streams[i & 1]):
-                aggs[i & 1].fa_aggregate(devs[i & 1], w.m, w.lam, w.iters, 0.0, out=outs[i & 1])
-        for i in range(2 * max(1, args.warmup // 2)):
+        def go(i):      # set i % nsets works on input i % 2
+            with torch.cuda.stream(streams[i % nsets]):
+                aggs[i % nsets].fa_aggregate(devs[i & 1], w.m, w.lam, w.iters, 0.0,
+                                             out=outs[i % nsets])
+        for i in range(2 * nsets):
             go(i)
         torch.cuda.synchronize()
+        rounds = max(1, main_steps // (2 * nsets))
+        total = rounds * 2 * nsets       # every set ends on the same input it began with
         t0 = time.perf_counter()
-        for i in range(main_steps):
+        for i in range(total):
             go(i)
         torch.cuda.synchronize()
         t_elapsed = time.perf_counter() - t0
-        same = bool(torch.equal(outs[0], refs[0]) and torch.equal(outs[1], refs[1]))
-        agg2.close()
-        return t_elapsed, same
+        same = all(bool(torch.equal(outs[k], refs[(total - nsets + k) & 1])) for k in range(nsets))
+        for a in aggs[1:]:
+            a.close()
+        return total, t_elapsed, same
 
-    two_sets = time_two_sets() if (do_main and main_steps >= 2) else None
+    sets = None
+    if do_main and args.sets_in_flight > 1 and main_steps >= 2 * args.sets_in_flight:
+        sets = time_sets_in_flight(args.sets_in_flight)
 
     # leave the result of the seed-0 set in `out` / info for the parity check below
     counter[0] = 0
@@ -371,15 +381,16 @@ def main() -> int:
         "step": step,
         "hbm_gbs": {"gram": gram_gbs, "combine": comb_gbs, "whole_step": whole_gbs},
     }
-    if two_sets is not None:
-        t_elapsed, same = two_sets
-        result["two_sets_in_flight"] = {
-            "aggregations_per_s": main_steps / t_elapsed,
-            "ms_per_aggregation": 1e3 * t_elapsed / main_steps, "streams": 2,
-            "GB/s": (gram_bytes + comb_bytes) / (t_elapsed / main_steps) / 1e9,
-            "hbm_frac": (gram_bytes + comb_bytes) / (t_elapsed / main_steps) / 1e9 / HBM_PEAK_GBS,
+    if sets is not None:
+        total, t_elapsed, same = sets
+        result["sets_in_flight"] = {
+            "sets": args.sets_in_flight, "aggregations": total,
+            "aggregations_per_s": total / t_elapsed,
+            "ms_per_aggregation": 1e3 * t_elapsed / total,
+            "GB/s": (gram_bytes + comb_bytes) / (t_elapsed / total) / 1e9,
+            "hbm_frac": (gram_bytes + comb_bytes) / (t_elapsed / total) / 1e9 / HBM_PEAK_GBS,
             "bitwise_equal_to_sequence": same,
-            "note": "two independent gradient sets, one context and stream each; not `value`"}
+            "note": "independent gradient sets, one context and stream each; not `value`"}
     if do_rs:
         result["restream"] = restream
     if not do_main:
