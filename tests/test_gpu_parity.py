@@ -908,3 +908,99 @@ def test_two_contexts_on_two_streams_give_the_results_of_the_sequence(name, n):
     finally:
         for a in aggs:
             a.close()
+
+
+# ---- random problems through every entry point and option -----------------------------------------
+_ENTRY_KINDS = ["bf16", "row_major", "row_major_bf16", "exponent", "restream", "static", "arrival",
+                "krum", "grouped", "stop_rule"]
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_problems_every_entry_point(seed):
+    """Shapes, m, lambda, solve counts, outliers drawn at random; the entry point or option under
+    test cycles with the seed.  Each result against the oracle's routine for that entry point."""
+    from paper_2302_05865_amd import fa_aggregate_static
+    rng = np.random.default_rng(70_000 + seed)
+    kind = _ENTRY_KINDS[seed % len(_ENTRY_KINDS)]
+    p = int(rng.integers(2, 65))
+    m = int(rng.integers(1, p + 1))
+    lam = float(rng.choice([0.0, 0.3, 1.0, 4.0]))
+    iters = int(rng.integers(1, 13))
+    n = int(rng.integers(p + 1, 5000))
+    announce("random entry", seed, kind, p, m, lam, iters, n)
+    mu = rng.standard_normal(n)
+    G32 = (mu[None, :] * rng.uniform(0.2, 2.0, p)[:, None] +
+           rng.uniform(0.05, 1.5) * rng.standard_normal((p, n))).astype(np.float32)
+    for b in rng.choice(p, size=int(rng.integers(0, max(1, p // 4) + 1)), replace=False):
+        G32[b] = (-4.0 * mu if rng.random() < 0.5 else 30.0 * rng.standard_normal(n)).astype(np.float32)
+    bf = kind in ("bf16", "row_major_bf16") or (kind in ("static", "arrival", "krum") and rng.random() < 0.4)
+    Gw = si.f32_to_bf16_bits(G32.reshape(-1)).reshape(p, n) if bf else G32
+    dt = "bf16" if bf else "f32"
+    info = None
+    if kind in ("bf16", "stop_rule"):
+        tol = 0.0 if kind == "bf16" else float(rng.choice([1e-3, 1e-5]))
+        ref = fa_scaled(Gw, m, lam, iters, tol)
+        agg = FlagAggregator(n_max=n, p_max=p, dtype=dt)
+        out = agg.fa_aggregate(to_device(Gw), m, lam, iters, tol)
+        info = agg.fa_get_info()
+        assert info.iters_done == ref["iters_done"]
+    elif kind in ("row_major", "row_major_bf16"):
+        es = 2 if bf else 4
+        pitch = ((p * es + 15) // 16) * 16 // es
+        ref = fa_scaled(Gw, m, lam, iters, 0.0)
+        agg = FlagAggregator(n_max=n, p_max=p, dtype=dt, layout="row_major")
+        out = agg.fa_aggregate(_rows_device(Gw, pitch), m, lam, iters, 0.0)
+        info = agg.fa_get_info()
+    elif kind == "exponent":
+        a = float(rng.choice([1.0, 1.5, 3.0, 6.0]))
+        ref = fa_scaled(Gw, m, lam, iters, 0.0, a=a)
+        agg = FlagAggregator(n_max=n, p_max=p, exponent_a=a)
+        out = agg.fa_aggregate(to_device(Gw), m, lam, iters, 0.0)
+        info = agg.fa_get_info()
+    elif kind == "restream":
+        ref = fa_scaled(Gw, m, lam, iters, 0.0)
+        agg = FlagAggregator(n_max=n, p_max=p)
+        out = agg.fa_aggregate_restream(to_device(Gw), m, lam, iters)
+        info = agg.fa_get_info()
+    elif kind == "static":
+        agg = None
+        ref = fa_scaled(Gw, m, lam, iters, 0.0)
+        out = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        fa_aggregate_static(to_device(Gw), m, lam, iters, 0.0, out)
+    elif kind == "arrival":
+        ref = fa_scaled(Gw, m, lam, iters, 0.0)
+        agg = FlagAggregator(n_max=n, p_max=p, dtype=dt)
+        full, buf = to_device(Gw), to_device(np.zeros_like(Gw))
+        agg.fa_gram_begin(p, n)
+        for i in rng.permutation(p):
+            buf[i] = full[i]
+            agg.fa_gram_update(buf, int(i))
+        out = agg.fa_aggregate_arrived(buf, m, lam, iters, 0.0)
+        info = agg.fa_get_info()
+    elif kind == "krum":
+        f = min(int(rng.integers(0, max(1, p - 2))), max(p - 3, 0))
+        q = int(rng.integers(1, p + 1))
+        if p - f - 2 < 1:
+            pytest.skip("Multi-Krum needs p - f - 2 >= 1")
+        ref = multi_krum(as_f64_matrix(Gw), f, q)
+        agg = FlagAggregator(n_max=n, p_max=p, dtype=dt)
+        out, scores, sel = agg.fa_multikrum(to_device(Gw), f, q)
+        sc = np.sort(ref["scores"])
+        if q == p or (sc[q] - sc[q - 1]) > 1e-9 * sc[-1]:      # no near-tie at the cut
+            assert np.array_equal(sel, ref["selected"])
+        else:
+            ref = None
+    else:   # grouped
+        nw = int(rng.integers(1, min(p, 8) + 1))
+        cuts = np.sort(rng.choice(np.arange(1, p), size=nw - 1, replace=False)) if nw > 1 else []
+        sizes = np.diff(np.concatenate([[0], cuts, [p]])).astype(int).tolist()
+        ref = fa_literal_grouped(as_f64_matrix(Gw), sizes, m, lam, iters, 0.0)
+        agg = FlagAggregator(n_max=n, p_max=p)
+        out = agg.fa_aggregate_grouped(to_device(Gw), sizes, m, lam, iters, 0.0)
+    if ref is not None:
+        assert rel_l2(out.cpu().numpy().astype(np.float64), ref["out"]) <= GATE
+        if info is not None:
+            assert info.status == 0
+            assert projector_difference(info.A, ref["A"], ref["R"]) <= GATE
+    if agg is not None:
+        agg.close()
