@@ -95,8 +95,8 @@ typedef struct {
                          D_ij = 0 and its term is dropped; default 1e-12 */
   double exponent_a;  /* the constant a >= 1 of the Taylor step in Sec. 2.2 ("Step 2"): every
                          term of the objective is (1 - v)^(1/a).  Default 2 = the Flag
-                         Aggregator's square roots (Eq. 5).  Other values run on the any-p
-                         Jacobi kernel (slower p x p part, same passes over G). */
+                         Aggregator's square roots (Eq. 5).  Every p x p solver takes other
+                         values (powers in place of the square roots; same passes over G). */
   int layout;         /* fa_layout of every G this context sees; default FA_WORKER_MAJOR */
   int solver;         /* fa_solver: which p x p solver runs the IRLS; default FA_SOLVER_AUTO */
   int wide_spin_budget; /* 16 < p <= 64 matrix-core solver: how many times a wavefront may poll

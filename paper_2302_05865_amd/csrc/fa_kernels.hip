@@ -1037,7 +1037,8 @@ __global__ __launch_bounds__(64) void fa_krum_kernel(const double* __restrict__ 
   }
 }
 
-// Y (+ a*ldy, a < m) = G A, A row-major p x m in device memory; worker-major G only.
+// Y (+ a*ldy, a < m) = G A, A row-major p x m in device memory; eight columns per pass over G
+// in either layout.
 hipError_t fa_launch_combine_multi(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int layout, const double* A, int m, float* Y, int64_t ldy,
                                    int max_blocks, hipStream_t st) {
