@@ -224,25 +224,39 @@ fa_status fa_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n, in
  * The Gram pass spread over the arrival of the gradients (Alg. 1: in every round the parameter
  * server receives the gradients of the p workers; they come in one after another, and the
  * aggregation step need not wait for the last one to start on S1).
- *   fa_gram_begin   starts a round of p gradients of n elements: nothing has arrived.
+ *   fa_gram_begin   starts a round of p gradients of n elements: nothing has arrived, K = 0.
  *   fa_gram_update  gradient i is now in its place in G (worker-major storage as for
  *                   fa_aggregate: element k at G + (i*ldg + k) * elem_size).  One pass over
  *                   gradient i and the gradients that arrived before it extends K by row and
  *                   column i: K_ij = g_i . g_j, exact products added in fp64 (as accurate as the
  *                   fp64 Gram pass).  The places of gradients that have not arrived are not
  *                   read.  Asynchronous on the context's stream; a gradient may be announced
- *                   once per round, in any order.
- *   fa_aggregate_arrived  once all p have arrived: the rest of fa_aggregate (S3-S6: p x p IRLS
- *                   on the K built so far, then out = G c), same arguments and results; the
- *                   Gram pass itself is not run again.  FA_ERR_ARG while a gradient is missing.
- * When the last gradient lands, only its own row of K is left to do: a pass that reads what the
- * one-shot Gram pass reads, but does p multiply-adds per coordinate instead of p (p + 1) / 2
- * matrix-core ones.  In total the updates read p (p + 1) / 2 gradients instead of p: the price
- * of starting early, paid while the server would otherwise wait for stragglers.
+ *                   once per round, in any order.  Short for fa_gram_update_rows(i, 0, n).
+ *   fa_gram_update_rows  the same for a gradient that lands piece by piece: elements
+ *                   [row0, row0 + nrows) of gradient i are now in place.  One pass over those
+ *                   rows of gradient i and of every gradient that already holds them adds their
+ *                   share to row and column i of K (a pair's share of a piece is added when the
+ *                   later of its two copies lands).  The pieces of one gradient are announced
+ *                   in order (row0 = the end of the previous piece, 0 first); a piece starts
+ *                   on a 16-byte boundary of the gradient (row0 * elem_size a multiple of 16);
+ *                   all gradients are cut at the same places: FA_ERR_ARG if another gradient's
+ *                   landed part ends inside the piece.  K is the fp64 Gram matrix to rounding
+ *                   whatever the order of the pieces; its last bits depend on that order.
+ *   fa_aggregate_arrived  once all p have arrived completely: the rest of fa_aggregate (S3-S6:
+ *                   p x p IRLS on the K built so far, then out = G c), same arguments and
+ *                   results; the Gram pass itself is not run again.  FA_ERR_ARG while anything
+ *                   is missing.
+ * When the last gradient lands whole, its own row of K is still to do: a pass that reads what
+ * the one-shot Gram pass reads.  When it lands in pieces, only its last piece is: after the last
+ * byte the server is a pass over (piece) x p elements away from the p x p solve, instead of a
+ * pass over all of G.  In total the updates read p (p + 1) / 2 gradients instead of p: the price
+ * of starting early, paid while the server would otherwise wait for the network.
  * Worker-major contexts only (a gradient arrives as one contiguous vector).
  */
 fa_status fa_gram_begin(fa_ctx* ctx, int p, int64_t n);
 fa_status fa_gram_update(fa_ctx* ctx, const void* G, int64_t ldg, int i);
+fa_status fa_gram_update_rows(fa_ctx* ctx, const void* G, int64_t ldg, int i, int64_t row0,
+                              int64_t nrows);
 fa_status fa_aggregate_arrived(fa_ctx* ctx, const void* G, int64_t ldg, int m, double lambda,
                                int iters, double tol, float* out);
 

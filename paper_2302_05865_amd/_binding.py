@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "fa_get_info", "fa_gram", "fa_gram_async", "fa_irls", "fa_combine", "fa_basis", "fa_check_basis", "fa_aggregate_grouped", "fa_multikrum",
     "fa_set_profiling",
     "fa_get_timings", "fa_enqueue_kernel", "fa_aggregate_restream", "fa_get_restream_info",
-    "fa_status_string", "fa_version", "fa_aggregate_static", "fa_gram_begin", "fa_gram_update",
+    "fa_status_string", "fa_version", "fa_aggregate_static", "fa_gram_begin", "fa_gram_update", "fa_gram_update_rows",
     "fa_aggregate_arrived",
 )
 
@@ -97,6 +97,8 @@ def load_library() -> ctypes.CDLL:
     lib.fa_gram_begin.restype = i32
     lib.fa_gram_update.argtypes = [vp, vp, i64, i32]
     lib.fa_gram_update.restype = i32
+    lib.fa_gram_update_rows.argtypes = [vp, vp, i64, i32, i64, i64]
+    lib.fa_gram_update_rows.restype = i32
     lib.fa_aggregate_arrived.argtypes = [vp, vp, i64, i32, dbl, i32, dbl, vp]
     lib.fa_aggregate_arrived.restype = i32
     lib.fa_status_string.argtypes = [i32]
@@ -312,6 +314,13 @@ class FlagAggregator:
         ptr, ldg, p, n = self._matrix(G)
         self._use_current_stream()
         _check(self._lib.fa_gram_update(self._ctx, ptr, ldg, int(i)), "fa_gram_update")
+
+    def fa_gram_update_rows(self, G, i: int, row0: int, nrows: int) -> None:
+        """Elements ``[row0, row0 + nrows)`` of gradient ``i`` have arrived in ``G``."""
+        ptr, ldg, p, n = self._matrix(G)
+        self._use_current_stream()
+        _check(self._lib.fa_gram_update_rows(self._ctx, ptr, ldg, int(i), int(row0), int(nrows)),
+               "fa_gram_update_rows")
 
     def fa_aggregate_arrived(self, G, m: int, lam: float, iters: int, tol: float, out=None):
         ptr, ldg, p, n = self._matrix(G)

@@ -38,7 +38,8 @@ struct fa_ctx {
   int last_nparts;    // partial Grams written by the last Gram pass
   int arr_p;          // fa_gram_begin: gradients expected this round (0: no round open)
   int64_t arr_n;
-  uint64_t arrived;   // bit j: gradient j has been announced by fa_gram_update
+  uint64_t arrived;   // bit j: gradient j is complete
+  int64_t arr_rows[FA_P_MAX];   // rows of gradient j announced so far (a prefix)
 };
 
 static int elem_size(int dtype) { return dtype == FA_F32 ? 4 : 2; }
@@ -435,24 +436,45 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
 extern "C" fa_status fa_gram_begin(fa_ctx* c, int p, int64_t n) {
   if (!c || p < 1 || p > c->cfg.p_max || n < 1 || n > c->cfg.n_max) return FA_ERR_ARG;
   if (c->cfg.layout != FA_WORKER_MAJOR) return FA_ERR_ARG;
+  if (fa_launch_zero(c->Kd, FA_P_MAX * FA_P_MAX, c->stream) != hipSuccess) return FA_ERR_DEVICE;
   c->arr_p = p;
   c->arr_n = n;
   c->arrived = 0;
+  for (int j = 0; j < FA_P_MAX; ++j) c->arr_rows[j] = 0;
+  return FA_OK;
+}
+
+extern "C" fa_status fa_gram_update_rows(fa_ctx* c, const void* G, int64_t ldg, int i,
+                                         int64_t row0, int64_t nrows) {
+  if (!c || c->arr_p < 1 || i < 0 || i >= c->arr_p) return FA_ERR_ARG;
+  const int64_t n = c->arr_n, row1 = row0 + nrows;
+  const int es = elem_size(c->cfg.dtype);
+  // the rows of a gradient are announced in order, each once; a piece starts on a 16-byte
+  // boundary of the gradient
+  if (nrows < 1 || row0 != c->arr_rows[i] || row1 > n || (row0 * es) % 16 != 0) return FA_ERR_ARG;
+  if (!check_matrix_args(c, G, ldg, c->arr_p, n)) return FA_ERR_ARG;
+  // the other gradients hold these rows entirely or not at all (same piece boundaries for all)
+  uint64_t resident = 0;
+  for (int j = 0; j < c->arr_p; ++j) {
+    if (j == i) continue;
+    if (c->arr_rows[j] >= row1) resident |= (uint64_t)1 << j;
+    else if (c->arr_rows[j] > row0) return FA_ERR_ARG;
+  }
+  // partial rows go to the Gram pass's partial buffer (at least 256 doubles per compute unit)
+  int max_parts = c->gram_max_blocks * 256 / FA_ROW_JB;
+  if (max_parts > 1024) max_parts = 1024;
+  const unsigned char* first = reinterpret_cast<const unsigned char*>(G) + row0 * es;
+  if (fa_launch_gram_row(first, ldg, c->arr_p, nrows, c->cfg.dtype, i, resident, c->partials,
+                         max_parts, c->Kd, c->stream) != hipSuccess)
+    return FA_ERR_DEVICE;
+  c->arr_rows[i] = row1;
+  if (row1 == n) c->arrived |= (uint64_t)1 << i;
   return FA_OK;
 }
 
 extern "C" fa_status fa_gram_update(fa_ctx* c, const void* G, int64_t ldg, int i) {
-  if (!c || c->arr_p < 1 || i < 0 || i >= c->arr_p) return FA_ERR_ARG;
-  if ((c->arrived >> i) & 1u) return FA_ERR_ARG;              // announced twice
-  if (!check_matrix_args(c, G, ldg, c->arr_p, c->arr_n)) return FA_ERR_ARG;
-  // partial rows go to the Gram pass's partial buffer (at least 256 doubles per compute unit)
-  int max_parts = c->gram_max_blocks * 256 / FA_ROW_JB;
-  if (max_parts > 1024) max_parts = 1024;
-  if (fa_launch_gram_row(G, ldg, c->arr_p, c->arr_n, c->cfg.dtype, i, c->arrived, c->partials,
-                         max_parts, c->Kd, c->stream) != hipSuccess)
-    return FA_ERR_DEVICE;
-  c->arrived |= (uint64_t)1 << i;
-  return FA_OK;
+  if (!c || c->arr_p < 1) return FA_ERR_ARG;
+  return fa_gram_update_rows(c, G, ldg, i, 0, c->arr_n);     // the whole gradient at once
 }
 
 extern "C" fa_status fa_aggregate_arrived(fa_ctx* c, const void* G, int64_t ldg, int m,

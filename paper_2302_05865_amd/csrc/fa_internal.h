@@ -43,13 +43,15 @@ hipError_t fa_launch_gram_lp_partials(const void* G, int64_t ldg, int p, int64_t
                                       int max_blocks, double* partials, int* nparts,
                                       hipStream_t st, const fa_ktime* tm);
 hipError_t fa_gram_lp_prepare(void);
-// Row and column i of K from one pass over gradient i and the resident gradients (bit j of
-// `resident` set: gradient j is in place; i itself is always included): K[i][j] = K[j][i] =
-// g_i . g_j in fp64.  partials: max_parts * FA_ROW_JB doubles of scratch.  Worker-major G.
+// Row and column i of K from one pass over n rows of gradient i and of the gradients that
+// hold those rows too (bit j of `resident` set; i itself is always included): K[i][j] and
+// K[j][i] += g_i . g_j over those rows, in fp64.  G points at the first of the rows in gradient
+// 0.  partials: max_parts * FA_ROW_JB doubles of scratch.  Worker-major G.
 #define FA_ROW_JB 16          // gradients paired with gradient i in one pass
 hipError_t fa_launch_gram_row(const void* G, int64_t ldg, int p, int64_t n, int dtype, int i,
                               uint64_t resident, double* partials, int max_parts, double* Kd,
                               hipStream_t st);
+hipError_t fa_launch_zero(double* dst, int count, hipStream_t st);
 // K2: their fixed-order sum into Kd (p*p doubles, row-major).  colscale (device, p doubles,
 // may be null): entry (i, j) is multiplied by colscale[i] colscale[j], i.e. the result is
 // diag(u) K diag(u), the Gram matrix of the columns scaled by u.

@@ -861,7 +861,7 @@ __global__ __launch_bounds__(256) void fa_gram_row_kernel(const unsigned char* _
 }
 
 // Fixed-order sum of the partial rows (four interleaved strands per entry, then a fixed
-// tree) into row and column i of K (row-major p x p).
+// tree), added to row and column i of K (row-major p x p; zero when the round opens).
 __global__ __launch_bounds__(64 * FA_ROW_JB) void fa_gram_row_reduce_kernel(
     const double* __restrict__ partials, int nparts, fa_row_cols cols, int nj, int i, int p,
     double* __restrict__ K) {
@@ -880,9 +880,19 @@ __global__ __launch_bounds__(64 * FA_ROW_JB) void fa_gram_row_reduce_kernel(
 #pragma unroll
       for (int k = 0; k < w; ++k) t[k] += t[k + w];
     const int j = cols.idx[u];
-    K[i * p + j] = t[0];
-    K[j * p + i] = t[0];
+    const double v = K[i * p + j] + t[0];     // K_ij and K_ji see the same addends in the same order
+    K[i * p + j] = v;
+    K[j * p + i] = v;
   }
+}
+
+__global__ __launch_bounds__(256) void fa_zero_kernel(double* __restrict__ dst, int count) {
+  for (int k = blockIdx.x * 256 + threadIdx.x; k < count; k += gridDim.x * 256) dst[k] = 0.0;
+}
+
+hipError_t fa_launch_zero(double* dst, int count, hipStream_t st) {
+  hipLaunchKernelGGL(fa_zero_kernel, dim3((count + 255) / 256), dim3(256), 0, st, dst, count);
+  return hipGetLastError();
 }
 
 hipError_t fa_launch_gram_row(const void* G, int64_t ldg, int p, int64_t n, int dtype, int i,

@@ -209,6 +209,76 @@ def test_gram_built_on_arrival_equals_the_one_shot_path(name, n):
     agg.close()
 
 
+@pytest.mark.parametrize("name,n,pieces", [("cfg2", 100_003, 5), ("cfg4", 60_001, 3),
+                                          ("cfg5", 20_011, 4), ("cfg1", 33_333, 16)])
+def test_gram_built_from_pieces_of_gradients(name, n, pieces):
+    """fa_gram_update_rows: every gradient lands in `pieces` pieces (same cuts for all, each on a
+    16-byte boundary), the pieces of different gradients interleaved at random; places that have
+    not landed hold NaN.  K ends up the fp64 Gram matrix and the aggregate the oracle's."""
+    announce("gram from pieces", name, n, pieces)
+    w = si.WORKLOADS[name].with_n(n)
+    Gw, _ = si.make_inputs(w, 4)
+    full = to_device(Gw)
+    nan = np.full(Gw.shape, 0x7FC0, np.uint16) if Gw.dtype == np.uint16 else \
+        np.full(Gw.shape, np.nan, np.float32)
+    buf = to_device(nan)
+    cuts = [0] + [int(round(n * k / pieces / 8)) * 8 for k in range(1, pieces)] + [n]
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, gram="fp64")
+    agg.fa_gram_begin(w.p, w.n)
+    rng = np.random.default_rng(9)
+    nxt = np.zeros(w.p, dtype=int)              # next piece of each gradient
+    events = []
+    while (nxt < pieces).any():
+        i = int(rng.choice(np.flatnonzero(nxt < pieces)))
+        events.append((i, int(nxt[i])))
+        nxt[i] += 1
+    for i, c in events:
+        r0, r1 = cuts[c], cuts[c + 1]
+        buf[i, r0:r1] = full[i, r0:r1]
+        agg.fa_gram_update_rows(buf, i, r0, r1 - r0)
+    out = agg.fa_aggregate_arrived(buf, w.m, w.lam, w.iters, 0.0)
+    info = agg.fa_get_info()
+    G = as_f64_matrix(Gw)
+    Kref = G.T @ G
+    scale = np.sqrt(np.outer(np.diag(Kref), np.diag(Kref)))
+    assert info.status == 0
+    assert np.max(np.abs(info.K - Kref) / scale) <= 1e-12
+    assert np.array_equal(info.K, info.K.T)
+    ref = fa_scaled(Gw, w.m, w.lam, w.iters, 0.0)
+    assert rel_l2(out.cpu().numpy().astype(np.float64), ref["out"]) <= GATE
+    assert projector_difference(info.A, ref["A"], ref["R"]) <= GATE
+    agg.close()
+
+
+def test_gram_from_pieces_argument_errors():
+    announce("gram from pieces: errors")
+    dev = to_device(si.random_dense(3, 1000, seed=8))
+    agg_f32 = FlagAggregator(n_max=1000, p_max=3)
+    agg_f32.fa_gram_begin(3, 1000)
+    with pytest.raises(FaError):
+        agg_f32.fa_gram_update_rows(dev, 0, 8, 100)          # does not start where the last piece ended
+    agg_f32.fa_gram_update_rows(dev, 0, 0, 400)
+    with pytest.raises(FaError):
+        agg_f32.fa_gram_update_rows(dev, 0, 0, 400)          # the same piece twice
+    with pytest.raises(FaError):
+        agg_f32.fa_gram_update_rows(dev, 1, 0, 600)          # gradient 0 ends inside this piece
+    with pytest.raises(FaError):
+        agg_f32.fa_gram_update_rows(dev, 0, 400, 601)        # past the end
+    agg_f32.fa_gram_update_rows(dev, 1, 0, 400)
+    agg_f32.fa_gram_update_rows(dev, 1, 400, 101)            # may end anywhere ...
+    with pytest.raises(FaError):
+        agg_f32.fa_gram_update_rows(dev, 1, 501, 100)        # ... but the next piece starts off a 16-byte boundary
+    with pytest.raises(FaError):
+        agg_f32.fa_aggregate_arrived(dev, 1, 0.0, 1, 0.0)    # nothing is complete yet
+    agg_f32.fa_gram_begin(3, 1000)                           # a new round forgets the old one
+    for i in range(3):
+        agg_f32.fa_gram_update(dev, i)
+    a = agg_f32.fa_aggregate_arrived(dev, 1, 0.0, 2, 0.0)
+    b = agg_f32.fa_aggregate(dev, 1, 0.0, 2, 0.0)
+    assert rel_l2(a.cpu().numpy().astype(np.float64), b.cpu().numpy().astype(np.float64)) <= 1e-6
+    agg_f32.close()
+
+
 def test_gram_on_arrival_argument_errors(agg_f32):
     announce("gram on arrival: errors")
     dev = to_device(si.random_dense(5, 1000, seed=8))
