@@ -314,9 +314,9 @@ fa_status fa_check_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t
  * to each of its kernel dispatches (the events carry the kernel's own timestamps; nothing
  * extra is enqueued between the kernels); fa_get_timings synchronises and returns the last
  * call's kernel durations in milliseconds: ms[0] Gram pass, ms[1] partial reduction,
- * ms[2] p x p IRLS, ms[3] aggregate pass.  ms[2] covers the first p x p kernel only: when the
- * matrix-core solver of 16 < p <= 64 gives a solve up, the Jacobi kernel that redoes it (a
- * separate launch, which otherwise returns at once) is not in it.
+ * ms[2] p x p IRLS, ms[3] aggregate pass.  For 16 < p <= 64 the p x p part is two launches (the
+ * matrix-core solver, then the Jacobi kernel that redoes a solve the first gave up and
+ * otherwise returns at once); ms[2] runs from the begin of the first to the end of the second.
  */
 fa_status fa_set_profiling(fa_ctx* ctx, int enabled);
 fa_status fa_get_timings(fa_ctx* ctx, float ms[4]);

@@ -1458,14 +1458,17 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
                             info_d,
                             gws + FA_GWS_MLAST_OFF, solver == 0 ? 1 : 0, rs, st, tm);
   int retry_only = 0;
+  fa_ktime first = {nullptr, nullptr}, second = {nullptr, nullptr};
   if (p > 16 && solver == 0) {
+    // timing, if asked for, spans both launches: begin of the first, end of the second
+    if (tm) { first.start = tm->start; second.stop = tm->stop; }
     hipError_t e = fa_launch_irls64(Kd, p, m, lambda, iters, tol, delta, exponent_a, rank_tol,
                                     pair_tol, cd,
                                     info_d, gws + FA_GWS_GENERIC, gws + FA_GWS_MLAST_OFF,
-                                    spin_budget, rs, st, tm);
+                                    spin_budget, rs, st, tm ? &first : nullptr);
     if (e != hipSuccess) return e;
     retry_only = 1;   // the Jacobi kernel below runs only if the one above gave up
-    tm = nullptr;
+    tm = tm ? &second : nullptr;
   }
   fa_irls_args ar;
   ar.p = p; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
