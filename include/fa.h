@@ -150,7 +150,10 @@ fa_status fa_set_stream(fa_ctx* ctx, void* stream);
  *   iters  number of weighted-PCA solves including the first, uniform one, 1..FA_ITERS_MAX
  *   tol    stop when successive objective values differ by less than tol; 0 = never
  *   out    device, n floats, caller-owned; receives d
- * Asynchronous on the context's stream; allocates nothing.  Argument errors
+ * Asynchronous on the context's stream; allocates nothing.  With profiling off the call is
+ * kernel launches only (no copies, no memset nodes), so it may be recorded into a HIP graph
+ * on a capturing stream; the same holds for fa_aggregate_restream and fa_aggregate_static
+ * (whose first call on a device, the set-up, must come before the capture).  Argument errors
  * (including p > p_max, n > n_max, misaligned G/ldg, NULL pointers) return
  * FA_ERR_ARG synchronously.  Data errors are found on the device and reported by
  * fa_get_info: non-finite input fills out with NaN, all-zero input with zeros.

@@ -331,7 +331,12 @@ extern "C" fa_status fa_aggregate_restream(fa_ctx* c, const void* G, int64_t ldg
   const bool prof = c->profiling != 0;
   c->ev_recorded = 0;
   c->ev_recorded_r = 0;
-  if (hipMemsetAsync(c->rs_d, 0, sizeof(fa_resume), st) != hipSuccess) return FA_ERR_DEVICE;
+  // start from uniform weights: the state cleared by a kernel (a fill kernel, not a memset
+  // node, so that the sequence may be recorded into a graph)
+  static_assert(sizeof(fa_resume) % sizeof(double) == 0, "fa_resume is cleared as doubles");
+  if (fa_launch_zero(reinterpret_cast<double*>(c->rs_d), (int)(sizeof(fa_resume) / sizeof(double)),
+                     st) != hipSuccess)
+    return FA_ERR_DEVICE;
   const double* A_d = reinterpret_cast<const double*>(reinterpret_cast<const char*>(c->info_d) +
                                                       offsetof(fa_info, A));
   const double* u_d = reinterpret_cast<const double*>(reinterpret_cast<const char*>(c->rs_d) +

@@ -61,7 +61,7 @@ hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, doub
 // K3: p x p solver.  Kd p*p doubles; cd p doubles out; info_d device fa_info; gws global
 // workspace of FA_GWS_DOUBLES doubles.  solver: 0 = default (matrix-core purification, with
 // the Jacobi solvers as fallback), 1 = p <= 16 Jacobi path, 2 = any-p Jacobi kernel.
-// exponent_a other than 2 always runs on the any-p kernel.
+// Every solver takes any exponent_a > 1 (the constant a of Sec. 2.2 Step 2).
 // spin_budget: see fa_config.wide_spin_budget.
 // rs (device, may be null): continue the IRLS from the weights left there by an earlier
 // launch and leave the next ones (see fa_resume.h).

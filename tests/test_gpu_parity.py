@@ -980,6 +980,62 @@ def test_two_contexts_on_two_streams_give_the_results_of_the_sequence(name, n):
             a.close()
 
 
+# ---- the enqueue-only entry points inside a HIP graph ------------------------------------------
+@pytest.mark.parametrize("name,n,entry", [("cfg2", 300_007, "aggregate"),
+                                          ("cfg4", 200_003, "aggregate"),
+                                          ("cfg5", 60_013, "aggregate"),
+                                          ("cfg2", 100_003, "restream"),
+                                          ("cfg4", 100_003, "static")])
+def test_enqueue_only_entry_points_recorded_into_a_graph(name, n, entry):
+    """fa_aggregate, fa_aggregate_restream and fa_aggregate_static only launch kernels (what
+    they clear, a fill kernel clears), so a caller may record them into a HIP graph.  The graph
+    is replayed four times on changing inputs, with eager calls on the same workspace and
+    synchronisations between the replays; every replay is bit for bit the eager result."""
+    from paper_2302_05865_amd import fa_aggregate_static
+    w = si.WORKLOADS[name].with_n(n)
+    hosts = [si.make_inputs(w, seed)[0] for seed in (0, 1)]
+    devs = [to_device(h) for h in hosts]
+    Gin = to_device(hosts[0])                        # the graph's input buffer
+    iters = min(w.iters, 4) if entry == "restream" else w.iters
+    agg = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype)
+
+    def run(G, out):
+        if entry == "aggregate":
+            agg.fa_aggregate(G, w.m, w.lam, iters, 0.0, out=out)
+        elif entry == "restream":
+            agg.fa_aggregate_restream(G, w.m, w.lam, iters, out=out)
+        else:
+            fa_aggregate_static(G, w.m, w.lam, iters, 0.0, out)
+
+    try:
+        refs = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(2)]
+        for i in range(2):
+            run(devs[i], refs[i])
+        torch.cuda.synchronize()
+        assert agg.fa_get_info().status == 0 or entry == "static"
+        out = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        other = torch.empty_like(out)
+        announce(f"graph capture {entry} {name} n={n}")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run(Gin, out)
+        torch.cuda.synchronize()
+        for rep in range(4):
+            k = rep & 1
+            out.fill_(float("nan"))
+            other.fill_(float("nan"))
+            Gin.copy_(devs[k])
+            announce(f"graph replay {rep}")
+            graph.replay()
+            run(devs[1 - k], other)                  # eager work on the same workspace
+            torch.cuda.synchronize()
+            assert torch.equal(out, refs[k]), rep
+            assert torch.equal(other, refs[1 - k]), rep
+        del graph
+    finally:
+        agg.close()
+
+
 # ---- random problems through every entry point and option -----------------------------------------
 _ENTRY_KINDS = ["bf16", "row_major", "row_major_bf16", "exponent", "restream", "static", "arrival",
                 "krum", "grouped", "stop_rule"]
