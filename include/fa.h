@@ -60,7 +60,7 @@ typedef enum { FA_WORKER_MAJOR = 0, FA_ROW_MAJOR = 1 } fa_layout;
  * FA_SOLVER_AUTO: projector by matrix-core purification, no eigen-decomposition; a solve it
  *   cannot finish (eigenvalues m and m+1 tied) is redone by a Jacobi solver.
  * FA_SOLVER_JACOBI16: the p <= 16 Jacobi eigensolver (p > 16: as FA_SOLVER_AUTO).
- * FA_SOLVER_JACOBI: the any-p Jacobi eigensolver (always used for fa_aggregate_grouped).
+ * FA_SOLVER_JACOBI: the any-p Jacobi eigensolver.
  * Every solver knows exponent_a. */
 typedef enum { FA_SOLVER_AUTO = 0, FA_SOLVER_JACOBI16 = 1, FA_SOLVER_JACOBI = 2 } fa_solver;
 
@@ -273,8 +273,9 @@ fa_status fa_aggregate_arrived(fa_ctx* ctx, const void* G, int64_t ldg, int m, d
  * once: out = (1/nworkers) Y Y^T sum_i mean_of_columns(g_i).  With every size 1 this is
  * fa_aggregate.  The other arguments, the layouts and the errors are fa_aggregate's (q takes
  * the place of p, also in m <= q and q <= p_max); fa_get_info then reports per column (v and w
- * of a column are its worker's).  Runs on the any-p solver.  Synchronises the stream before
- * it returns, so sizes_host may be reused at once.
+ * of a column are its worker's).  Solvers: the matrix-core purification kernel with the any-p
+ * kernel as stand-by (FA_SOLVER_AUTO), else the any-p kernel alone.  Synchronises the stream
+ * before it returns, so sizes_host may be reused at once.
  */
 fa_status fa_aggregate_grouped(fa_ctx* ctx, const void* G, int64_t ldg, int q, int64_t n,
                                const int* sizes_host, int nworkers, int m, double lambda,

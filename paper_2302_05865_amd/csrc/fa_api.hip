@@ -592,7 +592,8 @@ extern "C" fa_status fa_aggregate_grouped(fa_ctx* c, const void* G, int64_t ldg,
     return FA_ERR_DEVICE;
   if (fa_launch_irls_grouped(c->Kd, q, nworkers, c->sizes_d, m, lambda, iters, tol,
                              c->cfg.clamp_delta, c->cfg.rank_tol, c->cfg.pair_tol,
-                             c->cfg.exponent_a, c->cd, c->info_d, c->gws, st) != hipSuccess)
+                             c->cfg.exponent_a, c->cd, c->info_d, c->gws, c->cfg.solver,
+                             c->cfg.wide_spin_budget, st) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_combine(G, ldg, q, n, c->cfg.dtype, c->cfg.layout, c->cd, 1, out,
                         c->combine_max_blocks, st, nullptr) != hipSuccess)

@@ -73,7 +73,8 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
 hipError_t fa_launch_irls_grouped(const double* Kd, int q, int nworkers, const int* sizes_d, int m,
                                   double lambda, int iters, double tol, double delta,
                                   double rank_tol, double pair_tol, double exponent_a, double* cd,
-                                  fa_info* info_d, double* gws, hipStream_t st);
+                                  fa_info* info_d, double* gws, int solver, int spin_budget,
+                                  hipStream_t st);
 // Launch attributes (dynamic LDS above the default limit) of every kernel that needs them, on
 // the current device; called by fa_create.
 hipError_t fa_kernels_prepare(void);
@@ -100,12 +101,14 @@ hipError_t fa_launch_irls16(const double* Kd, int p, int m, double lambda, int i
 // K3 for 16 < p <= 64 (sixteen wavefronts, tiled matrix-core products).  tiles_ws:
 // FA_GWS_TILES doubles; mlast as above with N = 16 ceil(p/16).  May leave
 // info_d->status = FA_ST_RETRY, in which case the any-p kernel must run next.  exponent_a as
-// for fa_launch_irls16.
-hipError_t fa_launch_irls64(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                            double delta, double exponent_a, double rank_tol, double pair_tol,
-                            double* cd,
-                            fa_info* info_d, double* tiles_ws, double* mlast, int spin_budget,
-                            fa_resume* rs, hipStream_t st, const fa_ktime* tm);
+// for fa_launch_irls16.  nworkers > 0: the p columns are nworkers blocks of sizes_d[i]
+// consecutive columns (device memory), one block per worker; then any p <= 64 is taken.
+// nworkers = 0: one column per worker, 16 < p <= 64 only.
+hipError_t fa_launch_irls64(const double* Kd, int p, int nworkers, const int* sizes_d, int m,
+                            double lambda, int iters, double tol, double delta, double exponent_a,
+                            double rank_tol, double pair_tol, double* cd, fa_info* info_d,
+                            double* tiles_ws, double* mlast, int spin_budget, fa_resume* rs,
+                            hipStream_t st, const fa_ktime* tm);
 // eigengap (mu_m - mu_{m+1}) / mu_1 of the N x N matrix left in mlast (then rank, m), into
 // info_d->eigengap.
 hipError_t fa_launch_gap(const double* mlast, int N, fa_info* info_d, hipStream_t st);

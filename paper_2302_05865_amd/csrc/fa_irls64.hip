@@ -19,6 +19,9 @@
 // Frobenius norm of its tile, all wavefronts add the published numbers in the same order
 // after the step's barrier, so they take identical decisions.
 //
+// The same kernel has a mode for workers that send several gradients (blocks of columns, see
+// MODE below); in that mode it is also built for a single tile (p <= 16).
+//
 // If the purification cannot converge (tied eigenvalues m, m+1) the kernel leaves
 // info->status = FA_ST_RETRY and touches nothing else; the caller then runs the any-p Jacobi
 // kernel, which starts from the same inputs.
@@ -141,16 +144,26 @@ struct Small {
   double dgx[2][64], dgy[2][64];   // [step parity]: diagonals of X_k and of X_k^2
   double red[NW];
   int piv[64], used[64];
+  // workers that send several gradients: first column and width of the block a column is in,
+  // 1 / tr(g^T g) of that block
+  int gf[64], gc[64];
+  double ginv[64];
   int dec[4];   // word of purification step g at [g & 3]: g << 4 | trace ok (4) | converged (2) | square (1)
   int flag[2];  // [step parity] a wavefront gave up waiting for that step's steering word
 };
 
 }  // namespace
 
-// GEN: terms residual^(1/a) with the constant a of Sec. 2.2 Step 2 other than Eq. 5's a = 2 (a
-// kernel of its own: the powers must not take registers from the a = 2 code)
-template <int T, bool GEN>
+// MODE 0: Eq. 5.  MODE 1: terms residual^(1/a) with the constant a of Sec. 2.2 Step 2 other than
+// Eq. 5's a = 2 (a kernel of its own: the powers must not take registers from the a = 2 code).
+// MODE 2: workers that send several gradients (Sec. 2.1; Sec. 2.2, the extension to
+// g_i in R^{n x k}): the p columns are nworkers blocks of sizes[i] consecutive columns; a block's
+// value is tr(g^T Y Y^T g) / tr(g^T g), the IRLS re-weights whole blocks, pair terms exist
+// between blocks of equal width (Frobenius distance, column l against column l); any exponent.
+template <int T, int MODE>
 __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __restrict__ Kg, int p,
+                                                             int nworkers,
+                                                             const int* __restrict__ sizes,
                                                              int m, int iters, double lambda,
                                                              double tol, double delta,
                                                              double expo,
@@ -177,7 +190,9 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
   // in a scalar register: everything decided per wavefront is a scalar branch
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c16 = lane & 15, q4 = lane >> 4;
-  const double coef = (lambda > 0.0 && p > 1) ? lambda / (double)(p - 1) : 0.0;
+  constexpr bool GEN = MODE != 0, GRP = MODE == 2;
+  const int P = GRP ? nworkers : p;                       // workers
+  const double coef = (lambda > 0.0 && P > 1) ? lambda / (double)(P - 1) : 0.0;
   const int it0 = rs ? rs->it0 : 0;
   const bool scaled = rs && rs->scaled;
   bool isdiag[4];
@@ -196,6 +211,25 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     if (tid < 4) sm.dec[tid] = 0;   // tag 0 is never used
   }
   __syncthreads();
+  if constexpr (GRP) {
+    if (tid < 64) {
+      int first = tid, cnt = 1;
+      if (tid < p) {
+        int c = 0;
+        for (int i = 0; i < nworkers; ++i) {
+          const int k = sizes[i];
+          if (tid < c + k) { first = c; cnt = k; break; }
+          c += k;
+        }
+      }
+      double gs = 0.0;
+      for (int l = 0; l < cnt; ++l) gs += sm.s[first + l];
+      sm.gf[tid] = first; sm.gc[tid] = cnt;
+      sm.ginv[tid] = gs > 0.0 ? 1.0 / gs : 0.0;
+      sm.w[tid] = gs > 0.0 ? 1.0 : 0.0;
+    }
+    __syncthreads();
+  }
   bool bad = false, live = false;
 #pragma unroll
   for (int q = 0; q < EPT; ++q) {
@@ -210,8 +244,26 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
       const double si = sm.s[i], sj = sm.s[j];
       live = live || (i == j && si > 0.0);
       B0[e] = (i == j) ? (si > 0.0 ? 1.0 : 0.0) : kv * sm.dinv[i] * sm.dinv[j];   // K~, row-major
-      const double d2 = si + sj - 2.0 * kv;
-      const bool livep = in && i != j && d2 > pair_tol * (si + sj);
+      double d2 = si + sj - 2.0 * kv;
+      bool livep = in && i != j && d2 > pair_tol * (si + sj);
+      if constexpr (GRP) {
+        // D^2 between two blocks: column l of one against column l of the other; only blocks
+        // of equal width have one, and it sits at the column pairs at the same place in them
+        livep = false;
+        if (in && i != j) {
+          const int fi = sm.gf[i], fj = sm.gf[j], ki = sm.gc[i];
+          if (fi != fj && ki == sm.gc[j] && i - fi == j - fj) {
+            double ssum = 0.0;
+            d2 = 0.0;
+            for (int l = 0; l < ki; ++l) {
+              const double sa = sm.s[fi + l], sb = sm.s[fj + l];
+              d2 += sa + sb - 2.0 * Kg[(fi + l) * p + fj + l];
+              ssum += sa + sb;
+            }
+            livep = d2 > pair_tol * ssum;
+          }
+        }
+      }
       D2I[eidx<T>(i, j)] = livep ? 1.0 / d2 : 0.0;
     }
   }
@@ -309,7 +361,10 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     const int a = tid >> 4, l16 = tid & 15;
     double acc = 0.0;
     if (a < N)
-      for (int j = l16; j < N; j += 16) acc += RA[aidx<T>(a, j)];
+      for (int j = l16; j < N; j += 16) {
+        const double x = RA[aidx<T>(a, j)];
+        acc += GRP ? x / (double)sm.gc[j] : x;          // a block counts with its mean column
+      }
     acc = row_sum(acc);
     if (a < N && l16 == 0) sm.r1[a] = acc;
   }
@@ -353,7 +408,8 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
         for (int j = l16; j < N; j += 16) acc += (j != i) ? B2[eidx<T>(i, j)] : 0.0;
       acc = row_sum(acc);
       __syncthreads();
-      if (i < N && l16 == 0) B2[eidx<T>(i, i)] = sm.w[i] * sm.dinv[i] * sm.dinv[i] - acc;
+      if (i < N && l16 == 0)
+        B2[eidx<T>(i, i)] = sm.w[i] * (GRP ? sm.ginv[i] : sm.dinv[i] * sm.dinv[i]) - acc;
     }
     __syncthreads();
     // ---- W = C R^T (B1): A operand = C (symmetric: tile (K, I)), B operand = R^T tile (K, J),
@@ -561,6 +617,15 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
       }
     }
     __syncthreads();
+    if constexpr (GRP) {
+      // a block's residual adds entries of Gq that other wavefronts hold: all of it into LDS
+      // (over Z, which nobody reads any more)
+      if (wave < NTP) {
+        store_tile<T>(nxt, uI, uJ, lane, gq);
+        if (uI != uJ) store_tile_transposed<T>(nxt, uI, uJ, lane, gq);
+      }
+      __syncthreads();
+    }
     // ---- residuals, objective, next weights (pair part straight into C = B2) -------------------
     double part = 0.0;
     if (wave < NTP) {
@@ -602,18 +667,42 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
           double rho = 0.0, scale = 0.0;       // residual; factor of its term in the objective
           bool diag = i == j, use = false;
           double d2i = 0.0;
-          if (diag) {
-            rho = gqr * sm.dinv[j] * sm.dinv[j];
-            use = sm.s[j] > 0.0;
-            scale = 1.0;
+          if constexpr (!GRP) {
+            if (diag) {
+              rho = gqr * sm.dinv[j] * sm.dinv[j];
+              use = sm.s[j] > 0.0;
+              scale = 1.0;
+            } else {
+              d2i = D2I[eidx<T>(i, j)];
+              if (d2i > 0.0 && coef > 0.0) {
+                double num = sm.gd[i] + sm.gd[j] - 2.0 * gqr;
+                num = num > 0.0 ? num : 0.0;
+                rho = num * d2i;
+                use = true;
+                scale = (uI == uJ ? 1.0 : 2.0) * coef;
+              }
+            }
           } else {
-            d2i = D2I[eidx<T>(i, j)];
-            if (d2i > 0.0 && coef > 0.0) {
-              double num = sm.gd[i] + sm.gd[j] - 2.0 * gqr;
-              num = num > 0.0 ? num : 0.0;
-              rho = num * d2i;
-              use = true;
-              scale = (uI == uJ ? 1.0 : 2.0) * coef;
+            // the block's numbers, the same at each of its columns; its term of the objective
+            // is counted at its first column (pair terms: at the blocks' first columns)
+            const int fi = sm.gf[i], fj = sm.gf[j], kj = sm.gc[j];
+            if (diag) {
+              double bot = 0.0;
+              for (int l = 0; l < kj; ++l) bot += sm.gd[fj + l];
+              rho = bot * sm.ginv[j];
+              use = sm.ginv[j] > 0.0;
+              scale = j == fj ? 1.0 : 0.0;
+            } else {
+              d2i = D2I[eidx<T>(i, j)];
+              if (d2i > 0.0 && coef > 0.0) {
+                double num = 0.0;
+                for (int l = 0; l < kj; ++l)
+                  num += sm.gd[fi + l] + sm.gd[fj + l] - 2.0 * nxt[eidx<T>(fi + l, fj + l)];
+                num = num > 0.0 ? num : 0.0;
+                rho = num * d2i;
+                use = true;
+                scale = i == fi ? (uI == uJ ? 1.0 : 2.0) * coef : 0.0;
+              }
             }
           }
           const double tv = fa_term_pow(rho, expo), wv = fa_weight_pow(rho, delta, expo);
@@ -727,7 +816,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
       }
     }
     acc = row_sum(acc);
-    if (a < rank && l16 == 0) sm.gd[sm.piv[a]] = acc / (double)p;     // c of that worker
+    if (a < rank && l16 == 0) sm.gd[sm.piv[a]] = acc / (double)P;     // c of that column
   }
   if (tid < 64) sm.used[tid] = 0;
   __syncthreads();
@@ -738,7 +827,7 @@ __global__ __launch_bounds__(NTHREADS) void fa_irls64_kernel(const double* __res
     cg[tid] = cv;
     info->c[tid] = cv;
     info->s[tid] = sm.s[tid];
-    info->v[tid] = sm.s[tid] > 0.0 ? 1.0 - sm.rho[tid] : 0.0;
+    info->v[tid] = (GRP ? sm.ginv[tid] > 0.0 : sm.s[tid] > 0.0) ? 1.0 - sm.rho[tid] : 0.0;
     info->w[tid] = sm.w[tid];
   }
   if (rs) {
@@ -770,48 +859,67 @@ static constexpr size_t lds_bytes() {
   return (size_t)4 * T * T * FA_TILE * sizeof(double) + sizeof(Small);
 }
 
-template <int T>
-static hipError_t launch_t(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                           double delta, double expo, double rank_tol, double pair_tol, double* cd,
-                           fa_info* info_d, double* tiles_ws, double* mlast, int spin_budget,
-                           fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
-  if (expo == 0.5)
-    FA_LAUNCH(tm, (fa_irls64_kernel<T, false>), dim3(1), dim3(NTHREADS), lds_bytes<T>(), st, Kd, p,
-              m, iters, lambda, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast,
-              spin_budget, rs);
-  else
-    FA_LAUNCH(tm, (fa_irls64_kernel<T, true>), dim3(1), dim3(NTHREADS), lds_bytes<T>(), st, Kd, p,
-              m, iters, lambda, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast,
-              spin_budget, rs);
+template <int T, int MODE>
+static hipError_t launch_tm(const double* Kd, int p, int nworkers, const int* sizes_d, int m,
+                            double lambda, int iters, double tol, double delta, double expo,
+                            double rank_tol, double pair_tol, double* cd, fa_info* info_d,
+                            double* tiles_ws, double* mlast, int spin_budget, fa_resume* rs,
+                            hipStream_t st, const fa_ktime* tm) {
+  FA_LAUNCH(tm, (fa_irls64_kernel<T, MODE>), dim3(1), dim3(NTHREADS), lds_bytes<T>(), st, Kd, p,
+            nworkers, sizes_d, m, iters, lambda, tol, delta, expo, rank_tol, pair_tol, cd, info_d,
+            tiles_ws, mlast, spin_budget, rs);
   return hipGetLastError();
 }
 
-template <int T, bool GEN>
+template <int T>
+static hipError_t launch_t(const double* Kd, int p, int nworkers, const int* sizes_d, int m,
+                           double lambda, int iters, double tol, double delta, double expo,
+                           double rank_tol, double pair_tol, double* cd, fa_info* info_d,
+                           double* tiles_ws, double* mlast, int spin_budget, fa_resume* rs,
+                           hipStream_t st, const fa_ktime* tm) {
+  if (nworkers > 0)
+    return launch_tm<T, 2>(Kd, p, nworkers, sizes_d, m, lambda, iters, tol, delta, expo, rank_tol,
+                           pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+  if constexpr (T > 1) {
+    if (expo == 0.5)
+      return launch_tm<T, 0>(Kd, p, 0, nullptr, m, lambda, iters, tol, delta, expo, rank_tol,
+                             pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+    return launch_tm<T, 1>(Kd, p, 0, nullptr, m, lambda, iters, tol, delta, expo, rank_tol,
+                           pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+  }
+  return hipErrorInvalidValue;      // single columns at p <= 16 have a solver of their own
+}
+
+template <int T, int MODE>
 static hipError_t prepare_t() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<T, GEN>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(fa_irls64_kernel<T, MODE>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<T>());
 }
 
 hipError_t fa_irls64_prepare(void) {
-  hipError_t e = prepare_t<2, false>();
-  if (e == hipSuccess) e = prepare_t<3, false>();
-  if (e == hipSuccess) e = prepare_t<4, false>();
-  if (e == hipSuccess) e = prepare_t<2, true>();
-  if (e == hipSuccess) e = prepare_t<3, true>();
-  if (e == hipSuccess) e = prepare_t<4, true>();
+  hipError_t e = prepare_t<1, 2>();
+#define FA_X(t)                                        \
+  if (e == hipSuccess) e = prepare_t<t, 0>();          \
+  if (e == hipSuccess) e = prepare_t<t, 1>();          \
+  if (e == hipSuccess) e = prepare_t<t, 2>();
+  FA_X(2) FA_X(3) FA_X(4)
+#undef FA_X
   return e;
 }
 
-hipError_t fa_launch_irls64(const double* Kd, int p, int m, double lambda, int iters, double tol,
-                            double delta, double exponent_a, double rank_tol, double pair_tol,
-                            double* cd,
-                            fa_info* info_d, double* tiles_ws, double* mlast, int spin_budget,
-                            fa_resume* rs, hipStream_t st, const fa_ktime* tm) {
+hipError_t fa_launch_irls64(const double* Kd, int p, int nworkers, const int* sizes_d, int m,
+                            double lambda, int iters, double tol, double delta, double exponent_a,
+                            double rank_tol, double pair_tol, double* cd, fa_info* info_d,
+                            double* tiles_ws, double* mlast, int spin_budget, fa_resume* rs,
+                            hipStream_t st, const fa_ktime* tm) {
   const double expo = exponent_a == 2.0 ? 0.5 : 1.0 / exponent_a;
   switch ((p + 15) / 16) {
-    case 2: return launch_t<2>(Kd, p, m, lambda, iters, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
-    case 3: return launch_t<3>(Kd, p, m, lambda, iters, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
-    case 4: return launch_t<4>(Kd, p, m, lambda, iters, tol, delta, expo, rank_tol, pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+#define FA_X(t)                                                                                  \
+    case t:                                                                                      \
+      return launch_t<t>(Kd, p, nworkers, sizes_d, m, lambda, iters, tol, delta, expo, rank_tol, \
+                         pair_tol, cd, info_d, tiles_ws, mlast, spin_budget, rs, st, tm);
+    FA_X(1) FA_X(2) FA_X(3) FA_X(4)
+#undef FA_X
   }
   return hipErrorInvalidValue;
 }

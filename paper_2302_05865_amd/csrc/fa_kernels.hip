@@ -1462,8 +1462,8 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
   if (p > 16 && solver == 0) {
     // timing, if asked for, spans both launches: begin of the first, end of the second
     if (tm) { first.start = tm->start; second.stop = tm->stop; }
-    hipError_t e = fa_launch_irls64(Kd, p, m, lambda, iters, tol, delta, exponent_a, rank_tol,
-                                    pair_tol, cd,
+    hipError_t e = fa_launch_irls64(Kd, p, 0, nullptr, m, lambda, iters, tol, delta, exponent_a,
+                                    rank_tol, pair_tol, cd,
                                     info_d, gws + FA_GWS_GENERIC, gws + FA_GWS_MLAST_OFF,
                                     spin_budget, rs, st, tm ? &first : nullptr);
     if (e != hipSuccess) return e;
@@ -1483,11 +1483,22 @@ hipError_t fa_launch_irls(const double* Kd, int p, int m, double lambda, int ite
 }
 
 // The same for workers that send several gradients: q columns in nworkers blocks of
-// sizes_d[i] consecutive columns (device memory).  Always the any-p kernel.
+// sizes_d[i] consecutive columns (device memory).  solver 0: the matrix-core purification
+// kernel, with the any-p kernel behind it as stand-by; otherwise the any-p kernel alone.
 hipError_t fa_launch_irls_grouped(const double* Kd, int q, int nworkers, const int* sizes_d, int m,
                                   double lambda, int iters, double tol, double delta,
                                   double rank_tol, double pair_tol, double exponent_a, double* cd,
-                                  fa_info* info_d, double* gws, hipStream_t st) {
+                                  fa_info* info_d, double* gws, int solver, int spin_budget,
+                                  hipStream_t st) {
+  int retry_only = 0;
+  if (solver == 0) {
+    hipError_t e = fa_launch_irls64(Kd, q, nworkers, sizes_d, m, lambda, iters, tol, delta,
+                                    exponent_a, rank_tol, pair_tol, cd, info_d,
+                                    gws + FA_GWS_GENERIC, gws + FA_GWS_MLAST_OFF, spin_budget,
+                                    nullptr, st, nullptr);
+    if (e != hipSuccess) return e;
+    retry_only = 1;   // the Jacobi kernel below runs only if the one above gave up
+  }
   fa_irls_args ar;
   ar.p = q; ar.m = m; ar.iters = iters; ar.lambda = lambda; ar.tol = tol;
   ar.delta = delta; ar.rank_tol = rank_tol; ar.pair_tol = pair_tol;
@@ -1496,7 +1507,7 @@ hipError_t fa_launch_irls_grouped(const double* Kd, int q, int nworkers, const i
   int big = 0;
   const size_t lds = fa_irls_lds_bytes(q, &big);
   hipLaunchKernelGGL(fa_irls_kernel, dim3(1), dim3(FA_IRLS_THREADS), lds, st, Kd, ar, cd, info_d,
-                     gws, big, (fa_resume*)nullptr, 0);
+                     gws, big, (fa_resume*)nullptr, retry_only);
   return hipGetLastError();
 }
 

@@ -839,9 +839,13 @@ def test_check_basis_of_any_matrix_and_argument_errors(agg_f32):
     ([2, 3, 1, 2, 2, 1, 4], 8, 1.0, 30_011, "f32"), ([4] * 8, 9, 1.0, 20_000, "f32"),
     ([1] * 15, 8, 1.0, 25_003, "f32"), ([3, 2, 3, 2, 3], 4, 0.0, 12_345, "f32"),
     ([8, 8, 8, 8, 8, 8, 8, 4], 20, 0.5, 9_001, "f32"), ([5, 5, 6], 3, 1.0, 16_384, "bf16"),
-    ([7], 2, 1.0, 1_000, "f32")])
-def test_grouped_workers_match_the_block_oracle(sizes, m, lam, n, dtype):
-    announce("grouped", sizes, m, lam, n, dtype)
+    ([7], 2, 1.0, 1_000, "f32"), ([16] * 4, 33, 1.0, 5_003, "f32"),
+    ([3] * 5 + [1], 8, 2.0, 7_001, "f32")])
+@pytest.mark.parametrize("solver", ["auto", "jacobi"])
+def test_grouped_workers_match_the_block_oracle(sizes, m, lam, n, dtype, solver):
+    """Both routes of the block solver: the matrix-core purification kernel (default) and the
+    any-p Jacobi kernel."""
+    announce("grouped", sizes, m, lam, n, dtype, solver)
     q = sum(sizes)
     Gw = si.random_dense(q, n, seed=q + m)
     Gw[0] += 1.5 * Gw[q - 1]
@@ -849,7 +853,7 @@ def test_grouped_workers_match_the_block_oracle(sizes, m, lam, n, dtype):
         Gw = (Gw.view(np.uint32) >> 16).astype(np.uint16)      # truncated to bf16 bits
     iters = 6
     ref = fa_literal_grouped(as_f64_matrix(Gw), sizes, m, lam, iters, 0.0)
-    agg = FlagAggregator(n_max=n, p_max=q, dtype=dtype)
+    agg = FlagAggregator(n_max=n, p_max=q, dtype=dtype, solver=solver)
     out = agg.fa_aggregate_grouped(to_device(Gw), sizes, m, lam, iters, 0.0).cpu().numpy()
     info = agg.fa_get_info()
     assert info.status == 0 and info.iters_done == iters
@@ -857,23 +861,57 @@ def test_grouped_workers_match_the_block_oracle(sizes, m, lam, n, dtype):
     first = np.concatenate([[0], np.cumsum(sizes)[:-1]])
     assert np.allclose(info.v[first], ref["v"], atol=1e-6)
     assert np.allclose(info.objective, ref["objective"], atol=1e-6)
+    # every column reports its worker's value and weight
+    owner = np.repeat(np.arange(len(sizes)), sizes)
+    assert np.array_equal(info.v, info.v[first][owner])
+    assert np.array_equal(info.w, info.w[first][owner])
     agg.close()
 
 
-def test_grouped_with_single_columns_is_fa_aggregate_bit_for_bit(agg_f32):
-    announce("grouped = plain at k = 1")
-    w = si.WORKLOADS["cfg2"].with_n(100_003)
+@pytest.mark.parametrize("a", [1.5, 4.0])
+def test_grouped_workers_general_exponent(a):
+    """Blocks of columns with the constant a of Sec. 2.2 Step 2 other than 2, both routes."""
+    announce("grouped, exponent", a)
+    sizes, m, lam, n, iters = [2, 2, 3, 3, 2, 1, 5], 7, 1.0, 9_973, 5
+    q = sum(sizes)
+    Gw = si.random_dense(q, n, seed=77)
+    ref = fa_literal_grouped(as_f64_matrix(Gw), sizes, m, lam, iters, 0.0, a=a)
+    outs = []
+    for solver in ("auto", "jacobi"):
+        agg = FlagAggregator(n_max=n, p_max=q, exponent_a=a, solver=solver)
+        out = agg.fa_aggregate_grouped(to_device(Gw), sizes, m, lam, iters, 0.0).cpu().numpy()
+        info = agg.fa_get_info()
+        assert info.status == 0 and info.iters_done == iters
+        assert rel_l2(out.astype(np.float64), ref["out"]) <= GATE
+        assert np.allclose(info.objective, ref["objective"], atol=1e-6)
+        outs.append(out)
+        agg.close()
+    assert rel_l2(outs[0].astype(np.float64), outs[1].astype(np.float64)) <= 1e-6
+
+
+@pytest.mark.parametrize("name,n", [("cfg2", 100_003), ("cfg4", 50_021)])
+def test_grouped_with_single_columns_is_fa_aggregate(name, n):
+    announce("grouped = plain at k = 1", name)
+    w = si.WORKLOADS[name].with_n(n)
     Gw, _ = si.make_inputs(w, 2)
     dev = to_device(Gw)
-    plain = FlagAggregator(n_max=w.n, p_max=w.p)
-    a = agg_f32.fa_aggregate_grouped(dev, [1] * w.p, w.m, w.lam, 5, 0.0).clone()
-    # the plain entry on the same any-p solver
-    gen = FlagAggregator(n_max=w.n, p_max=w.p, solver="jacobi")
-    b = gen.fa_aggregate(dev, w.m, w.lam, 5, 0.0)
+    # on the any-p solver the two entries run the same code: bit for bit
+    gen = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype, solver="jacobi")
+    a = gen.fa_aggregate_grouped(dev, [1] * w.p, w.m, w.lam, 5, 0.0).clone()
+    b = gen.fa_aggregate(dev, w.m, w.lam, 5, 0.0).clone()
     assert torch.equal(a, b)
     gen.close()
-    c = plain.fa_aggregate(dev, w.m, w.lam, 5, 0.0)
-    assert rel_l2(a.cpu().numpy().astype(np.float64), c.cpu().numpy().astype(np.float64)) <= 1e-6
+    # on the default route the block kernel takes powers where the plain one has square roots
+    plain = FlagAggregator(n_max=w.n, p_max=w.p, dtype=w.dtype)
+    c = plain.fa_aggregate_grouped(dev, [1] * w.p, w.m, w.lam, 5, 0.0).clone()
+    info_c = plain.fa_get_info()
+    d = plain.fa_aggregate(dev, w.m, w.lam, 5, 0.0)
+    info_d = plain.fa_get_info()
+    assert info_c.status == 0 and info_d.status == 0
+    assert rel_l2(c.cpu().numpy().astype(np.float64), d.cpu().numpy().astype(np.float64)) <= 1e-6
+    assert rel_l2(c.cpu().numpy().astype(np.float64), b.cpu().numpy().astype(np.float64)) <= 1e-6
+    assert np.allclose(info_c.objective, info_d.objective, rtol=0, atol=1e-9)
+    assert np.allclose(info_c.v, info_d.v, rtol=0, atol=1e-8)
     plain.close()
 
 
