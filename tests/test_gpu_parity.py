@@ -915,6 +915,44 @@ def test_grouped_with_single_columns_is_fa_aggregate(name, n):
     plain.close()
 
 
+@pytest.mark.parametrize("sizes,m", [([4] * 10, 17), ([3, 3, 2, 2, 3], 6)])
+def test_grouped_stand_by_redoes_the_solve_when_the_purification_gives_up(sizes, m):
+    """The block solver's hand-over: with a spin budget of zero the purification kernel gives up
+    at its first wait and the Jacobi kernel behind it answers, bit for bit what a context asking
+    for that kernel returns.  Also on the block route: a worker sent twice (its pair is dropped,
+    its columns are linearly dependent), non-finite and all-zero input."""
+    q, n, iters = sum(sizes), 8_009, 4
+    announce("grouped stand-by", sizes, m)
+    Gw = si.random_dense(q, n, seed=31)
+    dev = to_device(Gw)
+    agg = FlagAggregator(n_max=n, p_max=q, wide_spin_budget=0)
+    a = agg.fa_aggregate_grouped(dev, sizes, m, 1.0, iters, 0.0).clone()
+    info = agg.fa_get_info()
+    ref = FlagAggregator(n_max=n, p_max=q, solver="jacobi")
+    b = ref.fa_aggregate_grouped(dev, sizes, m, 1.0, iters, 0.0)
+    info_j = ref.fa_get_info()
+    assert info.status == 0 and info_j.status == 0
+    assert info.sweeps == info_j.sweeps and torch.equal(a, b)
+    agg.close()
+    ref.close()
+    agg = FlagAggregator(n_max=n, p_max=q)
+    twice = Gw.copy()
+    twice[sizes[0]:2 * sizes[0]] = twice[0:sizes[0]]          # worker 1 = worker 0
+    oracle = fa_literal_grouped(as_f64_matrix(twice), sizes, m, 1.0, iters, 0.0)
+    out = agg.fa_aggregate_grouped(to_device(twice), sizes, m, 1.0, iters, 0.0).cpu().numpy()
+    info = agg.fa_get_info()
+    assert info.status == 0 and info.rank == q - sizes[0]
+    assert rel_l2(out.astype(np.float64), oracle["out"]) <= GATE
+    assert np.allclose(info.objective, oracle["objective"], atol=1e-6)
+    bad = Gw.copy()
+    bad[1, 5] = np.nan
+    out = agg.fa_aggregate_grouped(to_device(bad), sizes, m, 1.0, iters, 0.0).cpu().numpy()
+    assert agg.fa_get_info().status == 4 and np.all(np.isnan(out))
+    out = agg.fa_aggregate_grouped(to_device(np.zeros_like(Gw)), sizes, m, 1.0, iters, 0.0).cpu().numpy()
+    assert agg.fa_get_info().status == 5 and np.all(out == 0.0)
+    agg.close()
+
+
 def test_grouped_argument_errors(agg_f32):
     announce("grouped argument errors")
     dev = to_device(si.random_dense(6, 100, seed=1))
