@@ -304,7 +304,8 @@ fa_status fa_multikrum(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t n
  *   YtY_host (m x m, row-major, host memory)  = Y^T Y   - the identity for a basis,
  *   YtG_host (m x p, row-major, host memory)  = Y^T G   - row a, column i: y_a . g_i.
  * Y is device memory as fa_basis writes it (m columns of n floats, column a at Y + a*ldy,
- * ldy >= n, 16-byte aligned); G, ldg, p, n as for fa_aggregate, in the context's dtype and
+ * ldy >= n, every column 16-byte aligned: Y is, and for m > 1 so is ldy * 4); G, ldg, p, n as
+ * for fa_aggregate, in the context's dtype and
  * layout.  Y need not come from fa_basis.  Synchronises the context's stream.  Uses the
  * context's workspace: the record of the last solve stays, its p x p scratch does not.
  * FA_ERR_ARG for bad shapes or pointers, FA_ERR_DEVICE if a launch or copy fails.

@@ -18,7 +18,7 @@ struct fa_ctx {
   int num_cus;
   int gram_max_blocks;
   int combine_max_blocks;
-  double* partials;   // gram_max_blocks * NTP(p_max) * 256
+  double* partials;   // gram_max_blocks * 2 ceil(p_max/16)^2 * 256
   double* Kd;         // FA_P_MAX^2
   double* cd;         // FA_P_MAX
   double* gws;        // FA_GWS_DOUBLES: the p x p solvers' global workspace
@@ -100,7 +100,9 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   c->gram_max_blocks = c->num_cus;                 // one Gram workgroup per compute unit
   c->combine_max_blocks = 1 << 20;
   const int T = (cfg->p_max + 15) / 16;
-  const size_t ntp = (size_t)T * T;   // tile pairs of the Gram pass, T x TM tiles of the projections
+  // per workgroup: tile pairs of the Gram pass, T x TM tiles of the projections (<= T^2), and a
+  // tile row of the basis check, up to T x 2T tiles
+  const size_t ntp = (size_t)2 * T * T;
   const size_t part_bytes = (size_t)c->gram_max_blocks * ntp * 256 * sizeof(double);
   bool ok = true;
   ok = ok && hipMalloc((void**)&c->partials, part_bytes) == hipSuccess;
@@ -645,10 +647,11 @@ extern "C" fa_status fa_check_basis(fa_ctx* c, const void* G, int64_t ldg, int p
                                     double* YtG_host) {
   if (!check_matrix_args(c, G, ldg, p, n) || !Y || ((uintptr_t)Y & 15u) != 0) return FA_ERR_ARG;
   if (m < 1 || m > p || ldy < n || !YtY_host || !YtG_host) return FA_ERR_ARG;
+  if (m > 1 && (ldy * 4) % 16 != 0) return FA_ERR_ARG;     // every column of Y 16-byte aligned
   const int TMr = (m + 15) / 16, TC = TMr + (p + 15) / 16;
   const int T = (c->cfg.p_max + 15) / 16;
-  // the Gram pass's partial buffer holds gram_max_blocks * T^2 tiles
-  const int max_parts = (int)((int64_t)c->gram_max_blocks * T * T / (TMr * TC));
+  // the partial buffer holds gram_max_blocks * 2 T^2 tiles
+  const int max_parts = (int)((int64_t)c->gram_max_blocks * 2 * T * T / (TMr * TC));
   const int ncols = 16 * TMr + p;
   static_assert(FA_GWS_DOUBLES >= FA_P_MAX * (FA_P_MAX + 16 * ((FA_P_MAX + 15) / 16)),
                 "the solvers' workspace doubles as the result buffer of the check");

@@ -1107,12 +1107,13 @@ hipError_t fa_launch_krum(const double* Kd, int p, int f, int q, double* cd, dou
 // computes W = Y^T [Y | G] in fp64 on the matrix cores: Y^T Y (the identity for the
 // orthonormal basis of Sec. 2.1) and Y^T G (row a, column i: the projection of g_i on y_a,
 // whose squares add up to the explained variance of Sec. 2.1 times |g_i|^2).
-// One workgroup (sixteen wavefronts) per (row stripe, 16 x 16 output tile); a wavefront takes
-// 16 rows at a time: lane (c, k) holds rows 4k..4k+3 of column c of either operand (one
-// 16-byte load where the rows are contiguous), and feeds row 4k+s of both to the s-th
-// matrix instruction - the contraction does not care in which order the rows come, as long
-// as both operands agree.  Not a tuned kernel: the operand of a 16 x 16 tile is re-read for
-// every tile that uses it (once or twice at p, m <= 16).
+// One workgroup (eight wavefronts) per (row stripe, tile row ta of the result); a wavefront
+// takes 16 rows at a time: lane (c, k) holds rows 4k..4k+3 of column c of each 16-column tile
+// of [Y | G] (one 16-byte load where the rows are contiguous), and feeds row 4k+s of tile ta
+// of Y and of every tile to the s-th matrix instruction - the contraction does not care in
+// which order the rows come, as long as both operands agree, and the registers of a tile
+// serve as either operand.  [Y | G] is therefore read once per tile row of Y (once at
+// m <= 16), all TC result tiles of the row accumulate in registers.
 // G is addressed by strides (elements): g_rs between rows, g_cs between columns, which
 // covers both storage orders.
 template <typename E>
@@ -1148,55 +1149,159 @@ __device__ __forceinline__ void load_rows4(const unsigned char* base, int64_t co
     if (row0 + s < n) x[s] = load_elem<E>(base, col_off + (row0 + s) * rs);
 }
 
-template <typename E>
-__global__ __launch_bounds__(1024) void fa_cross_kernel(const float* __restrict__ Y, int64_t ldy,
-                                                        int m,
-                                                        const unsigned char* __restrict__ G,
-                                                        int64_t g_rs, int64_t g_cs, int p,
-                                                        int64_t n, int TMr, int TC,
-                                                        double* __restrict__ partials) {
-  __shared__ double red[16 * 256];
+// four rows row0..row0+3 (all inside the matrix) of one column as raw bits: the loads of a
+// stage are all issued before any of them is used
+template <typename E, bool ROWS>
+__device__ __forceinline__ uint4 cross_raw(const unsigned char* base, int64_t col_off, int64_t rs,
+                                           int64_t row0) {
+  uint4 r = {0u, 0u, 0u, 0u};
+  if constexpr (!ROWS) {
+    const unsigned char* src = base + (col_off + row0) * E::SIZE;
+    if constexpr (E::SIZE == 4) {
+      r = *reinterpret_cast<const uint4*>(src);
+    } else {
+      const uint2 h = *reinterpret_cast<const uint2*>(src);
+      r.x = h.x; r.y = h.y;
+    }
+  } else if constexpr (E::SIZE == 4) {
+    const uint32_t* g = reinterpret_cast<const uint32_t*>(base) + col_off + row0 * rs;
+    r.x = g[0]; r.y = g[rs]; r.z = g[2 * rs]; r.w = g[3 * rs];
+  } else {
+    const uint16_t* g = reinterpret_cast<const uint16_t*>(base) + col_off + row0 * rs;
+    r.x = g[0]; r.y = g[rs]; r.z = g[2 * rs]; r.w = g[3 * rs];
+  }
+  return r;
+}
+template <typename E, bool ROWS>
+__device__ __forceinline__ void cross_decode(const uint4& r, double* x) {
+  if constexpr (E::SIZE == 4) {
+    x[0] = (double)__uint_as_float(r.x); x[1] = (double)__uint_as_float(r.y);
+    x[2] = (double)__uint_as_float(r.z); x[3] = (double)__uint_as_float(r.w);
+  } else if constexpr (!ROWS) {
+    x[0] = (double)bf16_bits_to_f32(r.x & 0xffffu); x[1] = (double)bf16_bits_to_f32(r.x >> 16);
+    x[2] = (double)bf16_bits_to_f32(r.y & 0xffffu); x[3] = (double)bf16_bits_to_f32(r.y >> 16);
+  } else {
+    x[0] = (double)bf16_bits_to_f32(r.x); x[1] = (double)bf16_bits_to_f32(r.y);
+    x[2] = (double)bf16_bits_to_f32(r.z); x[3] = (double)bf16_bits_to_f32(r.w);
+  }
+}
+
+// ROWS: G is stored row-major (g_rs = row pitch, g_cs = 1); otherwise g_rs = 1 and the four
+// rows of a lane are one 16-byte (fp32) or 8-byte (bf16) load, aligned because G, Y and their
+// column pitches are (the caller checks).
+template <typename E, int TC, bool ROWS>
+__global__ __launch_bounds__(512) void fa_cross_kernel(const float* __restrict__ Y, int64_t ldy,
+                                                       int m,
+                                                       const unsigned char* __restrict__ G,
+                                                       int64_t g_rs, int64_t g_cs, int p,
+                                                       int64_t n, int TMr,
+                                                       double* __restrict__ partials) {
+  // wavefronts; 16-row chunks per stage (the next stage's loads are in flight while this
+  // one is multiplied: two stages of raw bits and TC accumulators share the registers)
+  constexpr int NWV = 8, U = TC <= 2 ? 4 : TC <= 4 ? 2 : 1;
+  __shared__ double red[NWV * 256];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c16 = lane & 15, kq = lane >> 4;
-  const int ta = (int)blockIdx.y / TC, tb = (int)blockIdx.y % TC;
-  // left operand: column ca of Y; right operand: column cb of Y (tb < TMr) or of G
-  const int ca = ta * 16 + c16;
-  const bool right_is_y = tb < TMr;
-  const int cb = (right_is_y ? tb : tb - TMr) * 16 + c16;
-  const bool a_on = ca < m, b_on = right_is_y ? cb < m : cb < p;
+  const int ta = (int)blockIdx.y;            // tile row: columns 16 ta .. of Y on the left
   const unsigned char* Yb = reinterpret_cast<const unsigned char*>(Y);
-  const int64_t a_off = (int64_t)ca * ldy;
-  const int64_t b_off = right_is_y ? (int64_t)cb * ldy : (int64_t)cb * g_cs;
-  const int64_t nchunks = (n + 15) / 16;
-  const int64_t wid = (int64_t)blockIdx.x * 16 + wave, nw = (int64_t)gridDim.x * 16;
-  v4f64 acc = {0.0, 0.0, 0.0, 0.0};
-  constexpr int U = 4;                       // chunks in flight per wavefront
-  for (int64_t c0 = wid; c0 < nchunks; c0 += nw * U) {
-    double a[U][4], b[U][4];
+  const int64_t wid = (int64_t)blockIdx.x * NWV + wave, nw = (int64_t)gridDim.x * NWV;
+  v4f64 acc[TC];
+#pragma unroll
+  for (int tb = 0; tb < TC; ++tb) acc[tb] = v4f64{0.0, 0.0, 0.0, 0.0};
+
+  // operands of tile tb for the rows of one chunk, already as doubles -> TC products
+  auto multiply = [&](double (&b)[TC][4]) {
+    double a[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      a[s] = b[0][s];
+#pragma unroll
+      for (int t = 1; t < TC && t < 4; ++t) a[s] = ta == t ? b[t][s] : a[s];
+    }
+#pragma unroll
+    for (int tb = 0; tb < TC; ++tb)
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        acc[tb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[s], b[tb][s], acc[tb], 0, 0, 0);
+  };
+  auto issue = [&](int64_t group, uint4 (&raw)[U][TC]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t ch = c0 + (int64_t)u * nw;
-      const int64_t row0 = ch < nchunks ? ch * 16 + 4 * kq : n;
-      load_rows4<ElemF32>(Yb, a_off, 1, row0, n, a_on, a[u]);
-      if (right_is_y) load_rows4<ElemF32>(Yb, b_off, 1, row0, n, b_on, b[u]);
-      else load_rows4<E>(G, b_off, g_rs, row0, n, b_on, b[u]);
+      const int64_t row0 = (group * U + u) * 16 + 4 * kq;
+#pragma unroll
+      for (int tb = 0; tb < TC; ++tb) {
+        raw[u][tb] = uint4{0u, 0u, 0u, 0u};
+        if (tb < TMr) {                      // a tile of Y
+          const int col = tb * 16 + c16;
+          if (col < m) raw[u][tb] = cross_raw<ElemF32, false>(Yb, (int64_t)col * ldy, 1, row0);
+        } else {                             // a tile of G
+          const int col = (tb - TMr) * 16 + c16;
+          if (col < p) raw[u][tb] = cross_raw<E, ROWS>(G, (int64_t)col * g_cs, g_rs, row0);
+        }
+      }
     }
+  };
+  auto consume = [&](uint4 (&raw)[U][TC]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      double b[TC][4];
+#pragma unroll
+      for (int tb = 0; tb < TC; ++tb) {
+        if (tb < TMr) cross_decode<ElemF32, false>(raw[u][tb], b[tb]);
+        else cross_decode<E, ROWS>(raw[u][tb], b[tb]);
+      }
+      multiply(b);
+    }
+  };
+
+  // groups of U whole chunks, two stages in flight
+  const int64_t ngroups = (n / 16) / U;
+  uint4 cur[U][TC], nxt[U][TC];
+  int64_t g = wid;
+  if (g < ngroups) issue(g, cur);
+  while (g < ngroups) {
+    const int64_t gn = g + nw;
+    if (gn < ngroups) issue(gn, nxt);
+    consume(cur);
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
-        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u][s], b[u][s], acc, 0, 0, 0);
+      for (int tb = 0; tb < TC; ++tb) cur[u][tb] = nxt[u][tb];
+    g = gn;
   }
-  // the wavefronts add up in wave order; one partial tile per workgroup leaves the kernel
+  // what is left: fewer than U whole chunks and the ragged one, one wavefront each, with
+  // the careful loads
+  const int64_t nchunks = (n + 15) / 16;
+  const int64_t ch = ngroups * U + wid;
+  if (ch < nchunks) {
+    const int64_t row0 = ch * 16 + 4 * kq;
+    double b[TC][4];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) red[wave * 256 + r * 64 + lane] = acc[r];
-  __syncthreads();
-  double* dst = partials + ((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * 256;
-  for (int e = threadIdx.x; e < 256; e += 1024) {
-    double tot = 0.0;
+    for (int tb = 0; tb < TC; ++tb) {
+      if (tb < TMr) {
+        const int col = tb * 16 + c16;
+        load_rows4<ElemF32>(Yb, (int64_t)col * ldy, 1, row0, n, col < m, b[tb]);
+      } else {
+        const int col = (tb - TMr) * 16 + c16;
+        load_rows4<E>(G, (int64_t)col * g_cs, g_rs, row0, n, col < p, b[tb]);
+      }
+    }
+    multiply(b);
+  }
+  // the wavefronts add up in wave order; one partial tile per workgroup and result tile
 #pragma unroll
-    for (int w = 0; w < 16; ++w) tot += red[w * 256 + e];
-    dst[e] = tot;
+  for (int tb = 0; tb < TC; ++tb) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave * 256 + r * 64 + lane] = acc[tb][r];
+    __syncthreads();
+    double* dst = partials + (((int64_t)blockIdx.x * gridDim.y + ta) * TC + tb) * 256;
+    for (int e = threadIdx.x; e < 256; e += 64 * NWV) {
+      double tot = 0.0;
+#pragma unroll
+      for (int w = 0; w < NWV; ++w) tot += red[w * 256 + e];
+      dst[e] = tot;
+    }
+    __syncthreads();
   }
 }
 
@@ -1359,16 +1464,30 @@ hipError_t fa_launch_cross(const float* Y, int64_t ldy, int m, const void* G, in
                            double* Wd, hipStream_t st) {
   const int TMr = (m + 15) / 16, TC = TMr + (p + 15) / 16;
   const int64_t g_rs = layout == FA_ROW_MAJOR ? ldg : 1, g_cs = layout == FA_ROW_MAJOR ? 1 : ldg;
-  int64_t stripes = (n + 16 * 16 * 4 - 1) / (16 * 16 * 4);   // at least one pass of 4 chunks each
+  // two workgroups of eight wavefronts per compute unit of a 256-unit chip, at most
+  int64_t stripes = (n + 8 * 16 - 1) / (8 * 16);             // a chunk per wavefront at least
+  if (stripes > 512 / TMr) stripes = 512 / TMr;
   if (stripes > max_parts) stripes = max_parts;
   if (stripes < 1) stripes = 1;
-  const dim3 grid((unsigned)stripes, (unsigned)(TMr * TC));
-  if (dtype == FA_F32)
-    hipLaunchKernelGGL((fa_cross_kernel<ElemF32>), grid, dim3(1024), 0, st, Y, ldy, m,
-                       (const unsigned char*)G, g_rs, g_cs, p, n, TMr, TC, partials);
-  else
-    hipLaunchKernelGGL((fa_cross_kernel<ElemBF16>), grid, dim3(1024), 0, st, Y, ldy, m,
-                       (const unsigned char*)G, g_rs, g_cs, p, n, TMr, TC, partials);
+  const dim3 grid((unsigned)stripes, (unsigned)TMr);
+  const bool rows = layout == FA_ROW_MAJOR;
+  switch (TC) {
+#define FA_Y(E, tc, R)                                                                     \
+  hipLaunchKernelGGL((fa_cross_kernel<E, tc, R>), grid, dim3(512), 0, st, Y, ldy, m,       \
+                     (const unsigned char*)G, g_rs, g_cs, p, n, TMr, partials)
+#define FA_X(tc)                                                       \
+    case tc:                                                           \
+      if (dtype == FA_F32) {                                           \
+        if (rows) FA_Y(ElemF32, tc, true); else FA_Y(ElemF32, tc, false);   \
+      } else {                                                         \
+        if (rows) FA_Y(ElemBF16, tc, true); else FA_Y(ElemBF16, tc, false); \
+      }                                                                \
+      break;
+    FA_X(2) FA_X(3) FA_X(4) FA_X(5) FA_X(6) FA_X(7) FA_X(8)
+#undef FA_X
+#undef FA_Y
+    default: return hipErrorInvalidValue;
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int ncols = 16 * TMr + p;

@@ -832,6 +832,31 @@ def test_check_basis_of_any_matrix_and_argument_errors(agg_f32):
         agg_f32.fa_check_basis(dev, Yd[:, :-1])
     with pytest.raises(FaError):
         agg_f32.fa_check_basis(dev, torch.zeros((p + 1, n), dtype=torch.float32, device="cuda"))
+    with pytest.raises(FaError):                 # columns of Y off the 16-byte grid
+        agg_f32.fa_check_basis(dev, torch.zeros((m, n + 2), dtype=torch.float32, device="cuda")[:, :n])
+
+
+@pytest.mark.parametrize("p,m,dtype,layout", [
+    (33, 5, "f32", "worker_major"), (20, 20, "bf16", "worker_major"), (40, 17, "f32", "row_major"),
+    (64, 40, "f32", "worker_major"), (64, 64, "bf16", "worker_major"), (17, 1, "f32", "worker_major"),
+    (64, 64, "f32", "row_major"), (48, 33, "bf16", "row_major")])
+def test_check_basis_every_tile_shape(p, m, dtype, layout):
+    """Any n x m matrix as Y: every count of 16-column tiles of Y and of G, both storage types and
+    orders, a ragged number of rows; against the definition."""
+    announce("fa_check_basis tiles", p, m, dtype, layout)
+    rng = np.random.default_rng(p * 100 + m)
+    n = 9_007
+    Gw = si.random_dense(p, n, seed=p + m)
+    if dtype == "bf16":
+        Gw = (Gw.view(np.uint32) >> 16).astype(np.uint16)
+    agg = FlagAggregator(n_max=n, p_max=p, dtype=dtype, layout=layout)
+    dev = _rows_device(Gw) if layout == "row_major" else to_device(Gw)
+    Yh = rng.standard_normal((m, n)).astype(np.float32)
+    Yd = torch.from_numpy(np.ascontiguousarray(np.pad(Yh, ((0, 0), (0, 1))))).cuda()[:, :n]
+    YtY, YtG = agg.fa_check_basis(dev, Yd)
+    rYY, rYG = basis_products(as_f64_matrix(Gw), Yh.astype(np.float64).T)
+    assert np.abs(YtY - rYY).max() <= 1e-9 and np.abs(YtG - rYG).max() <= 1e-9
+    agg.close()
 
 
 # ---- workers that send several gradients (blocks of columns) -----------------------------------
