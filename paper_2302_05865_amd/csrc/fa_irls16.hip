@@ -319,9 +319,13 @@ __device__ __forceinline__ unsigned dpp_u32(unsigned x) {
 
 // Greedy diagonal-pivoted Cholesky of the PSD matrix S (16 x 16 in LDS): rows[k][j] with
 // rows^T rows = S.  Stops at max_rank rows or when the chosen remaining diagonal entry is
-// <= tol.  Executed by all 64 lanes (the four 16-lane rows do the same work).  The pivot is
-// the largest remaining diagonal entry as seen in fp32 (any near-largest pivot serves; ties go
-// to the lowest index).  The loops are kept rolled on purpose: this code runs once per call,
+// <= tol.  Right-looking, on the matrix core: S is kept in the accumulator's register order
+// (entry r of lane (q, c) = element (4r + q, c)); the pivot row pv = 4 r' + q' is then entry r'
+// of the sixteen lanes (q', c), which is also where a matrix instruction takes column k = q' of
+// its A operand and row k = q' of its B operand from - so with that row, scaled, in those lanes
+// and zero in the others one instruction subtracts the rank-one term from all of S.  The pivot
+// is the largest remaining diagonal entry as seen in fp32 (any near-largest pivot serves; ties
+// go to the lowest index).  The loop is kept rolled on purpose: this code runs once per call,
 // and straight-line code that is executed once costs more in instruction fetch than it
 // saves.  It must be inlined: as a called function it slowed the whole solver by 10 %.
 // Returns the number of rows; piv[k] is the column chosen at step k, rinv[k] = 1/rows[k][piv[k]].
@@ -330,43 +334,46 @@ __device__ __forceinline__ unsigned dpp_u32(unsigned x) {
 #endif
 __device__ FA_CHOL_ATTR int pivoted_cholesky(const double* S, double* rows, int* piv, double* rinv,
                                              double tol, int max_rank, int lane) {
-  const int j = lane & 15;
-  double d = S[j * LDF + j];
-  bool used = false;
+  const int c16 = lane & 15, q4 = lane >> 4;
+  v4d s;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) s[r] = S[(4 * r + q4) * LDF + c16];
+  // element (c, c) is entry c / 4 of the lane (c % 4, c)
+  const bool hasd = (c16 & 3) == q4;
+  const int rd = c16 >> 2;
   int rank = 0;
 #pragma unroll 1
   for (int k = 0; k < max_rank; ++k) {
-    const float df = (!used && d > 0.0) ? (float)d : 0.0f;
-    unsigned key = (__float_as_uint(df) & ~15u) | (unsigned)(15 - j);
+    const double d = rd == 0 ? s[0] : rd == 1 ? s[1] : rd == 2 ? s[2] : s[3];
+    const float df = (hasd && d > 0.0) ? (float)d : 0.0f;
+    unsigned key = hasd ? ((__float_as_uint(df) & ~15u) | (unsigned)(15 - c16)) : 0u;
     key = max(key, dpp_u32<0x128>(key));   // row_ror:8
     key = max(key, dpp_u32<0x124>(key));   // row_ror:4
     key = max(key, dpp_u32<0x122>(key));   // row_ror:2
     key = max(key, dpp_u32<0x121>(key));   // row_ror:1
-    const int pv = 15 - (int)(__builtin_amdgcn_readfirstlane((int)key) & 15);
-    const double dpv = lane_bcast(used ? -1.0 : d, pv);
-    if (!(dpv > tol)) break;
-    double a0 = S[pv * LDF + j], a1 = 0.0;
-    int a = 0;
-#pragma unroll 1
-    for (; a + 1 < k; a += 2) {
-      a0 = fma(-rows[a * LDF + pv], rows[a * LDF + j], a0);
-      a1 = fma(-rows[(a + 1) * LDF + pv], rows[(a + 1) * LDF + j], a1);
-    }
-    if (a < k) a0 = fma(-rows[a * LDF + pv], rows[a * LDF + j], a0);
-    const double acc = a0 + a1;
-    const double dp = lane_bcast(acc, pv);           // recomputed pivot value S_k[pv][pv]
-    if (!(dp > 0.0)) break;
+    const unsigned k0 = (unsigned)__builtin_amdgcn_readlane((int)key, 0);
+    const unsigned k1 = (unsigned)__builtin_amdgcn_readlane((int)key, 16);
+    const unsigned k2 = (unsigned)__builtin_amdgcn_readlane((int)key, 32);
+    const unsigned k3 = (unsigned)__builtin_amdgcn_readlane((int)key, 48);
+    const int pv = 15 - (int)(max(max(k0, k1), max(k2, k3)) & 15u);
+    const int qp = pv & 3, rp = pv >> 2;
+    // row pv of what is left of S, in the lanes (qp, c); its diagonal entry is in lane (qp, pv)
+    const double rowv = rp == 0 ? s[0] : rp == 1 ? s[1] : rp == 2 ? s[2] : s[3];
+    const double dp = lane_bcast(rowv, 16 * qp + pv);
+    if (!(dp > tol)) break;
     const double rs = rsq_nr<2>(dp);
-    const double rk = used ? 0.0 : acc * rs;
-    if (lane < 16) rows[k * LDF + j] = rk;
+    const double a = q4 == qp ? rowv * rs : 0.0;
+    if (q4 == qp) rows[k * LDF + c16] = a;
     if (lane == 0) { piv[k] = pv; rinv[k] = rs; }
-    d = fma(-rk, rk, d);
-    if (j == pv) used = true;
+    s = __builtin_amdgcn_mfma_f64_16x16x4f64(-a, a, s, 0, 0, 0);
+    // row and column pv are done with (what the update leaves there is rounding noise)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s[r] = (c16 == pv || (q4 == qp && rp == r)) ? 0.0 : s[r];
     rank = k + 1;
-    wave_fence();
   }
+  wave_fence();
   for (int k = rank; k < 16; ++k) {
-    if (lane < 16) rows[k * LDF + j] = 0.0;
+    if (lane < 16) rows[k * LDF + c16] = 0.0;
     if (lane == 0) { piv[k] = 0; rinv[k] = 0.0; }
   }
   wave_fence();
