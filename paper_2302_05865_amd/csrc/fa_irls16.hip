@@ -284,6 +284,19 @@ __device__ __forceinline__ double lane_bcast(double x, int srclane) {
   const int hi = __builtin_amdgcn_readlane(__double2hiint(x), srclane);
   return __hiloint2double(hi, lo);
 }
+// Sum over the four lanes c, 16 + c, 32 + c, 48 + c, in every one of them: (t0 + t1) + (t2 + t3).
+// v_permlane16_swap / v_permlane32_swap with both operands the same value return the even rows
+// (the lower half) and the odd rows (the upper half) side by side.
+__device__ __forceinline__ double rows_sum(double t) {
+  int lo = __double2loint(t), hi = __double2hiint(t);
+  auto a = __builtin_amdgcn_permlane16_swap((unsigned)lo, (unsigned)lo, false, false);
+  auto b = __builtin_amdgcn_permlane16_swap((unsigned)hi, (unsigned)hi, false, false);
+  const double s = __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+  lo = __double2loint(s); hi = __double2hiint(s);
+  a = __builtin_amdgcn_permlane32_swap((unsigned)lo, (unsigned)lo, false, false);
+  b = __builtin_amdgcn_permlane32_swap((unsigned)hi, (unsigned)hi, false, false);
+  return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+}
 // deterministic sum over the wavefront, same value in every lane
 __device__ __forceinline__ double wave_sum(double x) {
   x = row_sum(x);
@@ -523,12 +536,12 @@ __device__ int solve(const double* __restrict__ Kg, int p, int m, int iters, dou
   int iters_done = 0, steps = 0;
   for (int it = 0; it < iters; ++it) {
     // C = diag(w/s) + Laplacian of the pair part;  M = R C R^T via W = C R^T, M = R W
+    // (the pair part is symmetric, bit for bit: the sum of row j is the sum of column j, which
+    // is spread over the four lanes that hold column j)
     v4d c;
+    const double csum = rows_sum((cp[0] + cp[1]) + (cp[2] + cp[3]));
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const double rs = row_sum(cp[r]);
-      c[r] = isdiag[r] ? wj * dj * dj - rs : cp[r];
-    }
+    for (int r = 0; r < 4; ++r) c[r] = isdiag[r] ? wj * dj * dj - csum : cp[r];
     const v4d wmat = mm16(c, ra);
     mk = mm16(ra, wmat);
     if (mm < rank) {
