@@ -1081,6 +1081,28 @@ def test_two_contexts_on_two_streams_give_the_results_of_the_sequence(name, n):
             a.close()
 
 
+# ---- degenerate shapes -----------------------------------------------------------------------------
+@pytest.mark.parametrize("p,n,m", [(15, 5, 8), (15, 5, 3), (7, 1, 4), (7, 2, 1), (40, 9, 20),
+                                   (40, 9, 4), (64, 3, 32), (2, 1, 1), (1, 10, 1), (1, 1, 1),
+                                   (16, 16, 8), (17, 16, 9), (33, 31, 32)])
+def test_fewer_coordinates_than_workers(p, n, m):
+    """n < p (the rank is n), n = p, a single worker, a single coordinate: against the oracle,
+    with and without the pairwise term."""
+    announce("tiny shape", p, n, m)
+    rng = np.random.default_rng(1000 * p + n)
+    for lam in (0.0, 1.0):
+        G = rng.standard_normal((p, n)).astype(np.float32)
+        ref = fa_scaled(G, m, lam, 6, 0.0)
+        agg = FlagAggregator(n_max=n, p_max=p)
+        out = agg.fa_aggregate(to_device(G), m, lam, 6, 0.0).cpu().numpy().astype(np.float64)
+        info = agg.fa_get_info()
+        agg.close()
+        assert info.status == 0 and info.rank == min(p, n)
+        assert rel_l2(out, ref["out"]) <= GATE
+        # (where Y spans all of G the terms are square roots of rounding noise: 1e-8 each)
+        assert np.allclose(info.objective[:6], ref["objective"][:6], atol=1e-5)
+
+
 # ---- the enqueue-only entry points inside a HIP graph ------------------------------------------
 @pytest.mark.parametrize("name,n,entry", [("cfg2", 300_007, "aggregate"),
                                           ("cfg4", 200_003, "aggregate"),
