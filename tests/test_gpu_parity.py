@@ -1103,6 +1103,34 @@ def test_fewer_coordinates_than_workers(p, n, m):
         assert np.allclose(info.objective[:6], ref["objective"][:6], atol=1e-5)
 
 
+@pytest.mark.parametrize("p,n,m", [(15, 20_011, 8), (32, 9_001, 16), (64, 5_003, 32)])
+def test_extreme_scales_and_parameters(p, n, m):
+    """Workers whose norms spread over twelve orders of magnitude or sit at 1e18 / 1e-18, a huge
+    and a vanishing lambda, the largest solve count, m = 1 and m = p, identical gradients:
+    against the oracle."""
+    announce("extremes", p, n, m)
+    rng = np.random.default_rng(11 + p)
+    mu = rng.standard_normal(n)
+    base = mu[None, :] + 0.5 * rng.standard_normal((p, n))
+    same = base.copy()
+    same[1:] = same[0]
+    cases = [("spread", base * (10.0 ** rng.uniform(-6, 6, p))[:, None], m, 1.0, 10),
+             ("1e18", base * 1e18, m, 1.0, 10), ("1e-18", base * 1e-18, m, 1.0, 10),
+             ("lambda 1e6", base, m, 1e6, 10), ("lambda 1e-9", base, m, 1e-9, 10),
+             ("64 solves", base, m, 1.0, 64), ("m = p", base, p, 1.0, 5), ("m = 1", base, 1, 1.0, 12),
+             ("identical", same, m, 1.0, 5)]
+    agg = FlagAggregator(n_max=n, p_max=p)
+    for tag, G64, mm, lam, iters in cases:
+        G = G64.astype(np.float32)
+        ref = fa_scaled(G, mm, lam, iters, 0.0)
+        out = agg.fa_aggregate(to_device(G), mm, lam, iters, 0.0).cpu().numpy().astype(np.float64)
+        info = agg.fa_get_info()
+        assert info.status == 0, tag
+        assert rel_l2(out, ref["out"]) <= GATE, tag
+        assert projector_difference(info.A, ref["A"], ref["R"]) <= GATE, tag
+    agg.close()
+
+
 # ---- the enqueue-only entry points inside a HIP graph ------------------------------------------
 @pytest.mark.parametrize("name,n,entry", [("cfg2", 300_007, "aggregate"),
                                           ("cfg4", 200_003, "aggregate"),
