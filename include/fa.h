@@ -73,8 +73,11 @@ typedef enum { FA_SOLVER_AUTO = 0, FA_SOLVER_JACOBI16 = 1, FA_SOLVER_JACOBI = 2 
  *   core -- exact products of bf16 values (fp32 values are split exactly into three bf16
  *   pieces), 32 rows summed in fp32 by one matrix instruction, every such partial added in
  *   fp64.  K good to 2^-21 of sqrt(K_ii K_jj) at worst and to a few 1e-9 from a few thousand
- *   rows on (measured).  Needs |g| below about 1e18 (32-row sums of products must be finite in
- *   fp32).  Cases the kernel does not cover (fp32 storage at p <= 16, row-major) take the
+ *   rows on (measured).  Its 32-row sums of products are fp32 and overflow for values beyond
+ *   about 1e18; the fp64 pass therefore stands by behind it (always enqueued, returns at once
+ *   unless K came out non-finite) and redoes K in that case, so finite input of any size is
+ *   served, at the price of a second pass; products below about 1e-38 count as zero on this
+ *   route.  Cases the kernel does not cover (fp32 storage at p <= 16, row-major) take the
  *   fp64 route.
  * FA_GRAM_AUTO: FA_GRAM_BF16_MATRIX from FA_GRAM_AUTO_MIN_ROWS rows on, where the pass is a
  *   visible share of the aggregation and the few 1e-9 stay well inside the parity gate;
@@ -322,6 +325,9 @@ fa_status fa_check_basis(fa_ctx* ctx, const void* G, int64_t ldg, int p, int64_t
  * ms[2] p x p IRLS, ms[3] aggregate pass.  For 16 < p <= 64 the p x p part is two launches (the
  * matrix-core solver, then the Jacobi kernel that redoes a solve the first gave up and
  * otherwise returns at once); ms[2] runs from the begin of the first to the end of the second.
+ * Where the Gram pass runs on the bf16 matrix core, ms[0] and ms[1] are that pass and its
+ * reduction; the fp64 pass standing by behind them (three launches that return at once unless
+ * the first overflowed) is not in any of the four figures.
  */
 fa_status fa_set_profiling(fa_ctx* ctx, int enabled);
 fa_status fa_get_timings(fa_ctx* ctx, float ms[4]);

@@ -29,6 +29,7 @@ struct fa_ctx {
   fa_resume* rs_d;    // IRLS state of the re-streaming schedule
   double* Pd;         // streamed projections, FA_P_MAX^2
   int* sizes_d;       // FA_P_MAX: block widths of fa_aggregate_grouped
+  int* flag_d;        // "the matrix-core Gram pass overflowed" (read by its fp64 stand-by)
   double* check_h;    // pinned host staging of fa_check_basis: FA_P_MAX * 2 FA_P_MAX doubles
   fa_ktime tm[4];     // per-kernel begin/end events (profiling)
   fa_ktime tm_r[2];   // re-streaming schedule: weighted Gram pass and projection pass of the
@@ -113,6 +114,7 @@ extern "C" fa_status fa_create(const fa_config* cfg, fa_ctx** out_ctx) {
   ok = ok && hipMalloc((void**)&c->rs_d, sizeof(fa_resume)) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->Pd, sizeof(double) * FA_P_MAX * FA_P_MAX) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->sizes_d, sizeof(int) * FA_P_MAX) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->flag_d, 64) == hipSuccess;
   ok = ok && hipHostMalloc((void**)&c->check_h, sizeof(double) * FA_P_MAX * 2 * FA_P_MAX,
                            hipHostMallocDefault) == hipSuccess;
   if (!ok) { fa_destroy(c); return FA_ERR_ALLOC; }
@@ -144,6 +146,7 @@ extern "C" void fa_destroy(fa_ctx* c) {
   if (c->rs_d) (void)hipFree(c->rs_d);
   if (c->Pd) (void)hipFree(c->Pd);
   if (c->sizes_d) (void)hipFree(c->sizes_d);
+  if (c->flag_d) (void)hipFree(c->flag_d);
   if (c->check_h) (void)hipHostFree(c->check_h);
   for (int i = 0; i < 4; ++i) {
     if (c->tm[i].start) (void)hipEventDestroy(c->tm[i].start);
@@ -197,11 +200,9 @@ extern "C" fa_status fa_aggregate(fa_ctx* c, const void* G, int64_t ldg, int p, 
   c->ev_recorded = 0;
   // S1: norms and Gram matrix, per-workgroup partials;  S2: their fixed-order sum
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
-                              &nparts, st, prof ? &c->tm[0] : nullptr) != hipSuccess)
-    return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, nullptr, st, prof ? &c->tm[1] : nullptr) !=
-      hipSuccess)
+  if (fa_launch_gram(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks,
+                     c->partials, c->Kd, c->flag_d, &nparts, st, prof ? &c->tm[0] : nullptr,
+                     prof ? &c->tm[1] : nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   // S3-S5: p x p IRLS and coefficients
   if (fa_launch_irls(c->Kd, p, m, lambda, iters, tol, c->cfg.clamp_delta, c->cfg.rank_tol,
@@ -234,7 +235,8 @@ constexpr size_t kOffK = kOffPartials + sizeof(double) * kStaticBlocks * kStatic
 constexpr size_t kOffC = kOffK + sizeof(double) * FA_P_MAX * FA_P_MAX;
 constexpr size_t kOffGws = kOffC + sizeof(double) * (FA_P_MAX + 8);
 constexpr size_t kOffInfo = kOffGws + sizeof(double) * FA_GWS_DOUBLES;
-constexpr size_t kStaticUsed = kOffInfo + sizeof(fa_info);
+constexpr size_t kOffFlag = kOffInfo + ((sizeof(fa_info) + 63) / 64) * 64;
+constexpr size_t kStaticUsed = kOffFlag + 64;
 static_assert(kStaticUsed <= FA_STATIC_SCRATCH_BYTES, "the static workspace is too small");
 static_assert(kOffK % 256 == 0 && kOffC % 8 == 0 && kOffGws % 8 == 0 && kOffInfo % 8 == 0,
               "alignment of the parts of the static workspace");
@@ -308,10 +310,9 @@ extern "C" fa_status fa_aggregate_static(const void* G, int64_t ldg, int p, int6
   hipLaunchKernelGGL(fa_static_clear_kernel, dim3(1), dim3(64), 0, st, info_d);
   if (hipGetLastError() != hipSuccess) return FA_ERR_DEVICE;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, dtype, FA_WORKER_MAJOR, cfg.gram, sd.blocks, partials,
-                              &nparts, st, nullptr) != hipSuccess)
-    return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(partials, nparts, p, Kd, nullptr, st, nullptr) != hipSuccess)
+  int* flag_d = reinterpret_cast<int*>(sd.base + kOffFlag);
+  if (fa_launch_gram(G, ldg, p, n, dtype, FA_WORKER_MAJOR, cfg.gram, sd.blocks, partials, Kd,
+                     flag_d, &nparts, st, nullptr, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls(Kd, p, m, lambda, iters, tol, cfg.clamp_delta, cfg.rank_tol, cfg.pair_tol,
                      cfg.exponent_a, cd, info_d, gws, cfg.solver, cfg.wide_spin_budget, nullptr,
@@ -429,10 +430,9 @@ extern "C" fa_status fa_gram(fa_ctx* c, const void* G, int64_t ldg, int p, int64
                              double* K_host) {
   if (!check_matrix_args(c, G, ldg, p, n) || !K_host) return FA_ERR_ARG;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
-                              &nparts, c->stream, nullptr) != hipSuccess)
-    return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, nullptr, c->stream, nullptr) != hipSuccess)
+  if (fa_launch_gram(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks,
+                     c->partials, c->Kd, c->flag_d, &nparts, c->stream, nullptr, nullptr) !=
+      hipSuccess)
     return FA_ERR_DEVICE;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return FA_ERR_DEVICE;
   if (hipMemcpy(K_host, c->Kd, sizeof(double) * p * p, hipMemcpyDeviceToHost) != hipSuccess)
@@ -514,10 +514,9 @@ extern "C" fa_status fa_aggregate_arrived(fa_ctx* c, const void* G, int64_t ldg,
 extern "C" fa_status fa_gram_async(fa_ctx* c, const void* G, int64_t ldg, int p, int64_t n) {
   if (!check_matrix_args(c, G, ldg, p, n)) return FA_ERR_ARG;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks, c->partials,
-                              &nparts, c->stream, nullptr) != hipSuccess)
-    return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, nullptr, c->stream, nullptr) != hipSuccess)
+  if (fa_launch_gram(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks,
+                     c->partials, c->Kd, c->flag_d, &nparts, c->stream, nullptr, nullptr) !=
+      hipSuccess)
     return FA_ERR_DEVICE;
   return FA_OK;
 }
@@ -587,10 +586,8 @@ extern "C" fa_status fa_aggregate_grouped(fa_ctx* c, const void* G, int64_t ldg,
       hipSuccess)
     return FA_ERR_DEVICE;
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, q, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram,
-                              c->gram_max_blocks, c->partials, &nparts, st, nullptr) != hipSuccess)
-    return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, q, c->Kd, nullptr, st, nullptr) != hipSuccess)
+  if (fa_launch_gram(G, ldg, q, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks,
+                     c->partials, c->Kd, c->flag_d, &nparts, st, nullptr, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   if (fa_launch_irls_grouped(c->Kd, q, nworkers, c->sizes_d, m, lambda, iters, tol,
                              c->cfg.clamp_delta, c->cfg.rank_tol, c->cfg.pair_tol,
@@ -618,10 +615,8 @@ extern "C" fa_status fa_multikrum(fa_ctx* c, const void* G, int64_t ldg, int p, 
   c->ev_recorded = 0;
   c->has_solution = 0;                       // no basis belongs to this result
   int nparts = 0;
-  if (fa_launch_gram_partials(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram,
-                              c->gram_max_blocks, c->partials, &nparts, st, nullptr) != hipSuccess)
-    return FA_ERR_DEVICE;
-  if (fa_launch_gram_reduce(c->partials, nparts, p, c->Kd, nullptr, st, nullptr) != hipSuccess)
+  if (fa_launch_gram(G, ldg, p, n, c->cfg.dtype, c->cfg.layout, c->cfg.gram, c->gram_max_blocks,
+                     c->partials, c->Kd, c->flag_d, &nparts, st, nullptr, nullptr) != hipSuccess)
     return FA_ERR_DEVICE;
   // scores in the solvers' workspace, the selection in the block-width buffer
   if (fa_launch_krum(c->Kd, p, f, q, c->cd, c->gws, c->sizes_d, st) != hipSuccess)

@@ -33,9 +33,19 @@ typedef struct { hipEvent_t start, stop; } fa_ktime;
 // the row pitch in elements, p <= ldg <= 16 ceil(p/16)).  gram_mode: fa_gram_mode
 // (FA_GRAM_BF16_MATRIX, and FA_GRAM_AUTO from FA_GRAM_AUTO_MIN_ROWS rows on, hand the cases of
 // fa_gram_lp_applies to the bf16 matrix-core kernel).
+// gate (device, may be null): the pass does nothing unless *gate != 0 (fp64 kernel only).
 hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
                                    int layout, int gram_mode, int max_blocks, double* partials,
-                                   int* nparts, hipStream_t st, const fa_ktime* tm);
+                                   int* nparts, hipStream_t st, const fa_ktime* tm,
+                                   const int* gate = nullptr);
+// whether that call hands the pass to the bf16 matrix-core kernel
+bool fa_gram_takes_matrix_core(int p, int64_t n, int dtype, int layout, int gram_mode);
+// K1 + K2 into Kd, with the fp64 pass standing by behind a matrix-core pass in case its fp32
+// sums overflowed (flag_d: one int of device scratch; see fa_kernels.hip).
+hipError_t fa_launch_gram(const void* G, int64_t ldg, int p, int64_t n, int dtype, int layout,
+                          int gram_mode, int max_blocks, double* partials, double* Kd,
+                          int* flag_d, int* nparts, hipStream_t st, const fa_ktime* tm_gram,
+                          const fa_ktime* tm_reduce);
 // K1 on the bf16 matrix core (fa_gram_lp.hip): same partials, for worker-major G without
 // column scales, where fa_gram_lp_applies (bf16 storage, or fp32 storage at p > 16).
 bool fa_gram_lp_applies(int p, int dtype);
@@ -56,7 +66,8 @@ hipError_t fa_launch_zero(double* dst, int count, hipStream_t st);
 // may be null): entry (i, j) is multiplied by colscale[i] colscale[j], i.e. the result is
 // diag(u) K diag(u), the Gram matrix of the columns scaled by u.
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
-                                 const double* colscale, hipStream_t st, const fa_ktime* tm);
+                                 const double* colscale, hipStream_t st, const fa_ktime* tm,
+                                 const int* gate = nullptr);
 
 // K3: p x p solver.  Kd p*p doubles; cd p doubles out; info_d device fa_info; gws global
 // workspace of FA_GWS_DOUBLES doubles.  solver: 0 = default (matrix-core purification, with

@@ -161,7 +161,10 @@ __global__ __launch_bounds__(64 * WAVES) void fa_gram_kernel(
                                                      const unsigned char* __restrict__ G,
                                                      int64_t ldg, int p, int64_t n,
                                                      int64_t ntiles,
-                                                     double* __restrict__ partials) {
+                                                     double* __restrict__ partials,
+                                                     const int* __restrict__ gate) {
+  // as the stand-by of the bf16 matrix-core pass: nothing to do unless that one overflowed
+  if (gate != nullptr && *gate == 0) return;
   constexpr int EPL = E::EPL;
   constexpr int LPC = 64 / CPL;            // lanes per column in one load instruction
   constexpr int R = LPC * EPL;             // rows per tile
@@ -635,7 +638,9 @@ __global__ __launch_bounds__(1024) void fa_gram_reduce_kernel(const double* __re
                                                               int nparts, int T, int p,
                                                               double* __restrict__ K, int TM,
                                                               int m,
-                                                              const double* __restrict__ colscale) {
+                                                              const double* __restrict__ colscale,
+                                                              const int* __restrict__ gate) {
+  if (gate != nullptr && *gate == 0) return;   // stand-by of a pass that did not need it
   const int NTP = TM > 0 ? T * TM : T * (T + 1) / 2;
   const int ei = threadIdx.x & 63, g = threadIdx.x >> 6;   // entry, strand 0..15
   const int E = blockIdx.x * 64 + ei;                      // entry in [0, NTP*256)
@@ -1376,7 +1381,7 @@ size_t fa_irls_lds_bytes(int p, int* big_in_global) {
 template <int T, int CPL, typename E, int WAVES, bool ROWS>
 static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
                                 double* partials, int* nparts, hipStream_t st,
-                                const fa_ktime* tm) {
+                                const fa_ktime* tm, const int* gate) {
   static_assert(WAVES <= FA_GRAM_WAVES_PER_CU, "partials buffer is sized for this many");
   constexpr int R = (64 / CPL) * E::EPL;
   constexpr int CS = R * E::SIZE + 16;
@@ -1390,7 +1395,7 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
   *nparts = (int)wgs;
   FA_LAUNCH(tm, (fa_gram_kernel<T, CPL, E, WAVES, ROWS>), dim3((unsigned)wgs),
             dim3(64 * WAVES), lds_bytes, st, (const unsigned char*)G, ldg, p, n, ntiles,
-            partials);
+            partials, gate);
   return hipGetLastError();
 }
 
@@ -1401,11 +1406,11 @@ static hipError_t launch_gram_t(const void* G, int64_t ldg, int p, int64_t n, in
 template <typename E, bool ROWS>
 static hipError_t launch_gram_e(const void* G, int64_t ldg, int p, int64_t n, int max_blocks,
                                 double* partials, int* nparts, hipStream_t st,
-                                const fa_ktime* tm) {
+                                const fa_ktime* tm, const int* gate) {
   switch ((p + 15) / 16) {
 #define FA_X(t, cpl, w)                                                                        \
     case t: return launch_gram_t<t, cpl, E, w, ROWS>(G, ldg, p, n, max_blocks, partials, nparts, \
-                                                     st, tm);
+                                                     st, tm, gate);
     FA_GRAM_TILINGS(FA_X)
 #undef FA_X
   }
@@ -1425,35 +1430,75 @@ static hipError_t prepare_gram_e() {
   return e;
 }
 
-hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
-                                   int layout, int gram_mode, int max_blocks, double* partials,
-                                   int* nparts, hipStream_t st, const fa_ktime* tm) {
+bool fa_gram_takes_matrix_core(int p, int64_t n, int dtype, int layout, int gram_mode) {
   const bool want_lp = gram_mode == FA_GRAM_BF16_MATRIX ||
                        (gram_mode == FA_GRAM_AUTO && n >= FA_GRAM_AUTO_MIN_ROWS);
-  if (want_lp && layout == FA_WORKER_MAJOR && fa_gram_lp_applies(p, dtype))
+  return want_lp && layout == FA_WORKER_MAJOR && fa_gram_lp_applies(p, dtype);
+}
+
+hipError_t fa_launch_gram_partials(const void* G, int64_t ldg, int p, int64_t n, int dtype,
+                                   int layout, int gram_mode, int max_blocks, double* partials,
+                                   int* nparts, hipStream_t st, const fa_ktime* tm,
+                                   const int* gate) {
+  if (fa_gram_takes_matrix_core(p, n, dtype, layout, gram_mode))
     return fa_launch_gram_lp_partials(G, ldg, p, n, dtype, max_blocks, partials, nparts, st, tm);
   const bool rows = layout == FA_ROW_MAJOR;
   if (dtype == FA_F32)
-    return rows ? launch_gram_e<ElemF32, true>(G, ldg, p, n, max_blocks, partials, nparts, st, tm)
-                : launch_gram_e<ElemF32, false>(G, ldg, p, n, max_blocks, partials, nparts, st, tm);
-  return rows ? launch_gram_e<ElemBF16, true>(G, ldg, p, n, max_blocks, partials, nparts, st, tm)
-              : launch_gram_e<ElemBF16, false>(G, ldg, p, n, max_blocks, partials, nparts, st, tm);
+    return rows ? launch_gram_e<ElemF32, true>(G, ldg, p, n, max_blocks, partials, nparts, st, tm, gate)
+                : launch_gram_e<ElemF32, false>(G, ldg, p, n, max_blocks, partials, nparts, st, tm, gate);
+  return rows ? launch_gram_e<ElemBF16, true>(G, ldg, p, n, max_blocks, partials, nparts, st, tm, gate)
+              : launch_gram_e<ElemBF16, false>(G, ldg, p, n, max_blocks, partials, nparts, st, tm, gate);
 }
 
 hipError_t fa_launch_gram_reduce(const double* partials, int nparts, int p, double* Kd,
-                                 const double* colscale, hipStream_t st, const fa_ktime* tm) {
+                                 const double* colscale, hipStream_t st, const fa_ktime* tm,
+                                 const int* gate) {
   const int T = (p + 15) / 16;
   const int NTP = T * (T + 1) / 2;
   FA_LAUNCH(tm, fa_gram_reduce_kernel, dim3(NTP * 4), dim3(1024), 0, st, partials, nparts, T, p,
-            Kd, 0, 0, colscale);
+            Kd, 0, 0, colscale, gate);
   return hipGetLastError();
+}
+
+// *flag = 1 if any of the count doubles at K is NaN or infinite, else 0
+__global__ __launch_bounds__(256) void fa_nonfinite_flag_kernel(const double* __restrict__ K,
+                                                                int count, int* __restrict__ flag) {
+  bool bad = false;
+  for (int k = threadIdx.x; k < count; k += 256) bad = bad || !(fabs(K[k]) <= 1.79e308);
+  const int any = __syncthreads_or(bad ? 1 : 0);
+  if (threadIdx.x == 0) *flag = any ? 1 : 0;
+}
+
+// K1 + K2: K = G^T G into Kd.  Where the pass runs on the bf16 matrix core, whose 32-row sums
+// are fp32 and overflow for values beyond ~1e18, the fp64 pass stands by behind it: it is
+// always enqueued and returns at once unless K came out non-finite (flag_d: one int of device
+// scratch), so that large finite values - a Byzantine worker may send anything - cost a second
+// pass instead of the result.  tm_gram / tm_reduce time the first pass and its reduction.
+hipError_t fa_launch_gram(const void* G, int64_t ldg, int p, int64_t n, int dtype, int layout,
+                          int gram_mode, int max_blocks, double* partials, double* Kd,
+                          int* flag_d, int* nparts, hipStream_t st, const fa_ktime* tm_gram,
+                          const fa_ktime* tm_reduce) {
+  hipError_t e = fa_launch_gram_partials(G, ldg, p, n, dtype, layout, gram_mode, max_blocks,
+                                         partials, nparts, st, tm_gram, nullptr);
+  if (e != hipSuccess) return e;
+  e = fa_launch_gram_reduce(partials, *nparts, p, Kd, nullptr, st, tm_reduce, nullptr);
+  if (e != hipSuccess || !fa_gram_takes_matrix_core(p, n, dtype, layout, gram_mode)) return e;
+  hipLaunchKernelGGL(fa_nonfinite_flag_kernel, dim3(1), dim3(256), 0, st, (const double*)Kd, p * p,
+                     flag_d);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  int np2 = 0;
+  e = fa_launch_gram_partials(G, ldg, p, n, dtype, layout, FA_GRAM_FP64, max_blocks, partials, &np2,
+                              st, nullptr, flag_d);
+  if (e != hipSuccess) return e;
+  return fa_launch_gram_reduce(partials, np2, p, Kd, nullptr, st, nullptr, flag_d);
 }
 
 hipError_t fa_launch_proj_reduce(const double* partials, int nparts, int p, int m, double* Td,
                                  hipStream_t st, const fa_ktime* tm) {
   const int T = (p + 15) / 16, TM = (m + 15) / 16;
   FA_LAUNCH(tm, fa_gram_reduce_kernel, dim3(T * TM * 4), dim3(1024), 0, st, partials, nparts, T,
-            p, Td, TM, m, (const double*)nullptr);
+            p, Td, TM, m, (const double*)nullptr, (const int*)nullptr);
   return hipGetLastError();
 }
 
@@ -1493,7 +1538,7 @@ hipError_t fa_launch_cross(const float* Y, int64_t ldy, int m, const void* G, in
   const int ncols = 16 * TMr + p;
   hipLaunchKernelGGL(fa_gram_reduce_kernel, dim3(TMr * TC * 4), dim3(1024), 0, st,
                      (const double*)partials, (int)stripes, TMr, m, Wd, TC, ncols,
-                     (const double*)nullptr);
+                     (const double*)nullptr, (const int*)nullptr);
   return hipGetLastError();
 }
 

@@ -1131,6 +1131,42 @@ def test_extreme_scales_and_parameters(p, n, m):
     agg.close()
 
 
+@pytest.mark.parametrize("p,n,dtype,gram", [(32, 9_001, "f32", "bf16"), (64, 4_003, "f32", "bf16"),
+                                            (15, 20_011, "bf16", "bf16"), (32, 9_001, "bf16", "bf16"),
+                                            (32, (1 << 20) + 5, "bf16", "auto")])
+def test_values_beyond_the_matrix_core_range_take_the_fp64_pass(p, n, dtype, gram):
+    """A worker may send anything: values of 1e25 (finite in fp32 and in bf16) overflow the fp32
+    sums of the bf16 matrix-core Gram pass; the fp64 pass standing by behind it redoes K, and
+    the aggregate is the oracle's.  The same context then takes an ordinary input on the
+    matrix-core route again."""
+    announce("beyond the matrix-core range", p, n, dtype, gram)
+    rng = np.random.default_rng(5 * p)
+    mu = rng.standard_normal(n)
+    G = (mu[None, :] + 0.5 * rng.standard_normal((p, n))).astype(np.float32)
+    big = G.copy()
+    big[3] = (1e25 * rng.standard_normal(n)).astype(np.float32)
+    big[p - 1] *= np.float32(3e20)
+    m, lam, iters = (p + 1) // 2, 1.0, 6
+    agg = FlagAggregator(n_max=n, p_max=p, dtype=dtype, gram=gram)
+    fp64 = FlagAggregator(n_max=n, p_max=p, dtype=dtype, gram="fp64")
+    for Gf in (big, G, big):
+        Gw = si.f32_to_bf16_bits(Gf.reshape(-1)).reshape(p, n) if dtype == "bf16" else Gf
+        dev = to_device(Gw)
+        ref = fa_scaled(Gw, m, lam, iters, 0.0)
+        out = agg.fa_aggregate(dev, m, lam, iters, 0.0).cpu().numpy().astype(np.float64)
+        info = agg.fa_get_info()
+        assert info.status == 0
+        assert rel_l2(out, ref["out"]) <= GATE
+        if Gf is big:
+            assert np.allclose(info.v, ref["v"], atol=1e-5)
+            # the stand-by's K is the fp64 route's, bit for bit
+            out64 = fp64.fa_aggregate(dev, m, lam, iters, 0.0)
+            assert np.array_equal(info.K, fp64.fa_get_info().K)
+            assert np.array_equal(out, out64.cpu().numpy().astype(np.float64))
+    agg.close()
+    fp64.close()
+
+
 # ---- the enqueue-only entry points inside a HIP graph ------------------------------------------
 @pytest.mark.parametrize("name,n,entry", [("cfg2", 300_007, "aggregate"),
                                           ("cfg4", 200_003, "aggregate"),
